@@ -1,0 +1,265 @@
+"""Pins for the oracle's layer and for the selective-prefill semantics.
+
+The whole decoder layer is checked against an independent Llama implementation (the
+`transformers` CPU model in float64, same weights): hidden state entering every layer and
+the K/V cache of every layer.  The selective semantics are checked through the degenerate
+cases the paper names as baselines (full prefill, full reuse: Sec. 5.1) and through
+invariants that hold for any correct implementation."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dsk_oracle as O
+from paper_2411_02820_amd import synth
+from tests.helpers import kv_list, oracle_config, weights_fn
+
+SHAPE = synth.ModelShape(n_layers=4, hidden=48, n_q_heads=4, n_kv_heads=2, head_dim=16, ffn=80,
+                         rope_base=10000.0, rms_eps=1e-5, dtype="f32")
+CFG = oracle_config(SHAPE)
+# weights with std 0.02 give a nearly linear network; scale them up so that every
+# nonlinearity (softmax, silu, norm) matters in the comparison
+W_STD_SCALE = 12.0
+# the library model evaluates its rotary cos/sin tables in float32 whatever the model dtype, so
+# agreement with it is limited to about 1e-6; any structural mistake is orders of magnitude larger
+LIB_ATOL = 2e-5
+
+
+def big_weights(seed):
+    base = weights_fn(SHAPE, seed)
+
+    def get(l):
+        w = dict(base(l))
+        for k in ("wq", "wk", "wv", "wo", "wg", "wu", "wd"):
+            w[k] = w[k] * W_STD_SCALE
+        return w
+    return get
+
+
+def hf_model(weights, n_layers):
+    from transformers import LlamaConfig, LlamaModel
+    cfg = LlamaConfig(hidden_size=SHAPE.hidden, intermediate_size=SHAPE.ffn, num_hidden_layers=n_layers,
+                      num_attention_heads=SHAPE.n_q_heads, num_key_value_heads=SHAPE.n_kv_heads,
+                      head_dim=SHAPE.head_dim, rms_norm_eps=SHAPE.rms_eps, attention_bias=False,
+                      mlp_bias=False, vocab_size=8, rope_theta=SHAPE.rope_base,
+                      max_position_embeddings=512, attn_implementation="eager")
+    m = LlamaModel(cfg).double().eval()
+    names = {"g1": "input_layernorm", "wq": "self_attn.q_proj", "wk": "self_attn.k_proj",
+             "wv": "self_attn.v_proj", "wo": "self_attn.o_proj", "g2": "post_attention_layernorm",
+             "wg": "mlp.gate_proj", "wu": "mlp.up_proj", "wd": "mlp.down_proj"}
+    sd = m.state_dict()
+    for l in range(n_layers):
+        for k, n in names.items():
+            sd[f"layers.{l}.{n}.weight"].copy_(torch.from_numpy(weights(l)[k]))
+    return m
+
+
+def hf_prefill(weights, x):
+    """Hidden state entering each layer (+ leaving the last but one) and per-layer K, V from transformers."""
+    L = SHAPE.n_layers
+    m = hf_model(weights, L)
+    with torch.no_grad():
+        out = m(inputs_embeds=torch.from_numpy(x)[None], use_cache=True, output_hidden_states=True)
+    hs = [h[0].numpy() for h in out.hidden_states[:L]]          # entering layers 0..L-1
+    kv = [(out.past_key_values.layers[l].keys[0].permute(1, 0, 2).numpy(),
+           out.past_key_values.layers[l].values[0].permute(1, 0, 2).numpy()) for l in range(L)]
+    return hs, kv
+
+
+def full_prefill(weights, x, cu=None, pos=None):
+    T = x.shape[0]
+    cu = np.array([0, T]) if cu is None else cu
+    pos = np.arange(T) if pos is None else pos
+    dummy = [(None, None)] * SHAPE.n_layers
+    return O.partial_prefill(CFG, weights, x, 0, SHAPE.n_layers, dummy, pos, cu)
+
+
+@pytest.fixture(scope="module")
+def setup():
+    T = 19
+    w = big_weights(synth.SEED_RECEIVER)
+    x = synth.hidden_states(SHAPE, T).astype(np.float64)
+    return w, x, T
+
+
+def test_layer_stack_matches_independent_llama(setup):
+    w, x, T = setup
+    hs, kv = hf_prefill(w, x)
+    kv_o, _ = full_prefill(w, x)
+    for l in range(SHAPE.n_layers):
+        assert np.allclose(kv_o[l][0], kv[l][0], atol=LIB_ATOL), f"K layer {l}"
+        assert np.allclose(kv_o[l][1], kv[l][1], atol=LIB_ATOL), f"V layer {l}"
+    # hidden state leaving layers 0..L-2 (= entering 1..L-1)
+    dummy = [(None, None)] * SHAPE.n_layers
+    for hi in range(1, SHAPE.n_layers):
+        _, h = O.partial_prefill(CFG, w, x, 0, hi, dummy, np.arange(T), np.array([0, T]))
+        assert np.allclose(h, hs[hi], atol=LIB_ATOL), f"hidden leaving layer {hi - 1}"
+    # the nonlinearities are exercised: the result is far from the input
+    assert np.abs(hs[-1] - hs[0]).max() > 0.5
+
+
+def test_full_reuse_is_identity(setup):
+    w, x, T = setup
+    kv_r = kv_list(synth.kv_cache(SHAPE, T))
+    for lo in (0, 2, SHAPE.n_layers):
+        kv_o, h = O.partial_prefill(CFG, w, x, lo, lo, kv_r, np.arange(T), np.array([0, T]))
+        assert h is x
+        for l in range(SHAPE.n_layers):
+            assert kv_o[l][0] is kv_r[l][0] and kv_o[l][1] is kv_r[l][1]
+
+
+def test_layers_outside_group_are_spliced_unchanged(setup):
+    w, x, T = setup
+    kv_r = kv_list(synth.kv_cache(SHAPE, T))
+    kv_o, _ = O.partial_prefill(CFG, w, x, 1, 3, kv_r, np.arange(T), np.array([0, T]))
+    for l in (0, 3):
+        assert np.array_equal(kv_o[l][0], kv_r[l][0]) and np.array_equal(kv_o[l][1], kv_r[l][1])
+    for l in (1, 2):
+        assert kv_o[l][0].shape == kv_r[l][0].shape
+        assert not np.allclose(kv_o[l][0], kv_r[l][0])
+
+
+def test_recompute_starts_from_hidden_in_at_lo(setup):
+    # same-model identity: with the E cache of the same model at layer lo, selective recompute
+    # reproduces that model's own full-prefill KV (the zero-distance case of Sec. 3)
+    w, x, T = setup
+    hs, kv_full = hf_prefill(w, x)
+    kv_r = kv_list(synth.kv_cache(SHAPE, T))
+    kv_o, _ = O.partial_prefill(CFG, w, hs[1], 1, 3, kv_r, np.arange(T), np.array([0, T]))
+    for l in (1, 2):
+        assert np.allclose(kv_o[l][0], kv_full[l][0], atol=LIB_ATOL)
+        assert np.allclose(kv_o[l][1], kv_full[l][1], atol=LIB_ATOL)
+
+
+def test_composition(setup):
+    w, x, T = setup
+    kv_r = kv_list(synth.kv_cache(SHAPE, T))
+    pos, cu = np.arange(T), np.array([0, T])
+    kv_a, h_a = O.partial_prefill(CFG, w, x, 0, 4, kv_r, pos, cu)
+    kv_1, h_1 = O.partial_prefill(CFG, w, x, 0, 2, kv_r, pos, cu)
+    kv_2, h_2 = O.partial_prefill(CFG, w, h_1, 2, 4, kv_1, pos, cu)
+    assert np.array_equal(h_a, h_2)
+    for l in range(4):
+        assert np.array_equal(kv_a[l][0], kv_2[l][0]) and np.array_equal(kv_a[l][1], kv_2[l][1])
+
+
+def test_causality_and_truncation(setup):
+    w, x, T = setup
+    t = 7
+    kv_a, h_a = full_prefill(w, x)
+    x2 = x.copy()
+    x2[t:] = synth.hidden_states(SHAPE, T - t, seed=99).astype(np.float64)
+    kv_b, h_b = full_prefill(w, x2)
+    kv_c, h_c = full_prefill(w, x[:t])
+    assert np.array_equal(h_a[:t], h_b[:t]) and not np.allclose(h_a[t:], h_b[t:])
+    assert np.allclose(h_a[:t], h_c, atol=1e-12)
+    for l in range(SHAPE.n_layers):
+        assert np.array_equal(kv_a[l][0][:t], kv_b[l][0][:t])
+        assert np.allclose(kv_a[l][1][:t], kv_c[l][1], atol=1e-12)
+
+
+def test_ragged_batch_equals_independent_sequences(setup):
+    w, _, _ = setup
+    lens = [5, 1, 9]
+    cu = synth.cu_seqlens(lens)
+    pos = synth.packed_positions(lens)
+    x = synth.hidden_states(SHAPE, int(cu[-1]), seed=11).astype(np.float64)
+    kv_r = kv_list(synth.kv_cache(SHAPE, int(cu[-1])))
+    kv_o, h = O.partial_prefill(CFG, w, x, 1, 3, kv_r, pos, cu)
+    for b, n in enumerate(lens):
+        s, e = cu[b], cu[b + 1]
+        kv_rb = [(k[s:e], v[s:e]) for k, v in kv_r]
+        kv_b, h_b = O.partial_prefill(CFG, w, x[s:e], 1, 3, kv_rb, np.arange(n), np.array([0, n]))
+        assert np.allclose(h[s:e], h_b, atol=1e-12)
+        for l in (1, 2):
+            assert np.allclose(kv_o[l][0][s:e], kv_b[l][0], atol=1e-12)
+            assert np.allclose(kv_o[l][1][s:e], kv_b[l][1], atol=1e-12)
+
+
+def test_positions_drive_rope_not_row_index(setup):
+    # shifting all positions by a constant leaves attention scores unchanged (relative encoding),
+    # so hidden states are unchanged while K itself changes
+    w, x, T = setup
+    dummy = [(None, None)] * SHAPE.n_layers
+    cu = np.array([0, T])
+    kv_a, h_a = O.partial_prefill(CFG, w, x, 0, 2, dummy, np.arange(T), cu)
+    kv_b, h_b = O.partial_prefill(CFG, w, x, 0, 2, dummy, np.arange(T) + 100, cu)
+    assert np.allclose(h_a, h_b, atol=1e-9)
+    assert not np.allclose(kv_a[0][0], kv_b[0][0])
+    assert np.allclose(kv_a[0][1], kv_b[0][1], atol=1e-12)
+
+
+def test_suffix_prefill_equals_prefix_caching(setup):
+    # full prefill of T+S tokens == prefix prefill, then suffix prefill against the model's own cache;
+    # the T+S reference comes from the independent Llama implementation
+    w, _, _ = setup
+    T, S = 13, 5
+    x = synth.hidden_states(SHAPE, T + S, seed=21).astype(np.float64)
+    hs, kv_full = hf_prefill(w, x)
+    kv_p, _ = full_prefill(w, x[:T])
+    kv_s, h_s = O.suffix_prefill(CFG, w, x[T:], kv_p, np.arange(T, T + S), np.array([0, T]), np.array([0, S]))
+    for l in range(SHAPE.n_layers):
+        assert np.allclose(kv_s[l][0], kv_full[l][0][T:], atol=LIB_ATOL)
+        assert np.allclose(kv_s[l][1], kv_full[l][1][T:], atol=LIB_ATOL)
+    # hidden leaving the last layer: compare with a 4-layer oracle full prefill (itself pinned above for
+    # layers 0..L-2; the last layer's K/V inputs are pinned here and its MLP by the next test)
+    _, h_full = full_prefill(w, x)
+    assert np.allclose(h_s, h_full[T:], atol=1e-10)
+
+
+def test_last_layer_output_against_library(setup):
+    # run the library model with one extra (5th) layer so that the state leaving layer 3 is exposed
+    w, x, T = setup
+    from transformers import LlamaConfig  # noqa: F401
+    L = SHAPE.n_layers
+
+    def w5(l):
+        return w(min(l, L - 1))
+    m = hf_model(w5, L + 1)
+    with torch.no_grad():
+        out = m(inputs_embeds=torch.from_numpy(x)[None], output_hidden_states=True)
+    _, h = full_prefill(w, x)
+    assert np.allclose(h, out.hidden_states[L][0].numpy(), atol=LIB_ATOL)
+
+
+def test_suffix_ragged_and_mixed_cache(setup):
+    # ragged suffix against a mixed cache == each sequence alone
+    w, _, _ = setup
+    lens, slens = [6, 3], [2, 4]
+    cu, cus = synth.cu_seqlens(lens), synth.cu_seqlens(slens)
+    kv = kv_list(synth.kv_cache(SHAPE, int(cu[-1])))
+    xs = synth.hidden_states(SHAPE, int(cus[-1]), seed=31).astype(np.float64)
+    spos = synth.packed_positions(slens, start=lens)
+    kv_s, h = O.suffix_prefill(CFG, w, xs, kv, spos, cu, cus)
+    for b in range(2):
+        p0, p1, s0, s1 = cu[b], cu[b + 1], cus[b], cus[b + 1]
+        kvb = [(k[p0:p1], v[p0:p1]) for k, v in kv]
+        kv_b, h_b = O.suffix_prefill(CFG, w, xs[s0:s1], kvb, spos[s0:s1],
+                                     np.array([0, p1 - p0]), np.array([0, s1 - s0]))
+        assert np.allclose(h[s0:s1], h_b, atol=1e-12)
+        for l in range(SHAPE.n_layers):
+            assert np.allclose(kv_s[l][0][s0:s1], kv_b[l][0], atol=1e-12)
+
+
+def test_sampled_rows_equal_full_rows(setup):
+    w, x, T = setup
+    lens = [8, 11]
+    cu, pos = synth.cu_seqlens(lens), synth.packed_positions(lens)
+    h_all, K, V = O.prefix_layer(CFG, w(1), x, pos, cu)
+    rows = [0, 7, 8, 18]
+    h_sel, K2, V2 = O.prefix_layer(CFG, w(1), x, pos, cu, rows=rows)
+    assert np.array_equal(K, K2) and np.array_equal(V, V2)
+    assert np.allclose(h_sel, h_all[rows], atol=1e-13)
+
+
+def test_bad_layer_range_rejected(setup):
+    w, x, T = setup
+    with pytest.raises(ValueError):
+        O.partial_prefill(CFG, w, x, 3, 2, [], np.arange(T), np.array([0, T]))
+    with pytest.raises(ValueError):
+        O.partial_prefill(CFG, w, x, 0, 5, [], np.arange(T), np.array([0, T]))
+
+
+def test_error_measure():
+    ref = np.array([0.0, 2.0, -4.0])
+    assert O.max_rel_err(ref, ref) == 0.0
+    assert np.isclose(O.max_rel_err(ref + np.array([0.1, 0.0, 0.0]), ref), 0.025)
