@@ -1,0 +1,187 @@
+/*
+ * dsk - selective-layer prefill for cross-model KV-cache reuse on AMD MI355X (gfx950).
+ *
+ * C ABI of the hot path of DroidSpeak (arxiv 2411.02820).  A receiver LLM takes the KV
+ * cache a sender LLM of the same architecture produced for a context, recomputes one
+ * contiguous group of decoder layers [lo, hi) from the sender's E cache (the hidden
+ * state entering layer lo), keeps the sender's KV for every other layer, and then
+ * prefills the new tokens against that mixed cache (Sec. 4.1).  Loading the reused
+ * layers runs on a side stream under the recomputation (Sec. 4.3 "Smart KV Cache
+ * Loading", Sec. 4.4: transfers on a stream other than the compute stream).
+ *
+ * Conventions
+ *  - Every function returns DSK_OK (0) or a negative dsk_status.  Arguments are checked
+ *    before anything is enqueued: a failed call has written nothing.
+ *  - "device" pointers are HIP device memory of the current device, "host" pointers are
+ *    ordinary host memory, "pinned" means page-locked host memory (hipHostMalloc).
+ *  - Streams are hipStream_t passed as void*; NULL is the default stream.  Calls are
+ *    asynchronous: they enqueue work and return without waiting for the device.
+ *  - Layer indices are 0-based and half open: [lo, hi).  The paper's "recompute layers
+ *    4-10 of 10" is lo=3, hi=10.
+ *  - Element type is the model's dtype (fp32 or bf16) for hidden states, KV and weights.
+ *  - Tokens of several sequences are packed back to back; sequence b owns token rows
+ *    cu_seqlens[b] .. cu_seqlens[b+1]-1; causal order inside a sequence is packed order.
+ *  - A model must not be used from two host threads at once, and two calls on one model
+ *    must be issued on the same stream or be ordered by the caller.
+ */
+#ifndef DSK_H
+#define DSK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#if defined(__GNUC__)
+#define DSK_API __attribute__((visibility("default")))
+#else
+#define DSK_API
+#endif
+
+typedef struct dsk_model dsk_model_t;
+
+typedef enum {
+  DSK_OK = 0,
+  DSK_EINVAL = -1, /* null pointer, bad layer range, bad batch descriptor, misaligned pointer */
+  DSK_ESHAPE = -2, /* model shape not supported (Hq % Hkv, odd head_dim, head_dim > 256, ...) */
+  DSK_EDTYPE = -3, /* dtype not DSK_F32 / DSK_BF16 */
+  DSK_ENOMEM = -4, /* device or host allocation failed */
+  DSK_EHIP = -5    /* a HIP call failed; see dsk_last_hip_error() */
+} dsk_status;
+
+typedef enum { DSK_F32 = 0, DSK_BF16 = 1 } dsk_dtype;
+typedef enum { DSK_MEM_DEVICE = 0, DSK_MEM_HOST_PINNED = 1 } dsk_mem;
+
+/* Tensors of one decoder layer, each in its logical [out, in] row-major shape:
+ * G1,G2 [d]; WQ [Hq*dh, d]; WK,WV [Hkv*dh, d]; WO [d, Hq*dh]; WG,WU [F, d]; WD [d, F]. */
+typedef enum {
+  DSK_G1 = 0, DSK_WQ = 1, DSK_WK = 2, DSK_WV = 3, DSK_WO = 4,
+  DSK_G2 = 5, DSK_WG = 6, DSK_WU = 7, DSK_WD = 8
+} dsk_tensor;
+
+/* Llama-style decoder: pre-norm residual blocks, RMSNorm (eps inside the root), rotary
+ * embedding on pairs (i, i+dh/2) with theta_i = rope_base^(-2i/dh), grouped-query causal
+ * attention (kv head = q head / (Hq/Hkv)), SwiGLU MLP, no biases. */
+typedef struct {
+  int32_t n_layers;   /* L */
+  int32_t hidden;     /* d */
+  int32_t n_q_heads;  /* Hq */
+  int32_t n_kv_heads; /* Hkv, divides Hq */
+  int32_t head_dim;   /* dh, even, <= 256 */
+  int32_t ffn;        /* F */
+  double rope_base;
+  double rms_eps;
+  int32_t dtype;      /* dsk_dtype */
+} dsk_config_t;
+
+/* A per-layer KV cache (Sec. 4.4: the cache is split into layers).  Layer l's keys are
+ * rows of Hkv*dh elements starting at base + l*layer_stride, its values start v_offset
+ * bytes later; row r is at + r*Hkv*dh*elem_size.  Keys are stored after the rotary
+ * embedding, values as projected.  Prefix token t lives in row t (its packed index). */
+typedef struct {
+  void* base;
+  int32_t mem;          /* dsk_mem: where base points */
+  int64_t layer_stride; /* bytes between layers */
+  int64_t v_offset;     /* bytes from a layer's K rows to its V rows, >= n_rows*Hkv*dh*elem */
+  int64_t n_rows;       /* rows allocated per layer for K (and for V) */
+} dsk_kv_t;
+
+/* A packed (ragged) batch of token rows. */
+typedef struct {
+  int32_t n_seqs;                 /* B >= 1 */
+  int32_t n_tokens;               /* = cu_seqlens[B] */
+  const int32_t* cu_seqlens_host; /* host, [B+1], cu[0]=0, strictly increasing */
+  const int32_t* cu_seqlens_dev;  /* device copy of the same array */
+  const int32_t* positions_dev;   /* device, [n_tokens], rotary position of every token; may be NULL for
+                                     descriptors that only delimit sequences */
+} dsk_batch_t;
+
+/* flags of dsk_partial_prefill */
+#define DSK_DEFER_JOIN 1u /* do not make `stream` wait for the reused-layer loads at the end of the call;
+                             the following dsk_suffix_prefill waits layer by layer, or call dsk_join_loads */
+/* How the reused layers are brought in (the three strategies of Sec. 4.3, Fig. 13). */
+typedef enum {
+  DSK_LOAD_PIPELINED = 0,    /* (c) E cache first, reused layers on the side stream under the recompute */
+  DSK_LOAD_REUSED_FIRST = 1, /* (b) load the reused layers, then recompute */
+  DSK_LOAD_ALL_FIRST = 2     /* (a) load every layer of the sender's KV, then recompute */
+} dsk_load_mode;
+
+/* Creates a model: allocates its weights (library-owned, in the library's own packed
+ * layout), a workspace for up to max_tokens token rows per call, a side stream and
+ * per-layer events, on the current device.  Weights start undefined: fill them with
+ * dsk_model_set_tensor or dsk_model_init_random.  *out is written only on success. */
+DSK_API int dsk_model_create(const dsk_config_t* cfg, int64_t max_tokens, dsk_model_t** out);
+
+/* Waits for the model's outstanding work and frees everything it owns. */
+DSK_API int dsk_model_destroy(dsk_model_t* model);
+
+/* Copies one tensor (logical [out,in] row-major, model dtype) into the model.  A device src is
+ * read on `stream`, asynchronously.  A host src (pinned or ordinary memory, src_mem =
+ * DSK_MEM_HOST_PINNED) is staged through a temporary device buffer and the call returns after
+ * the copy has completed. */
+DSK_API int dsk_model_set_tensor(dsk_model_t* model, int layer, int tensor, const void* src, int src_mem, void* stream);
+
+/* Writes one tensor back in its logical layout to device memory dst (for checks). */
+DSK_API int dsk_model_get_tensor(const dsk_model_t* model, int layer, int tensor, void* dst_device, void* stream);
+
+/* Fills all weights on the device with the counter-based generator of dsk_fill_normal:
+ * tensor `t` of layer `l` is stream l*16+t, element index = out*in_dim + in; projection
+ * matrices N(0, std), norm gains 1 + N(0, std).  For synthetic workloads (the 70B shape
+ * cannot be staged through host memory). */
+DSK_API int dsk_model_init_random(dsk_model_t* model, uint64_t seed, float std, void* stream);
+
+/* dst[i] = offset + std * z(seed, stream_id, idx0 + i), i < n, rounded to dtype; z is an
+ * integer-only approximately normal variate (sum of eight 16-bit lanes of two SplitMix64
+ * outputs, centred, scaled in fp32), so any implementation reproduces it bit for bit. */
+DSK_API int dsk_fill_normal(void* dst_device, int64_t n, uint64_t seed, uint64_t stream_id, float std, float offset,
+                    int64_t idx0, int dtype, void* stream);
+
+/* Selective-layer prefill (Sec. 4.1; the partial_prefill interface of Sec. 4.4).
+ *   hidden_in   [n_tokens, d]  E cache at the transition layer lo (the token embeddings when lo = 0);
+ *               device, or pinned host (then it is transferred first, before any KV: Fig. 13(c)).
+ *   kv_reused   the sender's cache, device or pinned host; may be NULL when lo=0 and hi=L.
+ *   kv_out      device cache that receives, for lo <= l < hi, K and V recomputed by the receiver
+ *               (rows 0..n_tokens-1), and for every other l a byte-exact copy of kv_reused's rows
+ *               0..n_tokens-1.  kv_out may alias kv_reused (same base and strides, device): the
+ *               splice is then free.  Rows >= n_tokens are left untouched.
+ *   batch       the packed prefix tokens with their positions.
+ *   hidden_out  optional device [n_tokens, d]: state leaving layer hi-1 (a copy of hidden_in if lo=hi).
+ * lo = hi is valid (pure splice).  Compute runs on `stream`, loads on the model's side stream
+ * after everything already enqueued on `stream`; on return from the call nothing has been waited
+ * for.  Unless DSK_DEFER_JOIN is set, work enqueued on `stream` afterwards sees the whole cache.
+ * Host buffers must stay valid until `stream` (and, with DSK_DEFER_JOIN, the loads) have drained. */
+DSK_API int dsk_partial_prefill(dsk_model_t* model, const void* hidden_in, int hidden_in_mem, int lo, int hi,
+                        const dsk_kv_t* kv_reused, const dsk_kv_t* kv_out, const dsk_batch_t* batch,
+                        void* hidden_out, uint32_t flags, void* stream);
+
+/* Prefill of the new tokens against the mixed cache through all L layers (Sec. 4.1: a layer whose
+ * KV is reused only sees the new tokens).  Suffix token j of sequence b attends to prefix rows
+ * prefix.cu[b] .. prefix.cu[b+1]-1 and to suffix tokens suffix.cu[b] .. j; its K/V is written to
+ * row suffix_row0 + j of every layer of kv.  Per layer, waits for that layer's load if a preceding
+ * dsk_partial_prefill deferred its join.
+ *   suffix_hidden_in [suffix.n_tokens, d] device;  hidden_out [suffix.n_tokens, d] device: state
+ *   leaving the last layer (before any final norm).  prefix.positions_dev is not used. */
+DSK_API int dsk_suffix_prefill(dsk_model_t* model, const void* suffix_hidden_in, const dsk_kv_t* kv,
+                       const dsk_batch_t* prefix, const dsk_batch_t* suffix, int64_t suffix_row0,
+                       void* hidden_out, void* stream);
+
+/* Makes `stream` wait for all loads a deferred dsk_partial_prefill left outstanding. */
+DSK_API int dsk_join_loads(dsk_model_t* model, void* stream);
+
+/* Selects the loading strategy used by later dsk_partial_prefill calls (default pipelined). */
+DSK_API int dsk_set_load_mode(dsk_model_t* model, int load_mode);
+
+/* Sizes, for callers that budget memory. */
+DSK_API int64_t dsk_model_weight_bytes(const dsk_model_t* model);
+DSK_API int64_t dsk_model_workspace_bytes(const dsk_model_t* model);
+
+DSK_API const char* dsk_strerror(int status);
+/* hipError_t (as int) of the last failed HIP call on this host thread, 0 if none. */
+DSK_API int dsk_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DSK_H */

@@ -1,0 +1,200 @@
+"""ctypes binding of libdsk.so: the same entry points as include/dsk.h, argument marshalling only.
+
+Every step of the path runs inside the library's HIP kernels.  There is no fallback: if the
+shared library has not been built, importing this module raises.  torch is used by callers
+for device memory and streams; this file only turns tensors into raw pointers.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdsk.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: build it first (python -m paper_2411_02820_amd.build "
+                      "or __graft_entry__.build()); there is no non-HIP fallback")
+
+lib = C.CDLL(LIB_PATH)
+
+# ---- enums (include/dsk.h) ----
+DSK_OK, DSK_EINVAL, DSK_ESHAPE, DSK_EDTYPE, DSK_ENOMEM, DSK_EHIP = 0, -1, -2, -3, -4, -5
+DSK_F32, DSK_BF16 = 0, 1
+DSK_MEM_DEVICE, DSK_MEM_HOST_PINNED = 0, 1
+DSK_G1, DSK_WQ, DSK_WK, DSK_WV, DSK_WO, DSK_G2, DSK_WG, DSK_WU, DSK_WD = range(9)
+DSK_DEFER_JOIN = 1
+DSK_LOAD_PIPELINED, DSK_LOAD_REUSED_FIRST, DSK_LOAD_ALL_FIRST = 0, 1, 2
+
+EXPORTS = (
+    "dsk_model_create", "dsk_model_destroy", "dsk_model_set_tensor", "dsk_model_get_tensor",
+    "dsk_model_init_random", "dsk_fill_normal", "dsk_partial_prefill", "dsk_suffix_prefill",
+    "dsk_join_loads", "dsk_set_load_mode", "dsk_model_weight_bytes", "dsk_model_workspace_bytes",
+    "dsk_strerror", "dsk_last_hip_error",
+)
+
+
+class dsk_config_t(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("hidden", C.c_int32), ("n_q_heads", C.c_int32),
+                ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("ffn", C.c_int32),
+                ("rope_base", C.c_double), ("rms_eps", C.c_double), ("dtype", C.c_int32)]
+
+
+class dsk_kv_t(C.Structure):
+    _fields_ = [("base", C.c_void_p), ("mem", C.c_int32), ("layer_stride", C.c_int64),
+                ("v_offset", C.c_int64), ("n_rows", C.c_int64)]
+
+
+class dsk_batch_t(C.Structure):
+    _fields_ = [("n_seqs", C.c_int32), ("n_tokens", C.c_int32),
+                ("cu_seqlens_host", C.POINTER(C.c_int32)), ("cu_seqlens_dev", C.c_void_p),
+                ("positions_dev", C.c_void_p)]
+
+
+_P = C.c_void_p
+lib.dsk_model_create.argtypes = [C.POINTER(dsk_config_t), C.c_int64, C.POINTER(_P)]
+lib.dsk_model_destroy.argtypes = [_P]
+lib.dsk_model_set_tensor.argtypes = [_P, C.c_int, C.c_int, _P, C.c_int, _P]
+lib.dsk_model_get_tensor.argtypes = [_P, C.c_int, C.c_int, _P, _P]
+lib.dsk_model_init_random.argtypes = [_P, C.c_uint64, C.c_float, _P]
+lib.dsk_fill_normal.argtypes = [_P, C.c_int64, C.c_uint64, C.c_uint64, C.c_float, C.c_float, C.c_int64, C.c_int, _P]
+lib.dsk_partial_prefill.argtypes = [_P, _P, C.c_int, C.c_int, C.c_int, C.POINTER(dsk_kv_t), C.POINTER(dsk_kv_t),
+                                    C.POINTER(dsk_batch_t), _P, C.c_uint32, _P]
+lib.dsk_suffix_prefill.argtypes = [_P, _P, C.POINTER(dsk_kv_t), C.POINTER(dsk_batch_t), C.POINTER(dsk_batch_t),
+                                   C.c_int64, _P, _P]
+lib.dsk_join_loads.argtypes = [_P, _P]
+lib.dsk_set_load_mode.argtypes = [_P, C.c_int]
+lib.dsk_model_weight_bytes.argtypes = [_P]
+lib.dsk_model_weight_bytes.restype = C.c_int64
+lib.dsk_model_workspace_bytes.argtypes = [_P]
+lib.dsk_model_workspace_bytes.restype = C.c_int64
+lib.dsk_strerror.argtypes = [C.c_int]
+lib.dsk_strerror.restype = C.c_char_p
+lib.dsk_last_hip_error.argtypes = []
+for _n in EXPORTS:
+    if _n not in ("dsk_model_weight_bytes", "dsk_model_workspace_bytes", "dsk_strerror"):
+        getattr(lib, _n).restype = C.c_int
+
+
+class DskError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib.dsk_strerror(status).decode()
+        if status == DSK_EHIP:
+            msg += f" (hipError_t {lib.dsk_last_hip_error()})"
+        super().__init__(f"{where}: {msg} [{status}]")
+
+
+def _check(status: int, where: str):
+    if status != DSK_OK:
+        raise DskError(status, where)
+
+
+def _ptr(x):
+    """Raw address of a torch tensor / int / None."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return x.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        return None
+    return stream if isinstance(stream, int) else stream.cuda_stream
+
+
+def _mem_of(t) -> int:
+    return DSK_MEM_DEVICE if t.is_cuda else DSK_MEM_HOST_PINNED
+
+
+# ---- the entry points, same names as the header ----
+def dsk_model_create(cfg: dsk_config_t, max_tokens: int) -> int:
+    out = _P()
+    _check(lib.dsk_model_create(C.byref(cfg), max_tokens, C.byref(out)), "dsk_model_create")
+    return out.value
+
+
+def dsk_model_destroy(model: int):
+    _check(lib.dsk_model_destroy(model), "dsk_model_destroy")
+
+
+def dsk_model_set_tensor(model: int, layer: int, tensor: int, src, stream=None):
+    _check(lib.dsk_model_set_tensor(model, layer, tensor, _ptr(src), _mem_of(src), _stream(stream)),
+           "dsk_model_set_tensor")
+
+
+def dsk_model_get_tensor(model: int, layer: int, tensor: int, dst, stream=None):
+    _check(lib.dsk_model_get_tensor(model, layer, tensor, _ptr(dst), _stream(stream)), "dsk_model_get_tensor")
+
+
+def dsk_model_init_random(model: int, seed: int, std: float, stream=None):
+    _check(lib.dsk_model_init_random(model, seed, std, _stream(stream)), "dsk_model_init_random")
+
+
+def dsk_fill_normal(dst, n: int, seed: int, stream_id: int, std: float, offset: float, idx0: int, dtype: int,
+                    stream=None):
+    _check(lib.dsk_fill_normal(_ptr(dst), n, seed, stream_id, std, offset, idx0, dtype, _stream(stream)),
+           "dsk_fill_normal")
+
+
+def dsk_partial_prefill(model: int, hidden_in, lo: int, hi: int, kv_reused, kv_out: dsk_kv_t, batch: dsk_batch_t,
+                        hidden_out=None, flags: int = 0, stream=None):
+    _check(lib.dsk_partial_prefill(model, _ptr(hidden_in), _mem_of(hidden_in), lo, hi,
+                                   None if kv_reused is None else C.byref(kv_reused), C.byref(kv_out),
+                                   C.byref(batch), _ptr(hidden_out), flags, _stream(stream)),
+           "dsk_partial_prefill")
+
+
+def dsk_suffix_prefill(model: int, suffix_hidden_in, kv: dsk_kv_t, prefix: dsk_batch_t, suffix: dsk_batch_t,
+                       suffix_row0: int, hidden_out, stream=None):
+    _check(lib.dsk_suffix_prefill(model, _ptr(suffix_hidden_in), C.byref(kv), C.byref(prefix), C.byref(suffix),
+                                  suffix_row0, _ptr(hidden_out), _stream(stream)), "dsk_suffix_prefill")
+
+
+def dsk_join_loads(model: int, stream=None):
+    _check(lib.dsk_join_loads(model, _stream(stream)), "dsk_join_loads")
+
+
+def dsk_set_load_mode(model: int, mode: int):
+    _check(lib.dsk_set_load_mode(model, mode), "dsk_set_load_mode")
+
+
+def dsk_model_weight_bytes(model: int) -> int:
+    return lib.dsk_model_weight_bytes(model)
+
+
+def dsk_model_workspace_bytes(model: int) -> int:
+    return lib.dsk_model_workspace_bytes(model)
+
+
+# ---- descriptor helpers (marshalling only) ----
+def config_from_shape(shape) -> dsk_config_t:
+    """shape: an object with n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, rope_base, rms_eps, dtype."""
+    return dsk_config_t(shape.n_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.ffn,
+                        float(shape.rope_base), float(shape.rms_eps), DSK_F32 if shape.dtype == "f32" else DSK_BF16)
+
+
+def kv_desc(t) -> dsk_kv_t:
+    """Descriptor of a cache tensor laid out [L, 2, n_rows, Hkv, dh] (contiguous; device or pinned host)."""
+    assert t.dim() == 5 and t.shape[1] == 2 and t.is_contiguous()
+    es = t.element_size()
+    row = t.shape[3] * t.shape[4] * es
+    return dsk_kv_t(t.data_ptr(), _mem_of(t), 2 * t.shape[2] * row, t.shape[2] * row, t.shape[2])
+
+
+class Batch:
+    """Owns the host and device arrays a dsk_batch_t points to (keeps them alive)."""
+
+    def __init__(self, cu_seqlens, positions=None, device="cuda"):
+        import torch
+        self.cu_host = np.ascontiguousarray(cu_seqlens, dtype=np.int32)
+        self.cu_dev = torch.from_numpy(self.cu_host).to(device)
+        self.pos_dev = None if positions is None else torch.from_numpy(
+            np.ascontiguousarray(positions, dtype=np.int32)).to(device)
+        self.desc = dsk_batch_t(len(self.cu_host) - 1, int(self.cu_host[-1]),
+                                self.cu_host.ctypes.data_as(C.POINTER(C.c_int32)), self.cu_dev.data_ptr(),
+                                None if self.pos_dev is None else self.pos_dev.data_ptr())

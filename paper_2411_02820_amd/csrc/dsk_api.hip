@@ -1,0 +1,450 @@
+// C-ABI entry points and the host-side scheduler (streams, per-layer load events) of libdsk.
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <new>
+
+#include "dsk_internal.h"
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+#define HIP_TRY(expr)                          \
+  do {                                         \
+    hipError_t e_ = (expr);                    \
+    if (e_ != hipSuccess) {                    \
+      g_last_hip_error = (int)e_;              \
+      return DSK_EHIP;                         \
+    }                                          \
+  } while (0)
+
+inline bool aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
+
+int alloc_dev(void** p, int64_t bytes, int64_t* total) {
+  if (bytes <= 0) bytes = 16;
+  hipError_t e = hipMalloc(p, (size_t)bytes);
+  if (e != hipSuccess) {
+    g_last_hip_error = (int)e;
+    *p = nullptr;
+    return e == hipErrorOutOfMemory ? DSK_ENOMEM : DSK_EHIP;
+  }
+  *total += bytes;
+  return DSK_OK;
+}
+
+void free_model(dsk_model* m) {
+  if (!m) return;
+  if (m->layers) {
+    for (int l = 0; l < m->cfg.n_layers; ++l) {
+      LayerWeights& w = m->layers[l];
+      (void)hipFree(w.g1); (void)hipFree(w.wqkv); (void)hipFree(w.wo);
+      (void)hipFree(w.g2); (void)hipFree(w.wgu); (void)hipFree(w.wd);
+    }
+    free(m->layers);
+  }
+  (void)hipFree(m->xn); (void)hipFree(m->qkv); (void)hipFree(m->attn); (void)hipFree(m->gu);
+  (void)hipFree(m->act); (void)hipFree(m->h); (void)hipFree(m->rope_cs); (void)hipFree(m->theta);
+  if (m->ev_kv) {
+    for (int l = 0; l < m->cfg.n_layers; ++l)
+      if (m->ev_kv[l]) (void)hipEventDestroy(m->ev_kv[l]);
+    free(m->ev_kv);
+  }
+  if (m->ev_entry) (void)hipEventDestroy(m->ev_entry);
+  if (m->ev_e) (void)hipEventDestroy(m->ev_e);
+  if (m->ev_all) (void)hipEventDestroy(m->ev_all);
+  if (m->load_stream) (void)hipStreamDestroy(m->load_stream);
+  free(m->pending);
+  free(m);
+}
+
+int check_batch(const dsk_batch_t* b, bool need_positions) {
+  if (!b || !b->cu_seqlens_host || !b->cu_seqlens_dev) return DSK_EINVAL;
+  if (need_positions && !b->positions_dev) return DSK_EINVAL;
+  if (b->n_seqs < 1 || b->n_tokens < 1) return DSK_EINVAL;
+  if (b->cu_seqlens_host[0] != 0) return DSK_EINVAL;
+  for (int i = 0; i < b->n_seqs; ++i)
+    if (b->cu_seqlens_host[i + 1] <= b->cu_seqlens_host[i]) return DSK_EINVAL;
+  if (b->cu_seqlens_host[b->n_seqs] != b->n_tokens) return DSK_EINVAL;
+  return DSK_OK;
+}
+
+int check_kv(const dsk_model* m, const dsk_kv_t* kv, int64_t rows_needed, bool must_be_device) {
+  if (!kv || !kv->base || !aligned16(kv->base)) return DSK_EINVAL;
+  if (kv->mem != DSK_MEM_DEVICE && kv->mem != DSK_MEM_HOST_PINNED) return DSK_EINVAL;
+  if (must_be_device && kv->mem != DSK_MEM_DEVICE) return DSK_EINVAL;
+  const int64_t row_bytes = (int64_t)m->cfg.n_kv_heads * m->cfg.head_dim * m->elem;
+  if (kv->n_rows < rows_needed || kv->n_rows >= (int64_t)1 << 31) return DSK_EINVAL;
+  if (kv->v_offset < kv->n_rows * row_bytes || (kv->v_offset & 15)) return DSK_EINVAL;
+  if (kv->layer_stride < kv->v_offset + kv->n_rows * row_bytes || (kv->layer_stride & 15)) return DSK_EINVAL;
+  return DSK_OK;
+}
+
+inline char* kv_k(const dsk_kv_t* kv, int l) { return (char*)kv->base + (int64_t)l * kv->layer_stride; }
+inline char* kv_v(const dsk_kv_t* kv, int l) { return kv_k(kv, l) + kv->v_offset; }
+
+hipError_t gemm(const dsk_model* m, const void* A, int64_t lda, const void* W, int64_t ldw, void* C, int64_t ldc,
+                const void* R, int64_t ldr, int M, int N, int K, int epi, hipStream_t s) {
+  if (m->cfg.dtype == DSK_BF16) {
+    hipError_t e = launch_gemm_mfma_bf16(A, lda, W, ldw, C, ldc, R, ldr, M, N, K, epi, s);
+    if (e != hipErrorNotSupported) return e;
+  }
+  return launch_gemm_generic(m->cfg.dtype, A, lda, W, ldw, C, ldc, R, ldr, M, N, K, epi, s);
+}
+
+hipError_t attention(const dsk_model* m, const AttnArgs& a, hipStream_t s) {
+  if (m->cfg.dtype == DSK_BF16) {
+    hipError_t e = launch_attn_mfma_bf16(a, s);
+    if (e != hipErrorNotSupported) return e;
+  }
+  return launch_attn_generic(m->cfg.dtype, a, s);
+}
+
+// One decoder layer over n token rows.  h_in: residual stream entering the layer; h_out: where the
+// state leaving the layer is written (may equal h_in).  K/V of the tokens go to rows own_row0.. of the
+// cache layer (k_rows, v_rows); attention additionally sees the prefix rows delimited by p_cu.
+int run_layer(dsk_model* m, int l, const void* h_in, void* h_out, char* k_layer, char* v_layer, int64_t own_row0,
+              const int32_t* q_cu, const int32_t* q_cu_host, const int32_t* p_cu, int n_seqs, int n, hipStream_t s) {
+  const dsk_config_t& c = m->cfg;
+  const LayerWeights& w = m->layers[l];
+  const int d = c.hidden, F = c.ffn, nq = c.n_q_heads * c.head_dim;
+  const int64_t row_bytes = (int64_t)c.n_kv_heads * c.head_dim * m->elem;
+  char* k_own = k_layer + own_row0 * row_bytes;
+  char* v_own = v_layer + own_row0 * row_bytes;
+  HIP_TRY(launch_rmsnorm(c.dtype, h_in, w.g1, m->xn, n, d, (float)c.rms_eps, s));
+  HIP_TRY(gemm(m, m->xn, d, w.wqkv, d, m->qkv, m->n_qkv, nullptr, 0, n, m->n_qkv, d, EPI_STORE, s));
+  HIP_TRY(launch_rope_kv_write(c.dtype, m->qkv, m->rope_cs, k_own, v_own, n, c.n_q_heads, c.n_kv_heads, c.head_dim, s));
+  AttnArgs a;
+  a.q = m->qkv; a.ldq = m->n_qkv; a.k_rows = k_layer; a.v_rows = v_layer; a.out = m->attn;
+  a.q_cu = q_cu; a.p_cu = p_cu; a.q_cu_host = q_cu_host; a.n_seqs = n_seqs; a.own_row0 = own_row0; a.n_q = n;
+  a.Hq = c.n_q_heads; a.Hkv = c.n_kv_heads; a.dh = c.head_dim;
+  HIP_TRY(attention(m, a, s));
+  HIP_TRY(gemm(m, m->attn, nq, w.wo, nq, m->h, d, h_in, d, n, d, nq, EPI_RESIDUAL, s));
+  HIP_TRY(launch_rmsnorm(c.dtype, m->h, w.g2, m->xn, n, d, (float)c.rms_eps, s));
+  HIP_TRY(gemm(m, m->xn, d, w.wgu, d, m->gu, 2 * (int64_t)F, nullptr, 0, n, 2 * F, d, EPI_STORE, s));
+  HIP_TRY(launch_swiglu(c.dtype, m->gu, m->act, n, F, m->gu_block, s));
+  HIP_TRY(gemm(m, m->act, F, w.wd, F, h_out, d, m->h, d, n, d, F, EPI_RESIDUAL, s));
+  return DSK_OK;
+}
+
+struct TensorPlace { void* base; int64_t rows, cols; int map; int64_t row_off; };
+
+int place_tensor(const dsk_model* m, int layer, int tensor, TensorPlace* p) {
+  if (layer < 0 || layer >= m->cfg.n_layers) return DSK_EINVAL;
+  const dsk_config_t& c = m->cfg;
+  const LayerWeights& w = m->layers[layer];
+  const int64_t d = c.hidden, nq = (int64_t)c.n_q_heads * c.head_dim, nkv = (int64_t)c.n_kv_heads * c.head_dim, F = c.ffn;
+  switch (tensor) {
+    case DSK_G1: *p = {w.g1, 1, d, 0, 0}; break;
+    case DSK_G2: *p = {w.g2, 1, d, 0, 0}; break;
+    case DSK_WQ: *p = {w.wqkv, nq, d, 0, 0}; break;
+    case DSK_WK: *p = {w.wqkv, nkv, d, 0, nq}; break;
+    case DSK_WV: *p = {w.wqkv, nkv, d, 0, nq + nkv}; break;
+    case DSK_WO: *p = {w.wo, d, nq, 0, 0}; break;
+    case DSK_WG: *p = {w.wgu, F, d, 1, 0}; break;
+    case DSK_WU: *p = {w.wgu, F, d, 2, 0}; break;
+    case DSK_WD: *p = {w.wd, d, F, 0, 0}; break;
+    default: return DSK_EINVAL;
+  }
+  return DSK_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int dsk_model_create(const dsk_config_t* cfg, int64_t max_tokens, dsk_model_t** out) {
+  if (!cfg || !out || max_tokens < 1 || max_tokens >= ((int64_t)1 << 31)) return DSK_EINVAL;
+  if (cfg->dtype != DSK_F32 && cfg->dtype != DSK_BF16) return DSK_EDTYPE;
+  if (cfg->n_layers < 1 || cfg->hidden < 1 || cfg->n_q_heads < 1 || cfg->n_kv_heads < 1 || cfg->head_dim < 2 ||
+      cfg->ffn < 1)
+    return DSK_ESHAPE;
+  if (cfg->n_q_heads % cfg->n_kv_heads || (cfg->head_dim & 1) || cfg->head_dim > 256) return DSK_ESHAPE;
+  // rows of every matrix must keep 16-byte alignment
+  const int elem = cfg->dtype == DSK_F32 ? 4 : 2;
+  const int per16 = 16 / elem;
+  if (cfg->hidden % per16 || cfg->ffn % per16 || cfg->head_dim % per16) return DSK_ESHAPE;
+  if (!(cfg->rope_base > 0.0) || !(cfg->rms_eps >= 0.0)) return DSK_EINVAL;
+
+  dsk_model* m = (dsk_model*)calloc(1, sizeof(dsk_model));
+  if (!m) return DSK_ENOMEM;
+  m->cfg = *cfg;
+  m->elem = elem;
+  m->max_tokens = max_tokens;
+  m->n_qkv = (cfg->n_q_heads + 2 * cfg->n_kv_heads) * cfg->head_dim;
+  m->gu_block = 1;
+  for (int g = 32; g >= 1; g >>= 1)
+    if (cfg->ffn % g == 0) { m->gu_block = g; break; }
+  const int L = cfg->n_layers;
+  const int64_t d = cfg->hidden, nq = (int64_t)cfg->n_q_heads * cfg->head_dim, F = cfg->ffn;
+  int rc = DSK_OK;
+  m->layers = (LayerWeights*)calloc(L, sizeof(LayerWeights));
+  m->ev_kv = (hipEvent_t*)calloc(L, sizeof(hipEvent_t));
+  m->pending = (unsigned char*)calloc(L, 1);
+  if (!m->layers || !m->ev_kv || !m->pending) rc = DSK_ENOMEM;
+  for (int l = 0; l < L && rc == DSK_OK; ++l) {
+    LayerWeights& w = m->layers[l];
+    if ((rc = alloc_dev(&w.g1, d * elem, &m->weight_bytes))) break;
+    if ((rc = alloc_dev(&w.g2, d * elem, &m->weight_bytes))) break;
+    if ((rc = alloc_dev(&w.wqkv, (int64_t)m->n_qkv * d * elem, &m->weight_bytes))) break;
+    if ((rc = alloc_dev(&w.wo, d * nq * elem, &m->weight_bytes))) break;
+    if ((rc = alloc_dev(&w.wgu, 2 * F * d * elem, &m->weight_bytes))) break;
+    if ((rc = alloc_dev(&w.wd, d * F * elem, &m->weight_bytes))) break;
+  }
+  const int64_t T = max_tokens;
+  const int half = cfg->head_dim / 2;
+  if (rc == DSK_OK) rc = alloc_dev(&m->xn, T * d * elem, &m->workspace_bytes);
+  if (rc == DSK_OK) rc = alloc_dev(&m->qkv, T * m->n_qkv * elem, &m->workspace_bytes);
+  if (rc == DSK_OK) rc = alloc_dev(&m->attn, T * nq * elem, &m->workspace_bytes);
+  if (rc == DSK_OK) rc = alloc_dev(&m->gu, T * 2 * F * elem, &m->workspace_bytes);
+  if (rc == DSK_OK) rc = alloc_dev(&m->act, T * F * elem, &m->workspace_bytes);
+  if (rc == DSK_OK) rc = alloc_dev(&m->h, T * d * elem, &m->workspace_bytes);
+  if (rc == DSK_OK) rc = alloc_dev((void**)&m->rope_cs, T * half * (int64_t)sizeof(float2), &m->workspace_bytes);
+  if (rc == DSK_OK) rc = alloc_dev((void**)&m->theta, half * (int64_t)sizeof(double), &m->workspace_bytes);
+  if (rc == DSK_OK) {
+    double* th = (double*)malloc(half * sizeof(double));
+    if (!th) rc = DSK_ENOMEM;
+    else {
+      for (int i = 0; i < half; ++i) th[i] = pow(cfg->rope_base, -2.0 * (double)i / (double)cfg->head_dim);
+      hipError_t e = hipMemcpy(m->theta, th, half * sizeof(double), hipMemcpyHostToDevice);
+      free(th);
+      if (e != hipSuccess) { g_last_hip_error = (int)e; rc = DSK_EHIP; }
+    }
+  }
+  auto hip_ok = [&](hipError_t e) {
+    if (e != hipSuccess && rc == DSK_OK) { g_last_hip_error = (int)e; rc = DSK_EHIP; }
+  };
+  if (rc == DSK_OK) {
+    hip_ok(hipStreamCreateWithFlags(&m->load_stream, hipStreamNonBlocking));
+    hip_ok(hipEventCreateWithFlags(&m->ev_entry, hipEventDisableTiming));
+    hip_ok(hipEventCreateWithFlags(&m->ev_e, hipEventDisableTiming));
+    hip_ok(hipEventCreateWithFlags(&m->ev_all, hipEventDisableTiming));
+    for (int l = 0; l < L; ++l) hip_ok(hipEventCreateWithFlags(&m->ev_kv[l], hipEventDisableTiming));
+  }
+  if (rc != DSK_OK) {
+    free_model(m);
+    return rc;
+  }
+  *out = m;
+  return DSK_OK;
+}
+
+int dsk_model_destroy(dsk_model_t* model) {
+  if (!model) return DSK_EINVAL;
+  (void)hipStreamSynchronize(model->load_stream);
+  (void)hipDeviceSynchronize();
+  free_model(model);
+  return DSK_OK;
+}
+
+int dsk_model_set_tensor(dsk_model_t* model, int layer, int tensor, const void* src, int src_mem, void* stream) {
+  if (!model || !src) return DSK_EINVAL;
+  if (src_mem != DSK_MEM_DEVICE && src_mem != DSK_MEM_HOST_PINNED) return DSK_EINVAL;
+  TensorPlace p;
+  int rc = place_tensor(model, layer, tensor, &p);
+  if (rc) return rc;
+  hipStream_t s = (hipStream_t)stream;
+  const int64_t bytes = p.rows * p.cols * model->elem;
+  if (src_mem == DSK_MEM_DEVICE) {
+    HIP_TRY(launch_pack_rows(model->cfg.dtype, p.base, src, p.rows, p.cols, p.map, model->gu_block, p.row_off, 1, s));
+    return DSK_OK;
+  }
+  // host source: staged through a temporary device buffer; this path waits for the copy to finish
+  void* staging = nullptr;
+  HIP_TRY(hipMalloc(&staging, (size_t)bytes));
+  hipError_t e = hipMemcpy(staging, src, (size_t)bytes, hipMemcpyHostToDevice);
+  if (e == hipSuccess)
+    e = launch_pack_rows(model->cfg.dtype, p.base, staging, p.rows, p.cols, p.map, model->gu_block, p.row_off, 1, s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  (void)hipFree(staging);
+  HIP_TRY(e);
+  return DSK_OK;
+}
+
+int dsk_model_get_tensor(const dsk_model_t* model, int layer, int tensor, void* dst_device, void* stream) {
+  if (!model || !dst_device) return DSK_EINVAL;
+  TensorPlace p;
+  int rc = place_tensor(model, layer, tensor, &p);
+  if (rc) return rc;
+  HIP_TRY(launch_pack_rows(model->cfg.dtype, p.base, dst_device, p.rows, p.cols, p.map, model->gu_block, p.row_off, 0,
+                           (hipStream_t)stream));
+  return DSK_OK;
+}
+
+int dsk_model_init_random(dsk_model_t* model, uint64_t seed, float std, void* stream) {
+  if (!model || !(std >= 0.f)) return DSK_EINVAL;
+  for (int l = 0; l < model->cfg.n_layers; ++l)
+    for (int t = DSK_G1; t <= DSK_WD; ++t) {
+      TensorPlace p;
+      int rc = place_tensor(model, l, t, &p);
+      if (rc) return rc;
+      float offset = (t == DSK_G1 || t == DSK_G2) ? 1.0f : 0.0f;
+      HIP_TRY(launch_fill_weight(model->cfg.dtype, p.base, p.rows, p.cols, p.map, model->gu_block, p.row_off, seed,
+                                 (uint64_t)l * 16 + (uint64_t)t, std, offset, (hipStream_t)stream));
+    }
+  return DSK_OK;
+}
+
+int dsk_fill_normal(void* dst_device, int64_t n, uint64_t seed, uint64_t stream_id, float std, float offset,
+                    int64_t idx0, int dtype, void* stream) {
+  if (!dst_device || n < 0 || idx0 < 0) return DSK_EINVAL;
+  if (dtype != DSK_F32 && dtype != DSK_BF16) return DSK_EDTYPE;
+  HIP_TRY(launch_fill_normal(dst_device, n, seed, stream_id, std, offset, idx0, dtype, (hipStream_t)stream));
+  return DSK_OK;
+}
+
+int dsk_partial_prefill(dsk_model_t* model, const void* hidden_in, int hidden_in_mem, int lo, int hi,
+                        const dsk_kv_t* kv_reused, const dsk_kv_t* kv_out, const dsk_batch_t* batch,
+                        void* hidden_out, uint32_t flags, void* stream) {
+  if (!model || !hidden_in || !kv_out || !batch) return DSK_EINVAL;
+  dsk_model* m = model;
+  const dsk_config_t& c = m->cfg;
+  const int L = c.n_layers;
+  if (!(0 <= lo && lo <= hi && hi <= L)) return DSK_EINVAL;
+  if (hidden_in_mem != DSK_MEM_DEVICE && hidden_in_mem != DSK_MEM_HOST_PINNED) return DSK_EINVAL;
+  if (!aligned16(hidden_in) || !aligned16(hidden_out)) return DSK_EINVAL;
+  if (flags & ~DSK_DEFER_JOIN) return DSK_EINVAL;
+  int rc = check_batch(batch, true);
+  if (rc) return rc;
+  const int T = batch->n_tokens;
+  if (T > m->max_tokens) return DSK_EINVAL;
+  if ((rc = check_kv(m, kv_out, T, true))) return rc;
+  const bool need_reused = (hi - lo) < L;
+  if (need_reused || kv_reused)
+    if ((rc = check_kv(m, kv_reused, T, false))) return rc;
+
+  hipStream_t s = (hipStream_t)stream;
+  hipStream_t ls = m->load_stream;
+  const int64_t row_bytes = (int64_t)c.n_kv_heads * c.head_dim * m->elem;
+  const int64_t hid_bytes = (int64_t)T * c.hidden * m->elem;
+  const bool alias = kv_reused && kv_reused->base == kv_out->base && kv_reused->mem == DSK_MEM_DEVICE &&
+                     kv_reused->layer_stride == kv_out->layer_stride && kv_reused->v_offset == kv_out->v_offset;
+  const hipMemcpyKind kv_kind = (kv_reused && kv_reused->mem == DSK_MEM_HOST_PINNED) ? hipMemcpyHostToDevice : hipMemcpyDeviceToDevice;
+  const int mode = m->load_mode;
+
+  // loads start after everything the caller already enqueued on `stream`
+  HIP_TRY(hipEventRecord(m->ev_entry, s));
+  HIP_TRY(hipStreamWaitEvent(ls, m->ev_entry, 0));
+
+  // the E cache goes first (Fig. 13(c)): recomputation can start as soon as it has arrived
+  const void* h_cur = hidden_in;
+  if (hidden_in_mem == DSK_MEM_HOST_PINNED) {
+    HIP_TRY(hipMemcpyAsync(m->h, hidden_in, (size_t)hid_bytes, hipMemcpyHostToDevice, ls));
+    HIP_TRY(hipEventRecord(m->ev_e, ls));
+    HIP_TRY(hipStreamWaitEvent(s, m->ev_e, 0));
+    h_cur = m->h;
+  }
+
+  // reused layers, ascending (the order the suffix prefill consumes them), one event per layer
+  memset(m->pending, 0, L);
+  m->any_pending = 0;
+  for (int l = 0; l < L; ++l) {
+    const bool recomputed = (l >= lo && l < hi);
+    if (recomputed && mode != DSK_LOAD_ALL_FIRST) continue;
+    if (!kv_reused || alias) continue;
+    const int64_t bytes = (int64_t)T * row_bytes;
+    const bool one_piece = kv_reused->v_offset == bytes && kv_out->v_offset == bytes;
+    if (one_piece) {
+      HIP_TRY(hipMemcpyAsync(kv_k(kv_out, l), kv_k(kv_reused, l), (size_t)(2 * bytes), kv_kind, ls));
+    } else {
+      HIP_TRY(hipMemcpyAsync(kv_k(kv_out, l), kv_k(kv_reused, l), (size_t)bytes, kv_kind, ls));
+      HIP_TRY(hipMemcpyAsync(kv_v(kv_out, l), kv_v(kv_reused, l), (size_t)bytes, kv_kind, ls));
+    }
+    HIP_TRY(hipEventRecord(m->ev_kv[l], ls));
+    m->pending[l] = 1;
+    m->any_pending = 1;
+  }
+  HIP_TRY(hipEventRecord(m->ev_all, ls));
+  if (mode != DSK_LOAD_PIPELINED) HIP_TRY(hipStreamWaitEvent(s, m->ev_all, 0));  // strategies (a), (b): load, then compute
+
+  // recompute [lo, hi) on the compute stream
+  if (hi > lo) {
+    HIP_TRY(launch_rope_table(batch->positions_dev, m->theta, m->rope_cs, T, c.head_dim / 2, s));
+    for (int l = lo; l < hi; ++l) {
+      void* h_next = (l == hi - 1 && hidden_out) ? hidden_out : m->h;
+      rc = run_layer(m, l, h_cur, h_next, kv_k(kv_out, l), kv_v(kv_out, l), 0, batch->cu_seqlens_dev,
+                     batch->cu_seqlens_host, nullptr, batch->n_seqs, T, s);
+      if (rc) return rc;
+      h_cur = h_next;
+    }
+  } else if (hidden_out && hidden_out != h_cur) {
+    HIP_TRY(hipMemcpyAsync(hidden_out, h_cur, (size_t)hid_bytes, hipMemcpyDeviceToDevice, s));
+  }
+
+  if (!(flags & DSK_DEFER_JOIN) || mode != DSK_LOAD_PIPELINED) {
+    HIP_TRY(hipStreamWaitEvent(s, m->ev_all, 0));
+    memset(m->pending, 0, L);
+    m->any_pending = 0;
+  }
+  return DSK_OK;
+}
+
+int dsk_suffix_prefill(dsk_model_t* model, const void* suffix_hidden_in, const dsk_kv_t* kv,
+                       const dsk_batch_t* prefix, const dsk_batch_t* suffix, int64_t suffix_row0,
+                       void* hidden_out, void* stream) {
+  if (!model || !suffix_hidden_in || !kv || !prefix || !suffix || !hidden_out) return DSK_EINVAL;
+  dsk_model* m = model;
+  const dsk_config_t& c = m->cfg;
+  if (!aligned16(suffix_hidden_in) || !aligned16(hidden_out)) return DSK_EINVAL;
+  int rc = check_batch(prefix, false);
+  if (rc) return rc;
+  if ((rc = check_batch(suffix, true))) return rc;
+  if (prefix->n_seqs != suffix->n_seqs) return DSK_EINVAL;
+  const int S = suffix->n_tokens;
+  if (S > m->max_tokens) return DSK_EINVAL;
+  if (suffix_row0 < prefix->n_tokens) return DSK_EINVAL;
+  if ((rc = check_kv(m, kv, suffix_row0 + S, true))) return rc;
+
+  hipStream_t s = (hipStream_t)stream;
+  HIP_TRY(launch_rope_table(suffix->positions_dev, m->theta, m->rope_cs, S, c.head_dim / 2, s));
+  const void* h_cur = suffix_hidden_in;
+  for (int l = 0; l < c.n_layers; ++l) {
+    if (m->pending[l]) {
+      HIP_TRY(hipStreamWaitEvent(s, m->ev_kv[l], 0));
+      m->pending[l] = 0;
+    }
+    void* h_next = (l == c.n_layers - 1) ? hidden_out : m->h;
+    rc = run_layer(m, l, h_cur, h_next, kv_k(kv, l), kv_v(kv, l), suffix_row0, suffix->cu_seqlens_dev,
+                   suffix->cu_seqlens_host, prefix->cu_seqlens_dev, suffix->n_seqs, S, s);
+    if (rc) return rc;
+    h_cur = h_next;
+  }
+  m->any_pending = 0;
+  return DSK_OK;
+}
+
+int dsk_join_loads(dsk_model_t* model, void* stream) {
+  if (!model) return DSK_EINVAL;
+  if (model->any_pending) {
+    HIP_TRY(hipStreamWaitEvent((hipStream_t)stream, model->ev_all, 0));
+    memset(model->pending, 0, model->cfg.n_layers);
+    model->any_pending = 0;
+  }
+  return DSK_OK;
+}
+
+int dsk_set_load_mode(dsk_model_t* model, int load_mode) {
+  if (!model || load_mode < DSK_LOAD_PIPELINED || load_mode > DSK_LOAD_ALL_FIRST) return DSK_EINVAL;
+  model->load_mode = load_mode;
+  return DSK_OK;
+}
+
+int64_t dsk_model_weight_bytes(const dsk_model_t* model) { return model ? model->weight_bytes : 0; }
+int64_t dsk_model_workspace_bytes(const dsk_model_t* model) { return model ? model->workspace_bytes : 0; }
+
+const char* dsk_strerror(int status) {
+  switch (status) {
+    case DSK_OK: return "ok";
+    case DSK_EINVAL: return "invalid argument";
+    case DSK_ESHAPE: return "unsupported model shape";
+    case DSK_EDTYPE: return "unsupported dtype";
+    case DSK_ENOMEM: return "out of memory";
+    case DSK_EHIP: return "HIP call failed";
+    default: return "unknown status";
+  }
+}
+
+int dsk_last_hip_error(void) { return g_last_hip_error; }
+
+}  // extern "C"

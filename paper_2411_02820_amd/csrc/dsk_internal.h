@@ -1,0 +1,96 @@
+// Internal declarations shared by the HIP sources of libdsk (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "dsk.h"
+
+typedef __bf16 bf16_t;
+
+// ---- element conversion (fp32 math everywhere; storage is float or bf16) ----
+__device__ __forceinline__ float to_f32(float x) { return x; }
+__device__ __forceinline__ float to_f32(bf16_t x) { return (float)x; }
+template <typename T> __device__ __forceinline__ T from_f32(float x);
+template <> __device__ __forceinline__ float from_f32<float>(float x) { return x; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float x) { return (bf16_t)x; }  // RNE (v_cvt_pk_bf16_f32)
+
+// ---- packed weight layout ----
+// QKV rows are [Wq; Wk; Wv].  Gate and up rows are interleaved in blocks of gu_block rows:
+// packed rows [2*gu_block*j, 2*gu_block*j+gu_block) hold gate rows [gu_block*j, ..+gu_block),
+// the next gu_block packed rows hold the same up rows, so that a GEMM tile owns gate and up of
+// the same FFN index.
+struct LayerWeights {
+  void* g1;
+  void* wqkv;  // [(Hq+2Hkv)*dh, d]
+  void* wo;    // [d, Hq*dh]
+  void* g2;
+  void* wgu;   // [2F, d] interleaved
+  void* wd;    // [d, F]
+};
+
+struct dsk_model {
+  dsk_config_t cfg;
+  int elem;         // bytes per element
+  int64_t max_tokens;
+  int gu_block;
+  int n_qkv;        // (Hq+2Hkv)*dh
+  LayerWeights* layers;
+  int64_t weight_bytes;
+  // workspace
+  void* xn;         // [maxT, d]      normalised activations
+  void* qkv;        // [maxT, n_qkv]
+  void* attn;       // [maxT, Hq*dh]
+  void* gu;         // [maxT, 2F]
+  void* act;        // [maxT, F]
+  void* h;          // [maxT, d]      residual stream
+  float2* rope_cs;  // [maxT, dh/2]   cos, sin
+  double* theta;    // [dh/2]         rope_base^(-2i/dh)
+  int64_t workspace_bytes;
+  // load pipeline
+  hipStream_t load_stream;
+  hipEvent_t ev_entry, ev_e, ev_all;
+  hipEvent_t* ev_kv;        // [L]
+  unsigned char* pending;   // [L] 1 if ev_kv[l] must be waited for by the suffix
+  int any_pending;
+  int load_mode;
+};
+
+// epilogues of the GEMM family
+enum { EPI_STORE = 0, EPI_RESIDUAL = 1 };
+
+// ---- launchers (each validates nothing: the C-ABI layer has checked shapes) ----
+// C[M,N] = A[M,K] * W[N,K]^T (+ R[M,N] when epi == EPI_RESIDUAL); row strides in elements.
+hipError_t launch_gemm_generic(int dtype, const void* A, int64_t lda, const void* W, int64_t ldw, void* C, int64_t ldc,
+                               const void* R, int64_t ldr, int M, int N, int K, int epi, hipStream_t s);
+// bf16 MFMA GEMM; returns hipErrorNotSupported when the shape is outside what it handles.
+hipError_t launch_gemm_mfma_bf16(const void* A, int64_t lda, const void* W, int64_t ldw, void* C, int64_t ldc,
+                                 const void* R, int64_t ldr, int M, int N, int K, int epi, hipStream_t s);
+
+hipError_t launch_rmsnorm(int dtype, const void* x, const void* g, void* y, int T, int d, float eps, hipStream_t s);
+hipError_t launch_rope_table(const int32_t* pos, const double* theta, float2* cs, int T, int half, hipStream_t s);
+// rotates q (in place) and k of qkv [T, n_qkv]; writes rotated k and v to the cache rows row0..row0+T-1
+hipError_t launch_rope_kv_write(int dtype, void* qkv, const float2* cs, void* k_rows, void* v_rows, int T, int Hq,
+                                int Hkv, int dh, hipStream_t s);
+// act[t,f] = silu(gate) * up from the interleaved gate/up GEMM output gu [T, 2F]
+hipError_t launch_swiglu(int dtype, const void* gu, void* act, int T, int F, int gu_block, hipStream_t s);
+
+// Causal grouped-query attention over packed sequences.  Query token i of sequence b (rows q_cu[b]..)
+// sees cache rows p_cu[b] .. p_cu[b+1]-1 (all of them; p_cu may be NULL: no such segment) and rows
+// own_row0 + q_cu[b] .. own_row0 + i.  q rows have stride ldq elements, out rows Hq*dh.
+struct AttnArgs {
+  const void* q; int64_t ldq;
+  const void* k_rows; const void* v_rows;  // layer base of K and V rows (row stride Hkv*dh)
+  void* out;
+  const int32_t* q_cu; const int32_t* p_cu; const int32_t* q_cu_host; int n_seqs;
+  int64_t own_row0; int n_q; int Hq, Hkv, dh;
+};
+hipError_t launch_attn_generic(int dtype, const AttnArgs& a, hipStream_t s);
+hipError_t launch_attn_mfma_bf16(const AttnArgs& a, hipStream_t s);
+
+hipError_t launch_fill_normal(void* dst, int64_t n, uint64_t seed, uint64_t stream_id, float std, float offset,
+                              int64_t idx0, int dtype, hipStream_t s);
+// weight (re)packing: logical tensor rows <-> packed rows.  map: 0 identity + row_off, 1 gate rows, 2 up rows.
+hipError_t launch_pack_rows(int dtype, void* packed, const void* logical, int64_t rows, int64_t cols, int map,
+                            int gu_block, int64_t row_off, int to_packed, hipStream_t s);
+hipError_t launch_fill_weight(int dtype, void* packed, int64_t rows, int64_t cols, int map, int gu_block, int64_t row_off,
+                              uint64_t seed, uint64_t stream_id, float std, float offset, hipStream_t s);

@@ -1,0 +1,129 @@
+// Memory-bound pieces of the decoder layer: RMSNorm, rotary table, RoPE + KV-cache write, SwiGLU.
+// All arithmetic in fp32 (the rotary angle in fp64); storage type T is float or bf16.
+#include "dsk_internal.h"
+
+namespace {
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+// y = x * rsqrt(mean(x^2) + eps) * g, one 256-thread block per token row.
+template <typename T>
+__global__ void __launch_bounds__(256) rmsnorm_kernel(const T* __restrict__ x, const T* __restrict__ g, T* __restrict__ y,
+                                                      int d, float eps) {
+  __shared__ float part[4];
+  const T* xr = x + (int64_t)blockIdx.x * d;
+  T* yr = y + (int64_t)blockIdx.x * d;
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < d; i += 256) {
+    float v = to_f32(xr[i]);
+    ss += v * v;
+  }
+  ss = wave_sum(ss);
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  float tot = part[0] + part[1] + part[2] + part[3];
+  float r = 1.0f / sqrtf(tot / (float)d + eps);
+  for (int i = threadIdx.x; i < d; i += 256) yr[i] = from_f32<T>(to_f32(xr[i]) * r * to_f32(g[i]));
+}
+
+// cos/sin of position * theta_i, angle and sincos in fp64, stored as fp32.
+__global__ void rope_table_kernel(const int32_t* __restrict__ pos, const double* __restrict__ theta,
+                                  float2* __restrict__ cs, int T, int half) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (int64_t)T * half) return;
+  int t = (int)(i / half), j = (int)(i - (int64_t)t * half);
+  double s, c;
+  sincos((double)pos[t] * theta[j], &s, &c);
+  cs[i] = make_float2((float)c, (float)s);
+}
+
+// One block per token.  q and k heads: pair (i, i+dh/2) rotated; rotated k and v go to the cache rows.
+template <typename T>
+__global__ void __launch_bounds__(256) rope_kv_write_kernel(T* __restrict__ qkv, const float2* __restrict__ cs,
+                                                            T* __restrict__ k_rows, T* __restrict__ v_rows, int Hq,
+                                                            int Hkv, int dh) {
+  const int t = blockIdx.x;
+  const int half = dh >> 1;
+  const int n_qkv = (Hq + 2 * Hkv) * dh;
+  T* row = qkv + (int64_t)t * n_qkv;
+  const float2* csr = cs + (int64_t)t * half;
+  T* kr = k_rows + (int64_t)t * Hkv * dh;
+  T* vr = v_rows + (int64_t)t * Hkv * dh;
+  const int n_pairs = (Hq + Hkv) * half;
+  for (int p = threadIdx.x; p < n_pairs; p += 256) {
+    int head = p / half, i = p - head * half;
+    float2 c = csr[i];
+    T* hp = row + head * dh;
+    float x1 = to_f32(hp[i]), x2 = to_f32(hp[i + half]);
+    T y1 = from_f32<T>(x1 * c.x - x2 * c.y);
+    T y2 = from_f32<T>(x2 * c.x + x1 * c.y);
+    if (head < Hq) {
+      hp[i] = y1;
+      hp[i + half] = y2;
+    } else {
+      T* kp = kr + (head - Hq) * dh;
+      kp[i] = y1;
+      kp[i + half] = y2;
+    }
+  }
+  const T* vsrc = row + (Hq + Hkv) * dh;
+  for (int e = threadIdx.x; e < Hkv * dh; e += 256) vr[e] = vsrc[e];
+}
+
+template <typename T>
+__global__ void swiglu_kernel(const T* __restrict__ gu, T* __restrict__ act, int64_t n, int F, int gu_block) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) {
+    int64_t t = i / F;
+    int f = (int)(i - t * F);
+    int pg = (f / gu_block) * 2 * gu_block + (f % gu_block);
+    const T* r = gu + t * 2 * F;
+    float g = to_f32(r[pg]), u = to_f32(r[pg + gu_block]);
+    act[i] = from_f32<T>(g / (1.0f + __expf(-g)) * u);
+  }
+}
+
+}  // namespace
+
+hipError_t launch_rmsnorm(int dtype, const void* x, const void* g, void* y, int T, int d, float eps, hipStream_t s) {
+  if (T <= 0) return hipSuccess;
+  if (dtype == DSK_F32)
+    hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(T), dim3(256), 0, s, (const float*)x, (const float*)g, (float*)y, d, eps);
+  else
+    hipLaunchKernelGGL(rmsnorm_kernel<bf16_t>, dim3(T), dim3(256), 0, s, (const bf16_t*)x, (const bf16_t*)g, (bf16_t*)y, d, eps);
+  return hipGetLastError();
+}
+
+hipError_t launch_rope_table(const int32_t* pos, const double* theta, float2* cs, int T, int half, hipStream_t s) {
+  if (T <= 0) return hipSuccess;
+  int64_t n = (int64_t)T * half;
+  hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, pos, theta, cs, T, half);
+  return hipGetLastError();
+}
+
+hipError_t launch_rope_kv_write(int dtype, void* qkv, const float2* cs, void* k_rows, void* v_rows, int T, int Hq,
+                                int Hkv, int dh, hipStream_t s) {
+  if (T <= 0) return hipSuccess;
+  if (dtype == DSK_F32)
+    hipLaunchKernelGGL(rope_kv_write_kernel<float>, dim3(T), dim3(256), 0, s, (float*)qkv, cs, (float*)k_rows, (float*)v_rows, Hq, Hkv, dh);
+  else
+    hipLaunchKernelGGL(rope_kv_write_kernel<bf16_t>, dim3(T), dim3(256), 0, s, (bf16_t*)qkv, cs, (bf16_t*)k_rows, (bf16_t*)v_rows, Hq, Hkv, dh);
+  return hipGetLastError();
+}
+
+hipError_t launch_swiglu(int dtype, const void* gu, void* act, int T, int F, int gu_block, hipStream_t s) {
+  int64_t n = (int64_t)T * F;
+  if (n <= 0) return hipSuccess;
+  int64_t b = (n + 255) / 256;
+  if (b > 256 * 32) b = 256 * 32;
+  if (dtype == DSK_F32)
+    hipLaunchKernelGGL(swiglu_kernel<float>, dim3((unsigned)b), dim3(256), 0, s, (const float*)gu, (float*)act, n, F, gu_block);
+  else
+    hipLaunchKernelGGL(swiglu_kernel<bf16_t>, dim3((unsigned)b), dim3(256), 0, s, (const bf16_t*)gu, (bf16_t*)act, n, F, gu_block);
+  return hipGetLastError();
+}

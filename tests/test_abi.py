@@ -1,0 +1,35 @@
+"""The C-ABI library loads and exports every symbol include/dsk.h declares (no GPU needed)."""
+import ctypes
+import os
+import re
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "dsk.h")).read()
+    return re.findall(r"DSK_API\s+[\w\s\*]+?\b(dsk_\w+)\s*\(", text)
+
+
+def test_header_declares_the_path():
+    names = declared_symbols()
+    for required in ("dsk_model_create", "dsk_partial_prefill", "dsk_suffix_prefill"):
+        assert required in names
+    assert len(names) == len(set(names)) >= 10
+
+
+def test_library_exports_every_declared_symbol():
+    from paper_2411_02820_amd import binding as B
+    lib = ctypes.CDLL(B.LIB_PATH)
+    for name in declared_symbols():
+        assert hasattr(lib, name), name
+    assert set(declared_symbols()) == set(B.EXPORTS)
+
+
+def test_error_strings_without_gpu():
+    from paper_2411_02820_amd import binding as B
+    assert B.lib.dsk_strerror(B.DSK_OK) == b"ok"
+    assert B.lib.dsk_strerror(B.DSK_EINVAL) == b"invalid argument"
+    # null arguments are rejected before any device call
+    assert B.lib.dsk_model_create(None, 1, None) == B.DSK_EINVAL
+    assert B.lib.dsk_partial_prefill(None, None, 0, 0, 0, None, None, None, None, 0, None) == B.DSK_EINVAL

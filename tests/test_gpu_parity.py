@@ -1,0 +1,243 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, element by element.
+
+Bars: KV splice, layer indexing and generated data bit-exact; K/V and hidden states within
+max|gpu-ref|/max|ref| <= 1e-3 (fp32 model) or 2e-2 (bf16 model)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dsk_oracle as O
+from paper_2411_02820_amd import synth
+from tests.helpers import kv_list, oracle_config, weights_fn
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-3, "bf16": 2e-2}
+
+SMALL_BF16 = synth.ModelShape(3, 512, 8, 2, 128, 1536, 500000.0, 1e-5, "bf16")
+SMALL_BF16_DH64 = synth.ModelShape(2, 256, 4, 4, 64, 512, 10000.0, 1e-5, "bf16")
+
+
+@pytest.fixture(scope="module")
+def G():
+    from tests import gpu_util
+    return gpu_util
+
+
+def scaled_weights(shape, seed, scale):
+    base = weights_fn(shape, seed)
+    if scale is None:
+        return base
+
+    def get(l):
+        w = dict(base(l))
+        for k in ("wq", "wk", "wv", "wo", "wg", "wu", "wd"):
+            w[k] = (w[k].astype(np.float32) * np.float32(scale)).astype(np.float64)
+        return w
+    return get
+
+
+def run_case(G, shape, lens, lo, hi, slens, scale, pinned_kv=False, pinned_e=False):
+    tol = TOL[shape.dtype]
+    cfg = oracle_config(shape)
+    cu = synth.cu_seqlens(lens)
+    T = int(cu[-1])
+    S = int(sum(slens)) if slens else 0
+    pos = synth.packed_positions(lens)
+    hidden_in = synth.hidden_states(shape, T)
+    kv_r = synth.kv_cache(shape, T)
+    w = scaled_weights(shape, synth.SEED_RECEIVER, scale)
+
+    with G.GpuModel(shape, max(T, S, 1)) as m:
+        m.load_from_generator(synth.SEED_RECEIVER, scale=scale)
+        kv_out, h_out = m.partial(G.to_dev(hidden_in, shape, pinned=pinned_e), lo, hi,
+                                  G.to_dev(kv_r, shape, pinned=pinned_kv), lens, n_rows=T + S)
+        torch.cuda.synchronize()
+        kv_gpu, h_gpu = G.to_np(kv_out), G.to_np(h_out)
+
+        kv_ref, h_ref = O.partial_prefill(cfg, w, hidden_in.astype(np.float64), lo, hi, kv_list(kv_r), pos, cu)
+        for l in range(shape.n_layers):
+            if lo <= l < hi:
+                assert O.max_rel_err(kv_gpu[l, 0, :T], kv_ref[l][0]) <= tol, f"K layer {l}"
+                assert O.max_rel_err(kv_gpu[l, 1, :T], kv_ref[l][1]) <= tol, f"V layer {l}"
+            else:  # splice: bit-exact
+                assert np.array_equal(kv_gpu[l, :, :T], kv_r[l]), f"splice layer {l}"
+            assert np.isnan(kv_gpu[l, :, T:]).all(), "rows beyond the prefix must stay untouched"
+        assert O.max_rel_err(h_gpu, h_ref) <= tol, "hidden_out"
+
+        if S:
+            xs = synth.hidden_states(shape, S, seed=synth.SEED_SUFFIX)
+            hs_out = m.suffix(G.to_dev(xs, shape), kv_out, lens, slens)
+            torch.cuda.synchronize()
+            kv_gpu2, hs_gpu = G.to_np(kv_out), G.to_np(hs_out)
+            kv_mixed = kv_ref   # the oracle's own mixed cache: spliced layers + its fresh layers
+            spos = synth.packed_positions(slens, start=lens)
+            kv_s, hs_ref = O.suffix_prefill(cfg, w, xs.astype(np.float64), kv_mixed, spos, cu, synth.cu_seqlens(slens))
+            assert np.array_equal(kv_gpu2[:, :, :T], kv_gpu[:, :, :T]), "suffix must not touch prefix rows"
+            for l in range(shape.n_layers):
+                assert O.max_rel_err(kv_gpu2[l, 0, T:], kv_s[l][0]) <= tol, f"suffix K layer {l}"
+                assert O.max_rel_err(kv_gpu2[l, 1, T:], kv_s[l][1]) <= tol, f"suffix V layer {l}"
+            assert O.max_rel_err(hs_gpu, hs_ref) <= tol, "suffix hidden_out"
+
+
+def test_config1_tiny_fp32(G):
+    # 4 layers, d 256, 4/2 heads, dh 64, F 688, prefix 128, recompute [1,3), suffix 16
+    run_case(G, synth.TINY, [128], 1, 3, [16], None)
+
+
+def test_tiny_fp32_strong_weights(G):
+    # weights scaled so that softmax and silu are far from their linear regime
+    run_case(G, synth.TINY, [128], 1, 3, [16], 8.0)
+
+
+def test_tiny_fp32_ragged(G):
+    run_case(G, synth.TINY, [70, 1, 129, 37], 0, 2, [3, 1, 16, 5], 8.0)
+
+
+def test_tiny_fp32_full_and_last_layer(G):
+    run_case(G, synth.TINY, [97], 0, 4, [5], 8.0)
+    run_case(G, synth.TINY, [97], 3, 4, [5], 8.0)
+
+
+def test_tiny_fp32_pinned_host_sources(G):
+    run_case(G, synth.TINY, [130], 1, 3, [4], 8.0, pinned_kv=True, pinned_e=True)
+
+
+def test_small_bf16(G):
+    run_case(G, SMALL_BF16, [333], 1, 3, [17], None)
+
+
+def test_small_bf16_strong_weights_ragged(G):
+    run_case(G, SMALL_BF16, [200, 1, 77, 300], 0, 2, [9, 1, 33, 2], 4.0)
+
+
+def test_small_bf16_dh64(G):
+    run_case(G, SMALL_BF16_DH64, [257, 64], 0, 2, [31, 2], 8.0)
+
+
+def test_pure_splice_and_aliasing(G):
+    shape = synth.TINY
+    T = 50
+    hidden_in = synth.hidden_states(shape, T)
+    kv_r = synth.kv_cache(shape, T)
+    with G.GpuModel(shape, T) as m:
+        m.load_from_generator(0)
+        for lo in (0, 2, 4):
+            kv_out, h_out = m.partial(G.to_dev(hidden_in, shape), lo, lo, G.to_dev(kv_r, shape), [T])
+            torch.cuda.synchronize()
+            assert np.array_equal(G.to_np(kv_out), kv_r)
+            assert np.array_equal(G.to_np(h_out), hidden_in)
+        # aliasing: kv_out is kv_reused; only the recomputed layers change
+        kv = G.to_dev(kv_r, shape)
+        m.partial(G.to_dev(hidden_in, shape), 1, 2, kv, [T], kv_out=kv)
+        torch.cuda.synchronize()
+        got = G.to_np(kv)
+        assert np.array_equal(got[[0, 2, 3]], kv_r[[0, 2, 3]])
+        assert not np.array_equal(got[1], kv_r[1])
+
+
+def test_composition_is_bit_exact_on_device(G):
+    # partial(lo,m) then partial(m,hi) chained through hidden_out == partial(lo,hi): the path is deterministic
+    shape = SMALL_BF16
+    lens = [150, 43]
+    T = sum(lens)
+    hidden_in = G.to_dev(synth.hidden_states(shape, T), shape)
+    kv_r = G.to_dev(synth.kv_cache(shape, T), shape)
+    with G.GpuModel(shape, T) as m:
+        m.load_from_generator(0, scale=4.0)
+        kv_a, h_a = m.partial(hidden_in, 0, 3, kv_r, lens)
+        kv_1, h_1 = m.partial(hidden_in, 0, 1, kv_r, lens)
+        kv_2, h_2 = m.partial(h_1, 1, 3, kv_1, lens)
+        torch.cuda.synchronize()
+        assert torch.equal(h_a, h_2)
+        assert torch.equal(kv_a, kv_2)
+
+
+def test_load_strategies_give_identical_results(G):
+    from paper_2411_02820_amd import binding as B
+    shape = synth.TINY
+    T = 64
+    hidden_in = G.to_dev(synth.hidden_states(shape, T), shape)
+    kv_r = G.to_dev(synth.kv_cache(shape, T), shape, pinned=True)
+    with G.GpuModel(shape, T) as m:
+        m.load_from_generator(0, scale=8.0)
+        outs = []
+        for mode in (B.DSK_LOAD_PIPELINED, B.DSK_LOAD_REUSED_FIRST, B.DSK_LOAD_ALL_FIRST):
+            B.dsk_set_load_mode(m.handle, mode)
+            kv_out, h_out = m.partial(hidden_in, 1, 3, kv_r, [T])
+            torch.cuda.synchronize()
+            outs.append((kv_out.clone(), h_out.clone()))
+        for kv_out, h_out in outs[1:]:
+            assert torch.equal(kv_out, outs[0][0]) and torch.equal(h_out, outs[0][1])
+
+
+def test_deferred_join_then_suffix(G):
+    from paper_2411_02820_amd import binding as B
+    shape = synth.TINY
+    T, S = 96, 8
+    hidden_in = G.to_dev(synth.hidden_states(shape, T), shape)
+    kv_r = G.to_dev(synth.kv_cache(shape, T), shape, pinned=True)
+    xs = G.to_dev(synth.hidden_states(shape, S, seed=synth.SEED_SUFFIX), shape)
+    with G.GpuModel(shape, T) as m:
+        m.load_from_generator(0, scale=8.0)
+        kv_a, _ = m.partial(hidden_in, 1, 3, kv_r, [T], n_rows=T + S)
+        h_a = m.suffix(xs, kv_a, [T], [S])
+        kv_b, _ = m.partial(hidden_in, 1, 3, kv_r, [T], n_rows=T + S, flags=B.DSK_DEFER_JOIN)
+        h_b = m.suffix(xs, kv_b, [T], [S])
+        kv_c, _ = m.partial(hidden_in, 1, 3, kv_r, [T], n_rows=T + S, flags=B.DSK_DEFER_JOIN)
+        B.dsk_join_loads(m.handle)
+        torch.cuda.synchronize()
+        assert torch.equal(h_a, h_b)
+        assert torch.equal(kv_a[:, :, :T], kv_c[:, :, :T])
+        assert torch.equal(kv_a, kv_b)
+
+
+def test_generator_bit_exact(G):
+    from paper_2411_02820_amd import binding as B
+    for dtype, tdt, code in (("f32", torch.float32, B.DSK_F32), ("bf16", torch.bfloat16, B.DSK_BF16)):
+        n = 100003
+        for (seed, stream, std, offset, idx0) in ((0, 5, 0.02, 0.0, 0), (9, 1 << 40, 1.0, 1.0, 12345678901)):
+            out = torch.empty(n, dtype=tdt, device="cuda")
+            B.dsk_fill_normal(out, n, seed, stream, std, offset, idx0, code)
+            torch.cuda.synchronize()
+            ref = synth.normal(n, seed, stream, std, offset, dtype, idx0)
+            assert np.array_equal(out.float().cpu().numpy(), ref)
+
+
+@pytest.mark.parametrize("shape", [synth.TINY, SMALL_BF16])
+def test_init_random_matches_host_generator(G, shape):
+    with G.GpuModel(shape, 16) as m:
+        m.init_random(3)
+        for l in (0, shape.n_layers - 1):
+            for kind in range(9):
+                got = m.get_tensor(l, kind).float().cpu().numpy()
+                assert np.array_equal(got, synth.layer_tensor(shape, 3, l, kind)), (l, kind)
+        # set_tensor -> get_tensor round trip through the packed layout
+        m.load_from_generator(7, layers=[1])
+        for kind in range(9):
+            assert np.array_equal(m.get_tensor(1, kind).float().cpu().numpy(), synth.layer_tensor(shape, 7, 1, kind))
+
+
+def test_argument_errors(G):
+    from paper_2411_02820_amd import binding as B
+    shape = synth.TINY
+    T = 8
+    with G.GpuModel(shape, T) as m:
+        h = G.to_dev(synth.hidden_states(shape, T), shape)
+        kv = G.to_dev(synth.kv_cache(shape, T), shape)
+        for lo, hi in ((-1, 2), (3, 2), (0, 5)):
+            with pytest.raises(B.DskError) as e:
+                m.partial(h, lo, hi, kv, [T])
+            assert e.value.status == B.DSK_EINVAL
+        with pytest.raises(B.DskError):   # more tokens than the workspace holds
+            m.partial(G.to_dev(synth.hidden_states(shape, 2 * T), shape), 0, 1, G.to_dev(synth.kv_cache(shape, 2 * T), shape), [2 * T])
+        with pytest.raises(B.DskError):   # cache smaller than the batch
+            m.partial(h, 0, 1, kv, [T], kv_out=m.new_cache(T - 1))
+        with pytest.raises(B.DskError):   # reused cache required when some layer is reused
+            m.partial(h, 0, 1, None, [T])
+        m.partial(h, 0, 4, None, [T])     # full prefill needs none
+        torch.cuda.synchronize()
+    bad = synth.ModelShape(2, 64, 6, 4, 16, 64, 1e4, 1e-5, "f32")
+    with pytest.raises(B.DskError) as e:
+        B.dsk_model_create(B.config_from_shape(bad), 8)
+    assert e.value.status == B.DSK_ESHAPE
