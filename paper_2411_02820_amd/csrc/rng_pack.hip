@@ -34,10 +34,11 @@ __device__ __forceinline__ uint32_t lane_sum(uint64_t a) {
 }
 
 __device__ __forceinline__ float ih8(uint64_t key, uint64_t idx, float scale, float offset) {
+#pragma clang fp contract(off)  // the multiply and the add round separately, as the definition says
   uint64_t c = key + (2 * idx) * kG;
   uint32_t s = lane_sum(mix64(c)) + lane_sum(mix64(c + kG));
-  float v = __fmul_rn((float)((int)s - 262140), scale);
-  if (offset != 0.0f) v = __fadd_rn(v, offset);
+  float v = (float)((int)s - 262140) * scale;
+  if (offset != 0.0f) v = v + offset;
   return v;
 }
 

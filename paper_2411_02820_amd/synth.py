@@ -65,7 +65,8 @@ def stream_key(seed: int, stream: int) -> int:
 
 
 def scale_for_std(std: float) -> np.float32:
-    return np.float32(std / LANE_SUM_STD)
+    # std enters as an fp32 value (the C ABI takes a float), the division is done in double
+    return np.float32(float(np.float32(std)) / LANE_SUM_STD)
 
 
 def _mix64(z: np.ndarray) -> np.ndarray:

@@ -108,11 +108,11 @@ def test_small_bf16(G):
 
 
 def test_small_bf16_strong_weights_ragged(G):
-    run_case(G, SMALL_BF16, [200, 1, 77, 300], 0, 2, [9, 1, 33, 2], 4.0)
+    run_case(G, SMALL_BF16, [200, 1, 77, 300], 0, 2, [9, 1, 33, 2], 2.0)
 
 
 def test_small_bf16_dh64(G):
-    run_case(G, SMALL_BF16_DH64, [257, 64], 0, 2, [31, 2], 8.0)
+    run_case(G, SMALL_BF16_DH64, [257, 64], 0, 2, [31, 2], 2.0)
 
 
 def test_pure_splice_and_aliasing(G):
@@ -144,7 +144,7 @@ def test_composition_is_bit_exact_on_device(G):
     hidden_in = G.to_dev(synth.hidden_states(shape, T), shape)
     kv_r = G.to_dev(synth.kv_cache(shape, T), shape)
     with G.GpuModel(shape, T) as m:
-        m.load_from_generator(0, scale=4.0)
+        m.load_from_generator(0, scale=2.0)
         kv_a, h_a = m.partial(hidden_in, 0, 3, kv_r, lens)
         kv_1, h_1 = m.partial(hidden_in, 0, 1, kv_r, lens)
         kv_2, h_2 = m.partial(h_1, 1, 3, kv_1, lens)
