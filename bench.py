@@ -1,0 +1,227 @@
+#!/usr/bin/env python3
+"""Benchmark of the selective-layer prefill hot path on one MI355X.
+
+One step = one pass of the whole path on one batch: dsk_partial_prefill (recompute layers [lo,hi)
+from the sender's E cache while the other layers' KV is spliced in on the side stream) followed by
+dsk_suffix_prefill (the new tokens through all layers against the mixed cache).  Inputs are
+synthetic and resident in HBM before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 8b-8k|8b-4k|70b-8k|tiny]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
+
+WORKLOADS = {
+    # name: (shape name, prefix tokens, lo, hi, suffix tokens)
+    "8b-8k": ("LLAMA_8B", 8192, 8, 16, 64),    # the point the headline metric is quoted on
+    "8b-4k": ("LLAMA_8B", 4096, 8, 16, 64),    # config 2
+    "70b-8k": ("LLAMA_70B", 8192, 20, 36, 64),  # config 5
+    "tiny": ("TINY", 128, 1, 3, 16),           # config 1
+}
+
+
+def recompute_flops(shape, T, n_layers):
+    """Algorithmic flops of recomputing n_layers over one T-token prefix (MAC = 2, attention causal)."""
+    d, hq, hkv, dh, f = shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.ffn
+    gemm = 2.0 * T * (d * (hq + 2 * hkv) * dh + hq * dh * d + 3 * d * f)
+    attn = 2.0 * hq * dh * T * (T + 1)
+    return n_layers * (gemm + attn)
+
+
+def time_region(torch, fn, reps):
+    s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    s.record()
+    for _ in range(reps):
+        fn()
+    e.record()
+    torch.cuda.synchronize()
+    return s.elapsed_time(e) / reps
+
+
+def cpu_baseline(shape, lo, hi):
+    """The oracle, as it stands, on a bounded sample: ONE decoder layer of the workload's shape over a
+    truncated prefix, on the host cores; scaled to the metric's unit (tokens/s for hi-lo layers)."""
+    import numpy as np
+    from oracle import dsk_oracle as O
+    from paper_2411_02820_amd import synth
+    n_tok = 128 if shape.hidden <= 4096 else 64
+    if shape.hidden <= 256:
+        n_tok = 128
+    cfg = O.Config(shape.n_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.ffn,
+                   shape.rope_base, shape.rms_eps)
+    w = {k: v.astype(np.float64) for k, v in synth.layer_weights(shape, synth.SEED_RECEIVER, lo).items()}
+    x = synth.hidden_states(shape, n_tok).astype(np.float64)
+    t0 = time.perf_counter()
+    O.prefix_layer(cfg, w, x, np.arange(n_tok), np.array([0, n_tok]))
+    dt = time.perf_counter() - t0
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    return {"value": n_tok / (dt * (hi - lo)), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"one {shape.hidden}-wide decoder layer (fp64 numpy oracle) over a {n_tok}-token prefix, "
+                      f"{dt:.2f} s; scaled by 1/{hi - lo} layers"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="8b-8k", choices=sorted(WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-full-prefill", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (no sharding or collectives); use --gpus 1")
+
+    import torch
+    from paper_2411_02820_amd import binding as B
+    from paper_2411_02820_amd import synth
+
+    shape_name, T, lo, hi, S = WORKLOADS[args.workload]
+    shape = getattr(synth, shape_name)
+    L = shape.n_layers
+    tdt = torch.float32 if shape.dtype == "f32" else torch.bfloat16
+    code = B.DSK_F32 if shape.dtype == "f32" else B.DSK_BF16
+    dev = "cuda"
+    cfg = B.config_from_shape(shape)
+    rows = T + S
+
+    def new_cache():
+        return torch.empty((L, 2, rows, shape.n_kv_heads, shape.head_dim), dtype=tdt, device=dev)
+
+    prefix = B.Batch([0, T], synth.packed_positions([T]))
+    suffix = B.Batch([0, S], synth.packed_positions([S], start=[T]))
+    hidden_in = torch.empty((T, shape.hidden), dtype=tdt, device=dev)
+    kv_sender = new_cache()
+
+    # ---- sender (seed 1): its KV for all layers and its hidden state entering layer lo (Sec. 4.1) ----
+    sender_fits = shape.hidden <= 4096
+    if sender_fits:
+        sender = B.dsk_model_create(cfg, T, rows)
+        B.dsk_model_init_random(sender, synth.SEED_SENDER, synth.WEIGHT_STD)
+        x0 = torch.empty((T, shape.hidden), dtype=tdt, device=dev)
+        B.dsk_fill_normal(x0, x0.numel(), synth.SEED_HIDDEN, 0, 1.0, 0.0, 0, code)
+        B.dsk_partial_prefill(sender, x0, 0, L, None, B.kv_desc(kv_sender), prefix.desc, None)
+        if lo > 0:
+            # layers [0, lo) again, in place (the path is deterministic), to obtain the state entering layer lo
+            B.dsk_partial_prefill(sender, x0, 0, lo, B.kv_desc(kv_sender), B.kv_desc(kv_sender), prefix.desc, hidden_in)
+        else:
+            hidden_in.copy_(x0)
+        torch.cuda.synchronize()
+        B.dsk_model_destroy(sender)
+        del x0
+        data = "synthetic: random-init receiver (seed 0); reused KV and E cache from a random-init sender (seed 1) prefill"
+    else:  # two 137 GB models do not fit: N(0,1) tensors stand in for the sender's caches
+        B.dsk_fill_normal(hidden_in, hidden_in.numel(), synth.SEED_HIDDEN, 0, 1.0, 0.0, 0, code)
+        B.dsk_fill_normal(kv_sender, kv_sender.numel(), synth.SEED_KV, 0, 1.0, 0.0, 0, code)
+        data = "synthetic: random-init receiver (seed 0); reused KV and E cache ~N(0,1)"
+    torch.cuda.empty_cache()
+
+    model = B.dsk_model_create(cfg, T, rows)
+    B.dsk_model_init_random(model, synth.SEED_RECEIVER, synth.WEIGHT_STD)
+    weights_gb = B.dsk_model_weight_bytes(model) / 1e9
+    kv_out = new_cache()
+    xs = torch.empty((S, shape.hidden), dtype=tdt, device=dev)
+    B.dsk_fill_normal(xs, xs.numel(), synth.SEED_SUFFIX, 0, 1.0, 0.0, 0, code)
+    hs_out = torch.empty_like(xs)
+    kv_r, kv_o = B.kv_desc(kv_sender), B.kv_desc(kv_out)
+    torch.cuda.synchronize()
+
+    def partial(a=lo, b=hi):
+        B.dsk_partial_prefill(model, hidden_in, a, b, kv_r, kv_o, prefix.desc, None, B.DSK_DEFER_JOIN)
+
+    def suffix_pass():
+        B.dsk_suffix_prefill(model, xs, kv_o, prefix.desc, suffix.desc, T, hs_out)
+
+    def step():
+        partial()
+        suffix_pass()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly K steps; the library brackets its prefill GEMM launches with HIP events ----
+    B.dsk_set_option("reset_stats", 0)
+    B.dsk_set_option("time_gemm", 1)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    B.dsk_set_option("time_gemm", 0)
+    ms_per_step = wall * 1e3 / args.steps
+    gemm_ms = B.dsk_get_stat("timed_gemm_ms")
+    gemm_n = B.dsk_get_stat("timed_gemm_launches")
+    gemm_flops = B.dsk_get_stat("timed_gemm_flops")
+
+    # ---- phase split, full-prefill comparison (outside the timed region) ----
+    def partial_joined():
+        partial()
+        B.dsk_join_loads(model)
+    t_partial = time_region(torch, partial_joined, max(2, args.steps // 2))
+    t_suffix = time_region(torch, suffix_pass, max(2, args.steps // 2))
+    extra = {}
+    if not args.no_full_prefill:
+        def full():
+            B.dsk_partial_prefill(model, hidden_in, 0, L, None, kv_o, prefix.desc, None, 0)
+        full()
+        t_full = time_region(torch, full, 2)
+        extra["full_prefill_ms"] = round(t_full, 3)
+        extra["speedup_vs_full_prefill"] = round((t_full + t_suffix) / (t_partial + t_suffix), 3)
+        extra["full_prefill_tokens_per_s"] = round(T / (t_full / 1e3), 1)
+    flops = recompute_flops(shape, T, hi - lo)
+    extra.update({
+        "partial_prefill_ms": round(t_partial, 3), "suffix_prefill_ms": round(t_suffix, 3),
+        "ttft_ms": round(t_partial + t_suffix, 3),
+        "recompute_tflops_algorithmic": round(flops / 1e12, 2),
+        "mfma_util_recompute_phase": round(flops / (t_partial * 1e-3) / (PEAK_BF16_TFLOPS * 1e12), 4),
+        "reused_kv_bytes": int((L - (hi - lo)) * 2 * T * shape.kv_width * shape.elem_bytes),
+        "weights_gb": round(weights_gb, 2),
+        "kernel_launch_mix": {k: int(B.dsk_get_stat(k)) for k in
+                              ("gemm_mfma_launches", "gemm_generic_launches", "attn_mfma_launches", "attn_generic_launches")},
+    })
+
+    out = {
+        "metric": "selective_prefill_tokens_per_s", "value": round(T / (ms_per_step / 1e3), 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if shape.dtype == "bf16" else "f32", "data": data,
+        "config": {"workload": f"{shape_name} shape, one {T}-token prefix, recompute layers [{lo},{hi}) of {L}, "
+                               f"suffix {S} tokens; step = dsk_partial_prefill + dsk_suffix_prefill",
+                   "prefix_tokens": T, "lo": lo, "hi": hi, "suffix_tokens": S},
+    }
+    if shape.dtype == "bf16" and gemm_n > 0:
+        achieved = gemm_flops / (gemm_ms * 1e-3) / 1e12
+        out["roofline"] = {"bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                           "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                           "kernel": "gemm_bf16_kernel (prefill GEMMs: QKV, O, gate/up, down)",
+                           "launches": int(gemm_n), "avg_launch_ms": round(gemm_ms / gemm_n, 4),
+                           "flops_per_launch": round(gemm_flops / gemm_n / 1e9, 1), "flops_unit": "GFLOP"}
+    else:
+        out["roofline"] = {"bound": "alu", "achieved": round(flops / (t_partial * 1e-3) / 1e12, 3), "peak": 157.3,
+                           "unit": "TFLOP/s", "frac": round(flops / (t_partial * 1e-3) / 157.3e12, 5), "traffic": None,
+                           "kernel": "fp32 plain-ALU path (latency bound at this size)"}
+    out.update(extra)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(shape, lo, hi)
+    B.dsk_model_destroy(model)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

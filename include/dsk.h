@@ -109,10 +109,11 @@ typedef enum {
 } dsk_load_mode;
 
 /* Creates a model: allocates its weights (library-owned, in the library's own packed
- * layout), a workspace for up to max_tokens token rows per call, a side stream and
+ * layout), a workspace for up to max_tokens token rows per call and for caches whose used rows
+ * stay below max_kv_rows (>= max_tokens; prefix rows plus suffix rows), a side stream and
  * per-layer events, on the current device.  Weights start undefined: fill them with
  * dsk_model_set_tensor or dsk_model_init_random.  *out is written only on success. */
-DSK_API int dsk_model_create(const dsk_config_t* cfg, int64_t max_tokens, dsk_model_t** out);
+DSK_API int dsk_model_create(const dsk_config_t* cfg, int64_t max_tokens, int64_t max_kv_rows, dsk_model_t** out);
 
 /* Waits for the model's outstanding work and frees everything it owns. */
 DSK_API int dsk_model_destroy(dsk_model_t* model);
@@ -172,6 +173,34 @@ DSK_API int dsk_join_loads(dsk_model_t* model, void* stream);
 
 /* Selects the loading strategy used by later dsk_partial_prefill calls (default pipelined). */
 DSK_API int dsk_set_load_mode(dsk_model_t* model, int load_mode);
+
+/* ---- component entry points: single steps of the layer, for parity tests and micro-benchmarks ---- */
+
+/* y[M,N] = x[M,K] * w[N,K]^T (+ r[M,N] if r != NULL); all device, row-major, dense rows, dtype as given.
+ * The projection step of the layer (QKV, O, gate/up, down); y may alias r. */
+DSK_API int dsk_linear(int dtype, const void* x, const void* w, void* y, const void* r, int M, int N, int K, void* stream);
+
+/* Causal grouped-query attention of packed query tokens q [n_q, Hq*dh] (already rotated) against cache
+ * rows k_rows/v_rows (row stride Hkv*dh): query i of sequence b sees rows prefix.cu[b]..prefix.cu[b+1]-1
+ * (prefix may be NULL) and rows own_row0+queries.cu[b] .. own_row0+i.  out [n_q, Hq*dh].  All device.
+ * scratch: optional device buffer of scratch_bytes >= Hkv*dh*roundup64(own_row0+n_q)*elem bytes; the bf16
+ * tensor-core kernel needs it (it keeps a transposed copy of V there), without it the plain kernel runs. */
+DSK_API int dsk_attention(int dtype, const void* q, const void* k_rows, const void* v_rows, void* out,
+                          const dsk_batch_t* queries, const dsk_batch_t* prefix, int64_t own_row0, int n_q_heads,
+                          int n_kv_heads, int head_dim, void* scratch, int64_t scratch_bytes, void* stream);
+
+/* Integer knobs for benchmarks and tests; unknown names return DSK_EINVAL.
+ *   "gemm_variant", "attn_variant": pick a kernel tiling (default 0 = what the library picks by itself)
+ *   "force_generic": 1 = use the plain-ALU kernels even for bf16
+ *   "time_gemm": 1 = bracket every tensor-core GEMM launch with M >= 1024 by a pair of HIP events on its
+ *                stream (read back through dsk_get_stat)
+ *   "reset_stats": any value; clears all counters and recorded timings */
+DSK_API int dsk_set_option(const char* name, int value);
+
+/* Counters since the last reset: "gemm_mfma_launches", "gemm_generic_launches", "attn_mfma_launches",
+ * "attn_generic_launches"; and for the launches bracketed under "time_gemm": "timed_gemm_launches",
+ * "timed_gemm_ms" (sum of their durations; waits for them to finish), "timed_gemm_flops" (sum of 2*M*N*K). */
+DSK_API int dsk_get_stat(const char* name, double* value);
 
 /* Sizes, for callers that budget memory. */
 DSK_API int64_t dsk_model_weight_bytes(const dsk_model_t* model);

@@ -32,7 +32,7 @@ EXPORTS = (
     "dsk_model_create", "dsk_model_destroy", "dsk_model_set_tensor", "dsk_model_get_tensor",
     "dsk_model_init_random", "dsk_fill_normal", "dsk_partial_prefill", "dsk_suffix_prefill",
     "dsk_join_loads", "dsk_set_load_mode", "dsk_model_weight_bytes", "dsk_model_workspace_bytes",
-    "dsk_strerror", "dsk_last_hip_error",
+    "dsk_strerror", "dsk_last_hip_error", "dsk_linear", "dsk_attention", "dsk_set_option", "dsk_get_stat",
 )
 
 
@@ -54,7 +54,7 @@ class dsk_batch_t(C.Structure):
 
 
 _P = C.c_void_p
-lib.dsk_model_create.argtypes = [C.POINTER(dsk_config_t), C.c_int64, C.POINTER(_P)]
+lib.dsk_model_create.argtypes = [C.POINTER(dsk_config_t), C.c_int64, C.c_int64, C.POINTER(_P)]
 lib.dsk_model_destroy.argtypes = [_P]
 lib.dsk_model_set_tensor.argtypes = [_P, C.c_int, C.c_int, _P, C.c_int, _P]
 lib.dsk_model_get_tensor.argtypes = [_P, C.c_int, C.c_int, _P, _P]
@@ -64,6 +64,11 @@ lib.dsk_partial_prefill.argtypes = [_P, _P, C.c_int, C.c_int, C.c_int, C.POINTER
                                     C.POINTER(dsk_batch_t), _P, C.c_uint32, _P]
 lib.dsk_suffix_prefill.argtypes = [_P, _P, C.POINTER(dsk_kv_t), C.POINTER(dsk_batch_t), C.POINTER(dsk_batch_t),
                                    C.c_int64, _P, _P]
+lib.dsk_linear.argtypes = [C.c_int, _P, _P, _P, _P, C.c_int, C.c_int, C.c_int, _P]
+lib.dsk_attention.argtypes = [C.c_int, _P, _P, _P, _P, C.POINTER(dsk_batch_t), C.POINTER(dsk_batch_t), C.c_int64,
+                              C.c_int, C.c_int, C.c_int, _P, C.c_int64, _P]
+lib.dsk_set_option.argtypes = [C.c_char_p, C.c_int]
+lib.dsk_get_stat.argtypes = [C.c_char_p, C.POINTER(C.c_double)]
 lib.dsk_join_loads.argtypes = [_P, _P]
 lib.dsk_set_load_mode.argtypes = [_P, C.c_int]
 lib.dsk_model_weight_bytes.argtypes = [_P]
@@ -112,9 +117,9 @@ def _mem_of(t) -> int:
 
 
 # ---- the entry points, same names as the header ----
-def dsk_model_create(cfg: dsk_config_t, max_tokens: int) -> int:
+def dsk_model_create(cfg: dsk_config_t, max_tokens: int, max_kv_rows: int) -> int:
     out = _P()
-    _check(lib.dsk_model_create(C.byref(cfg), max_tokens, C.byref(out)), "dsk_model_create")
+    _check(lib.dsk_model_create(C.byref(cfg), max_tokens, max_kv_rows, C.byref(out)), "dsk_model_create")
     return out.value
 
 
@@ -153,6 +158,28 @@ def dsk_suffix_prefill(model: int, suffix_hidden_in, kv: dsk_kv_t, prefix: dsk_b
                        suffix_row0: int, hidden_out, stream=None):
     _check(lib.dsk_suffix_prefill(model, _ptr(suffix_hidden_in), C.byref(kv), C.byref(prefix), C.byref(suffix),
                                   suffix_row0, _ptr(hidden_out), _stream(stream)), "dsk_suffix_prefill")
+
+
+def dsk_linear(dtype: int, x, w, y, r, M: int, N: int, K: int, stream=None):
+    _check(lib.dsk_linear(dtype, _ptr(x), _ptr(w), _ptr(y), _ptr(r), M, N, K, _stream(stream)), "dsk_linear")
+
+
+def dsk_attention(dtype: int, q, k_rows, v_rows, out, queries: dsk_batch_t, prefix, own_row0: int, n_q_heads: int,
+                  n_kv_heads: int, head_dim: int, scratch=None, stream=None):
+    nbytes = 0 if scratch is None else scratch.numel() * scratch.element_size()
+    _check(lib.dsk_attention(dtype, _ptr(q), _ptr(k_rows), _ptr(v_rows), _ptr(out), C.byref(queries),
+                             None if prefix is None else C.byref(prefix), own_row0, n_q_heads, n_kv_heads, head_dim,
+                             _ptr(scratch), nbytes, _stream(stream)), "dsk_attention")
+
+
+def dsk_set_option(name: str, value: int):
+    _check(lib.dsk_set_option(name.encode(), value), "dsk_set_option")
+
+
+def dsk_get_stat(name: str) -> float:
+    v = C.c_double()
+    _check(lib.dsk_get_stat(name.encode(), C.byref(v)), "dsk_get_stat")
+    return v.value
 
 
 def dsk_join_loads(model: int, stream=None):

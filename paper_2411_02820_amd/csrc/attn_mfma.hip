@@ -1,4 +1,297 @@
-// bf16 MFMA flash attention for gfx950 (placeholder until the tiled kernel lands).
+// bf16 MFMA flash attention for gfx950: causal grouped-query attention over packed sequences,
+// keys taken from up to two row ranges of a cache layer (a fully visible prefix range and the
+// queries' own causal range), online softmax in fp32.
+//
+// A workgroup (4 waves) owns 128 query rows of one (sequence, q head); each wave 32 of them.
+// Keys are walked in tiles of 64 cache rows (aligned to multiples of 64), staged in LDS:
+//   K tile  [64 keys][dh]   - rows permuted (bits 2 and 3 of the key offset swapped), see below
+//   Vt tile [dh][64 keys]   - from a transposed copy of V kept in the model's workspace
+// Scores are computed transposed, S^T = K Q^T, with v_mfma_f32_32x32x16_bf16 (K rows as the MFMA A
+// operand, Q rows as B): a lane then owns ONE query (column lane%32) and 16 keys per 32-key tile in its
+// accumulator registers, so the softmax row maximum/sum are in-lane reductions plus a single exchange
+// with lane^32.  With the K-row permutation the 8 registers [8t, 8t+8) of a lane are 8 consecutive keys
+// (16t + 8*(lane/32) + 0..7), i.e. exactly the B-operand layout of P^T for O^T += Vt P^T, and the
+// matching Vt fragment is one 16-byte LDS read.  The output accumulator O^T[d][q] keeps the query in the
+// lane as well, so rescaling by the running maximum is a per-lane scalar multiply.
 #include "dsk_internal.h"
 
-hipError_t launch_attn_mfma_bf16(const AttnArgs&, hipStream_t) { return hipErrorNotSupported; }
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+constexpr int BQ = 128;  // query rows per workgroup
+constexpr int BKV = 64;  // keys per tile
+
+struct AttnParams {
+  const bf16_t* q; int64_t ldq;
+  const bf16_t* k; const bf16_t* vt; int64_t ldvt;
+  bf16_t* out;
+  const int32_t* q_cu; const int32_t* p_cu;
+  int n_seqs; int64_t own_row0; int Hq, Hkv; int total_tiles;
+  float c;              // softmax scale * log2(e)
+  int64_t k_row_max;    // last cache row that may be read
+};
+
+// MFMA row of key offset u inside a 64-key tile: bits 2 and 3 swapped
+__device__ __forceinline__ int perm_key(int u) { return (u & ~0xC) | ((u & 4) << 1) | ((u & 8) >> 1); }
+
+template <int DH>
+__global__ void __launch_bounds__(256) attn_bf16_kernel(AttnParams p) {
+  constexpr int KCH = DH / 8;            // 16-byte chunks per K row
+  constexpr int K_LOADS = BKV * KCH / 256, V_LOADS = DH * (BKV / 8) / 256;
+  constexpr int NKS = DH / 16, NDT = DH / 32;
+  __shared__ __attribute__((aligned(16))) bf16_t sK[2][BKV * DH];
+  __shared__ __attribute__((aligned(16))) bf16_t sV[2][DH * BKV];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lq = lane & 31, hh = lane >> 5;
+  const int h = blockIdx.y, kvh = h / (p.Hq / p.Hkv);
+
+  // ---- which (sequence, query tile): heavy (late) tiles are launched first ----
+  int tile = p.total_tiles - 1 - (int)blockIdx.x;
+  int b = 0, seq_begin = 0, seq_end = 0;
+  for (;; ++b) {
+    seq_begin = p.q_cu[b];
+    seq_end = p.q_cu[b + 1];
+    int nt = (seq_end - seq_begin + BQ - 1) / BQ;
+    if (tile < nt || b + 1 >= p.n_seqs) break;
+    tile -= nt;
+  }
+  const int q0 = seq_begin + tile * BQ;          // first query row (packed index) of this workgroup
+  if (q0 >= seq_end) return;                      // cannot happen for a well-formed grid
+  const int qw0 = q0 + 32 * wave;                 // first query row of this wave
+  const bool wave_active = qw0 < seq_end;
+  const int qi = min(qw0 + lq, seq_end - 1);      // this lane's query (clamped for the padding rows)
+
+  const int64_t own_begin = p.own_row0 + seq_begin;
+  const int64_t lim = p.own_row0 + qi;                                   // last own row this lane's query sees
+  const int64_t wave_lim_min = p.own_row0 + min(qw0, seq_end - 1);       // smallest limit in the wave
+  const int64_t wave_lim_max = p.own_row0 + min(qw0 + 31, seq_end - 1);  // largest limit in the wave
+  const int64_t blk_lim = p.own_row0 + min(q0 + BQ, seq_end) - 1;
+  const int64_t pre_begin = p.p_cu ? p.p_cu[b] : 0, pre_end = p.p_cu ? p.p_cu[b + 1] : 0;
+  const int ta0 = (int)(pre_begin / BKV), nA = pre_end > pre_begin ? (int)((pre_end - 1) / BKV) - ta0 + 1 : 0;
+  const int tb0 = (int)(own_begin / BKV), nB = (int)(blk_lim / BKV) - tb0 + 1;
+  const int n_tiles = nA + nB;
+
+  // ---- Q fragments (B operand): query = lane%32, d = 16*ks + 8*(lane/32) .. +7 ----
+  bf16x8 qf[NKS];
+  {
+    const bf16_t* qp = p.q + (int64_t)qi * p.ldq + h * DH + 8 * hh;
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) qf[ks] = *(const bf16x8*)(qp + 16 * ks);
+  }
+
+  // ---- tile loads: global -> registers -> LDS ----
+  const int64_t ldkv = (int64_t)p.Hkv * DH;
+  u32x4 k_reg[K_LOADS], v_reg[V_LOADS];
+  int k_lds[K_LOADS], v_lds[V_LOADS], k_u[K_LOADS], k_ch[K_LOADS];
+  const bf16_t* v_ptr[V_LOADS];
+#pragma unroll
+  for (int i = 0; i < K_LOADS; ++i) {
+    int id = tid + i * 256, u = id / KCH, ch = id % KCH, r = perm_key(u);
+    k_u[i] = u;
+    k_ch[i] = ch;
+    k_lds[i] = r * DH + ((ch ^ (r & 7)) * 8);
+  }
+#pragma unroll
+  for (int i = 0; i < V_LOADS; ++i) {
+    int id = tid + i * 256, d = id / 8, ch = id % 8;
+    v_ptr[i] = p.vt + ((int64_t)kvh * DH + d) * p.ldvt + ch * 8;
+    v_lds[i] = d * BKV + ((ch ^ (d & 7)) * 8);
+  }
+  auto tile_row0 = [&](int it) -> int64_t { return (int64_t)(it < nA ? ta0 + it : tb0 + (it - nA)) * BKV; };
+  auto load_global = [&](int it) {
+    const int64_t r0 = tile_row0(it);
+#pragma unroll
+    for (int i = 0; i < K_LOADS; ++i) {
+      int64_t row = min(r0 + k_u[i], p.k_row_max);
+      k_reg[i] = *(const u32x4*)(p.k + row * ldkv + kvh * DH + k_ch[i] * 8);
+    }
+#pragma unroll
+    for (int i = 0; i < V_LOADS; ++i) v_reg[i] = *(const u32x4*)(v_ptr[i] + r0);
+  };
+  auto store_lds = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < K_LOADS; ++i) *(u32x4*)(&sK[buf][k_lds[i]]) = k_reg[i];
+#pragma unroll
+    for (int i = 0; i < V_LOADS; ++i) *(u32x4*)(&sV[buf][v_lds[i]]) = v_reg[i];
+  };
+
+  f32x16 o[NDT];
+#pragma unroll
+  for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[dt][r] = 0.f;
+  float m = -INFINITY, l = 0.f;
+
+  load_global(0);
+  store_lds(0);
+  __syncthreads();
+  for (int it = 0; it < n_tiles; ++it) {
+    const bool more = it + 1 < n_tiles;
+    if (more) load_global(it + 1);
+    const int buf = it & 1;
+    const int64_t r0 = tile_row0(it);
+    const bool segA = it < nA;
+    // visible key rows for this lane in this segment: [lo, hi]
+    const int64_t lo = segA ? pre_begin : own_begin;
+    const int64_t hi = segA ? pre_end - 1 : lim;
+    const bool skip = !wave_active || (!segA && r0 > wave_lim_max);
+    if (!skip) {
+      // S^T = K Q^T for the two 32-key halves of the tile
+      f32x16 s[2];
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[kt][r] = 0.f;
+        const int row = 32 * kt + lq;
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+          bf16x8 kf = *(const bf16x8*)(&sK[buf][row * DH + (((2 * ks + hh) ^ (row & 7)) * 8)]);
+          s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kt], 0, 0, 0);
+        }
+      }
+      // mask: register r of half kt is key r0 + 32*kt + 16*(r/8) + 8*(lane/32) + r%8
+      const bool full = r0 >= lo && r0 + BKV - 1 <= (segA ? pre_end - 1 : wave_lim_min);
+      if (!full) {
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            int64_t key = r0 + 32 * kt + 16 * (r >> 3) + 8 * hh + (r & 7);
+            s[kt][r] = (key >= lo && key <= hi) ? s[kt][r] : -INFINITY;
+          }
+      }
+      // online softmax; the query's 64 scores sit in this lane and in lane^32
+      float mx = s[0][0];
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kt][r]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float m_new = fmaxf(m, mx);
+      const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+      const float alpha = __builtin_amdgcn_exp2f((m - m_safe) * p.c);
+      const float mc = m_safe * p.c;
+      float psum = 0.f;
+      bf16x8 pf[2][2];
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          float e = __builtin_amdgcn_exp2f(s[kt][r] * p.c - mc);
+          psum += e;
+          pf[kt][r >> 3][r & 7] = (bf16_t)e;
+        }
+      l = l * alpha + psum;
+      m = m_new;
+#pragma unroll
+      for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+      // O^T += Vt P^T
+#pragma unroll
+      for (int dt = 0; dt < NDT; ++dt) {
+        const int d = 32 * dt + lq;
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+          for (int t = 0; t < 2; ++t) {
+            bf16x8 vf = *(const bf16x8*)(&sV[buf][d * BKV + (((4 * kt + 2 * t + hh) ^ (d & 7)) * 8)]);
+            o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kt][t], o[dt], 0, 0, 0);
+          }
+      }
+    }
+    if (more) store_lds((it + 1) & 1);
+    __syncthreads();
+  }
+
+  // ---- normalise and store: register 4g+e of d-tile dt is out[q][32dt + 8g + 4*(lane/32) + e] ----
+  const float l_tot = l + __shfl_xor(l, 32, 64);
+  if (wave_active && qw0 + lq < seq_end) {
+    const float inv = 1.0f / l_tot;
+    bf16_t* op = p.out + (int64_t)(qw0 + lq) * p.Hq * DH + h * DH;
+#pragma unroll
+    for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        bf16x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = (bf16_t)(o[dt][4 * g + e] * inv);
+        *(bf16x4*)(op + 32 * dt + 8 * g + 4 * hh) = v;
+      }
+  }
+}
+
+// Vt[(kvh*dh + d)*ldvt + row] = V[row][kvh*dh + d] for the valid rows, 0 for the others, over whole
+// 64-row tiles.  valid(row) = row < n_pre || own_row0 <= row < own_row0 + n_own.
+__global__ void __launch_bounds__(256) transpose_v_kernel(const bf16_t* __restrict__ v_rows, bf16_t* __restrict__ vt,
+                                                          int64_t ldvt, int width, int64_t n_pre, int64_t own_row0,
+                                                          int64_t n_own) {
+  __shared__ bf16_t tile[64][66];
+  const int64_t r0 = (int64_t)blockIdx.x * 64;
+  const int c0 = blockIdx.y * 64;
+  const int tid = threadIdx.x;
+  {
+    const int r = tid >> 3, ch = tid & 7;
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      const int rr = r + 32 * half;
+      const int64_t row = r0 + rr;
+      const bool valid = row < n_pre || (row >= own_row0 && row < own_row0 + n_own);
+      bf16x8 x;
+      if (valid) x = *(const bf16x8*)(v_rows + row * width + c0 + ch * 8);
+      else
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = (bf16_t)0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) tile[rr][ch * 8 + e] = x[e];
+    }
+  }
+  __syncthreads();
+  {
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      const int id = tid + 256 * half, d = id >> 3, rc = id & 7;
+      bf16x8 x;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) x[e] = tile[rc * 8 + e][d];
+      *(bf16x8*)(vt + (int64_t)(c0 + d) * ldvt + r0 + rc * 8) = x;
+    }
+  }
+}
+
+}  // namespace
+
+void attn_mfma_set_variant(int) {}
+
+hipError_t launch_transpose_v(const void* v_rows, void* vt, int64_t ldvt, int width, int64_t n_pre, int64_t own_row0,
+                              int64_t n_own, hipStream_t s) {
+  const int64_t end = own_row0 + n_own;
+  if (end <= 0) return hipSuccess;
+  dim3 grid((unsigned)((end + 63) / 64), width / 64);
+  hipLaunchKernelGGL(transpose_v_kernel, grid, dim3(256), 0, s, (const bf16_t*)v_rows, (bf16_t*)vt, ldvt, width, n_pre,
+                     own_row0, n_own);
+  return hipGetLastError();
+}
+
+hipError_t launch_attn_mfma_bf16(const AttnArgs& a, hipStream_t s) {
+  if (a.n_q <= 0) return hipSuccess;
+  if ((a.dh != 128 && a.dh != 64) || !a.vt || (a.ldq & 7)) return hipErrorNotSupported;
+  AttnParams p;
+  p.q = (const bf16_t*)a.q; p.ldq = a.ldq; p.k = (const bf16_t*)a.k_rows; p.vt = (const bf16_t*)a.vt; p.ldvt = a.ldvt;
+  p.out = (bf16_t*)a.out; p.q_cu = a.q_cu; p.p_cu = a.p_cu; p.n_seqs = a.n_seqs; p.own_row0 = a.own_row0;
+  p.Hq = a.Hq; p.Hkv = a.Hkv;
+  int total = 0;
+  for (int b = 0; b < a.n_seqs; ++b) total += (a.q_cu_host[b + 1] - a.q_cu_host[b] + BQ - 1) / BQ;
+  p.total_tiles = total;
+  p.c = (float)(1.4426950408889634 / sqrt((double)a.dh));
+  p.k_row_max = a.own_row0 + a.n_q - 1;
+  dim3 grid(total, a.Hq);
+  if (a.dh == 128) hipLaunchKernelGGL(attn_bf16_kernel<128>, grid, dim3(256), 0, s, p);
+  else hipLaunchKernelGGL(attn_bf16_kernel<64>, grid, dim3(256), 0, s, p);
+  return hipGetLastError();
+}

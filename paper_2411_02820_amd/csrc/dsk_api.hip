@@ -45,7 +45,7 @@ void free_model(dsk_model* m) {
     free(m->layers);
   }
   (void)hipFree(m->xn); (void)hipFree(m->qkv); (void)hipFree(m->attn); (void)hipFree(m->gu);
-  (void)hipFree(m->act); (void)hipFree(m->h); (void)hipFree(m->rope_cs); (void)hipFree(m->theta);
+  (void)hipFree(m->act); (void)hipFree(m->h); (void)hipFree(m->rope_cs); (void)hipFree(m->theta); (void)hipFree(m->vt);
   if (m->ev_kv) {
     for (int l = 0; l < m->cfg.n_layers; ++l)
       if (m->ev_kv[l]) (void)hipEventDestroy(m->ev_kv[l]);
@@ -84,28 +84,76 @@ int check_kv(const dsk_model* m, const dsk_kv_t* kv, int64_t rows_needed, bool m
 inline char* kv_k(const dsk_kv_t* kv, int l) { return (char*)kv->base + (int64_t)l * kv->layer_stride; }
 inline char* kv_v(const dsk_kv_t* kv, int l) { return kv_k(kv, l) + kv->v_offset; }
 
-hipError_t gemm(const dsk_model* m, const void* A, int64_t lda, const void* W, int64_t ldw, void* C, int64_t ldc,
-                const void* R, int64_t ldr, int M, int N, int K, int epi, hipStream_t s) {
-  if (m->cfg.dtype == DSK_BF16) {
+int g_force_generic = 0;
+int g_time_gemm = 0;
+
+// launch counters and the event pairs recorded under "time_gemm"
+struct Stats {
+  int64_t gemm_mfma = 0, gemm_generic = 0, attn_mfma = 0, attn_generic = 0;
+  static constexpr int kMaxTimed = 8192;
+  hipEvent_t* ev = nullptr;  // 2*kMaxTimed events, created on first use
+  int n_timed = 0;
+  double timed_flops = 0.0;
+} g_stats;
+
+hipError_t gemm_any(int dtype, const void* A, int64_t lda, const void* W, int64_t ldw, void* C, int64_t ldc,
+                    const void* R, int64_t ldr, int M, int N, int K, int epi, hipStream_t s) {
+  if (dtype == DSK_BF16 && !g_force_generic) {
+    const bool timed = g_time_gemm && M >= 1024 && g_stats.n_timed < Stats::kMaxTimed;
+    if (timed) {
+      if (!g_stats.ev) {
+        g_stats.ev = (hipEvent_t*)calloc(2 * Stats::kMaxTimed, sizeof(hipEvent_t));
+        if (!g_stats.ev) return hipErrorOutOfMemory;
+        for (int i = 0; i < 2 * Stats::kMaxTimed; ++i) {
+          hipError_t ee = hipEventCreate(&g_stats.ev[i]);
+          if (ee != hipSuccess) return ee;
+        }
+      }
+      hipError_t ee = hipEventRecord(g_stats.ev[2 * g_stats.n_timed], s);
+      if (ee != hipSuccess) return ee;
+    }
     hipError_t e = launch_gemm_mfma_bf16(A, lda, W, ldw, C, ldc, R, ldr, M, N, K, epi, s);
-    if (e != hipErrorNotSupported) return e;
+    if (e != hipErrorNotSupported) {
+      if (e == hipSuccess) {
+        ++g_stats.gemm_mfma;
+        if (timed) {
+          e = hipEventRecord(g_stats.ev[2 * g_stats.n_timed + 1], s);
+          g_stats.timed_flops += 2.0 * M * N * K;
+          ++g_stats.n_timed;
+        }
+      }
+      return e;
+    }
   }
-  return launch_gemm_generic(m->cfg.dtype, A, lda, W, ldw, C, ldc, R, ldr, M, N, K, epi, s);
+  ++g_stats.gemm_generic;
+  return launch_gemm_generic(dtype, A, lda, W, ldw, C, ldc, R, ldr, M, N, K, epi, s);
 }
 
-hipError_t attention(const dsk_model* m, const AttnArgs& a, hipStream_t s) {
-  if (m->cfg.dtype == DSK_BF16) {
-    hipError_t e = launch_attn_mfma_bf16(a, s);
-    if (e != hipErrorNotSupported) return e;
-  }
-  return launch_attn_generic(m->cfg.dtype, a, s);
+hipError_t gemm(const dsk_model* m, const void* A, int64_t lda, const void* W, int64_t ldw, void* C, int64_t ldc,
+                const void* R, int64_t ldr, int M, int N, int K, int epi, hipStream_t s) {
+  return gemm_any(m->cfg.dtype, A, lda, W, ldw, C, ldc, R, ldr, M, N, K, epi, s);
 }
+
+hipError_t attention_any(int dtype, const AttnArgs& a, hipStream_t s) {
+  if (dtype == DSK_BF16 && !g_force_generic) {
+    hipError_t e = launch_attn_mfma_bf16(a, s);
+    if (e != hipErrorNotSupported) {
+      if (e == hipSuccess) ++g_stats.attn_mfma;
+      return e;
+    }
+  }
+  ++g_stats.attn_generic;
+  return launch_attn_generic(dtype, a, s);
+}
+
+hipError_t attention(const dsk_model* m, const AttnArgs& a, hipStream_t s) { return attention_any(m->cfg.dtype, a, s); }
 
 // One decoder layer over n token rows.  h_in: residual stream entering the layer; h_out: where the
 // state leaving the layer is written (may equal h_in).  K/V of the tokens go to rows own_row0.. of the
 // cache layer (k_rows, v_rows); attention additionally sees the prefix rows delimited by p_cu.
 int run_layer(dsk_model* m, int l, const void* h_in, void* h_out, char* k_layer, char* v_layer, int64_t own_row0,
-              const int32_t* q_cu, const int32_t* q_cu_host, const int32_t* p_cu, int n_seqs, int n, hipStream_t s) {
+              const int32_t* q_cu, const int32_t* q_cu_host, const int32_t* p_cu, int64_t n_pre_rows, int n_seqs, int n,
+              hipStream_t s) {
   const dsk_config_t& c = m->cfg;
   const LayerWeights& w = m->layers[l];
   const int d = c.hidden, F = c.ffn, nq = c.n_q_heads * c.head_dim;
@@ -119,6 +167,11 @@ int run_layer(dsk_model* m, int l, const void* h_in, void* h_out, char* k_layer,
   a.q = m->qkv; a.ldq = m->n_qkv; a.k_rows = k_layer; a.v_rows = v_layer; a.out = m->attn;
   a.q_cu = q_cu; a.p_cu = p_cu; a.q_cu_host = q_cu_host; a.n_seqs = n_seqs; a.own_row0 = own_row0; a.n_q = n;
   a.Hq = c.n_q_heads; a.Hkv = c.n_kv_heads; a.dh = c.head_dim;
+  a.vt = nullptr; a.ldvt = 0;
+  if (m->vt && !g_force_generic) {
+    HIP_TRY(launch_transpose_v(v_layer, m->vt, m->ldvt, c.n_kv_heads * c.head_dim, n_pre_rows, own_row0, n, s));
+    a.vt = m->vt; a.ldvt = m->ldvt;
+  }
   HIP_TRY(attention(m, a, s));
   HIP_TRY(gemm(m, m->attn, nq, w.wo, nq, m->h, d, h_in, d, n, d, nq, EPI_RESIDUAL, s));
   HIP_TRY(launch_rmsnorm(c.dtype, m->h, w.g2, m->xn, n, d, (float)c.rms_eps, s));
@@ -154,8 +207,8 @@ int place_tensor(const dsk_model* m, int layer, int tensor, TensorPlace* p) {
 
 extern "C" {
 
-int dsk_model_create(const dsk_config_t* cfg, int64_t max_tokens, dsk_model_t** out) {
-  if (!cfg || !out || max_tokens < 1 || max_tokens >= ((int64_t)1 << 31)) return DSK_EINVAL;
+int dsk_model_create(const dsk_config_t* cfg, int64_t max_tokens, int64_t max_kv_rows, dsk_model_t** out) {
+  if (!cfg || !out || max_tokens < 1 || max_kv_rows < max_tokens || max_kv_rows >= ((int64_t)1 << 31)) return DSK_EINVAL;
   if (cfg->dtype != DSK_F32 && cfg->dtype != DSK_BF16) return DSK_EDTYPE;
   if (cfg->n_layers < 1 || cfg->hidden < 1 || cfg->n_q_heads < 1 || cfg->n_kv_heads < 1 || cfg->head_dim < 2 ||
       cfg->ffn < 1)
@@ -172,6 +225,8 @@ int dsk_model_create(const dsk_config_t* cfg, int64_t max_tokens, dsk_model_t** 
   m->cfg = *cfg;
   m->elem = elem;
   m->max_tokens = max_tokens;
+  m->max_kv_rows = max_kv_rows;
+  m->ldvt = (max_kv_rows + 63) / 64 * 64;
   m->n_qkv = (cfg->n_q_heads + 2 * cfg->n_kv_heads) * cfg->head_dim;
   m->gu_block = 1;
   for (int g = 32; g >= 1; g >>= 1)
@@ -202,6 +257,9 @@ int dsk_model_create(const dsk_config_t* cfg, int64_t max_tokens, dsk_model_t** 
   if (rc == DSK_OK) rc = alloc_dev(&m->h, T * d * elem, &m->workspace_bytes);
   if (rc == DSK_OK) rc = alloc_dev((void**)&m->rope_cs, T * half * (int64_t)sizeof(float2), &m->workspace_bytes);
   if (rc == DSK_OK) rc = alloc_dev((void**)&m->theta, half * (int64_t)sizeof(double), &m->workspace_bytes);
+  const int64_t kvw = (int64_t)cfg->n_kv_heads * cfg->head_dim;
+  if (rc == DSK_OK && cfg->dtype == DSK_BF16 && kvw % 64 == 0 && (cfg->head_dim == 64 || cfg->head_dim == 128))
+    rc = alloc_dev(&m->vt, kvw * m->ldvt * elem, &m->workspace_bytes);
   if (rc == DSK_OK) {
     double* th = (double*)malloc(half * sizeof(double));
     if (!th) rc = DSK_ENOMEM;
@@ -308,7 +366,7 @@ int dsk_partial_prefill(dsk_model_t* model, const void* hidden_in, int hidden_in
   int rc = check_batch(batch, true);
   if (rc) return rc;
   const int T = batch->n_tokens;
-  if (T > m->max_tokens) return DSK_EINVAL;
+  if (T > m->max_tokens || T > m->max_kv_rows) return DSK_EINVAL;
   if ((rc = check_kv(m, kv_out, T, true))) return rc;
   const bool need_reused = (hi - lo) < L;
   if (need_reused || kv_reused)
@@ -364,7 +422,7 @@ int dsk_partial_prefill(dsk_model_t* model, const void* hidden_in, int hidden_in
     for (int l = lo; l < hi; ++l) {
       void* h_next = (l == hi - 1 && hidden_out) ? hidden_out : m->h;
       rc = run_layer(m, l, h_cur, h_next, kv_k(kv_out, l), kv_v(kv_out, l), 0, batch->cu_seqlens_dev,
-                     batch->cu_seqlens_host, nullptr, batch->n_seqs, T, s);
+                     batch->cu_seqlens_host, nullptr, 0, batch->n_seqs, T, s);
       if (rc) return rc;
       h_cur = h_next;
     }
@@ -393,7 +451,7 @@ int dsk_suffix_prefill(dsk_model_t* model, const void* suffix_hidden_in, const d
   if (prefix->n_seqs != suffix->n_seqs) return DSK_EINVAL;
   const int S = suffix->n_tokens;
   if (S > m->max_tokens) return DSK_EINVAL;
-  if (suffix_row0 < prefix->n_tokens) return DSK_EINVAL;
+  if (suffix_row0 < prefix->n_tokens || suffix_row0 + S > m->max_kv_rows) return DSK_EINVAL;
   if ((rc = check_kv(m, kv, suffix_row0 + S, true))) return rc;
 
   hipStream_t s = (hipStream_t)stream;
@@ -406,7 +464,7 @@ int dsk_suffix_prefill(dsk_model_t* model, const void* suffix_hidden_in, const d
     }
     void* h_next = (l == c.n_layers - 1) ? hidden_out : m->h;
     rc = run_layer(m, l, h_cur, h_next, kv_k(kv, l), kv_v(kv, l), suffix_row0, suffix->cu_seqlens_dev,
-                   suffix->cu_seqlens_host, prefix->cu_seqlens_dev, suffix->n_seqs, S, s);
+                   suffix->cu_seqlens_host, prefix->cu_seqlens_dev, prefix->n_tokens, suffix->n_seqs, S, s);
     if (rc) return rc;
     h_cur = h_next;
   }
@@ -427,6 +485,82 @@ int dsk_join_loads(dsk_model_t* model, void* stream) {
 int dsk_set_load_mode(dsk_model_t* model, int load_mode) {
   if (!model || load_mode < DSK_LOAD_PIPELINED || load_mode > DSK_LOAD_ALL_FIRST) return DSK_EINVAL;
   model->load_mode = load_mode;
+  return DSK_OK;
+}
+
+int dsk_linear(int dtype, const void* x, const void* w, void* y, const void* r, int M, int N, int K, void* stream) {
+  if (!x || !w || !y || M < 1 || N < 1 || K < 1) return DSK_EINVAL;
+  if (dtype != DSK_F32 && dtype != DSK_BF16) return DSK_EDTYPE;
+  if (!aligned16(x) || !aligned16(w) || !aligned16(y) || !aligned16(r)) return DSK_EINVAL;
+  const int epi = r ? EPI_RESIDUAL : EPI_STORE;
+  HIP_TRY(gemm_any(dtype, x, K, w, K, y, N, r, N, M, N, K, epi, (hipStream_t)stream));
+  return DSK_OK;
+}
+
+int dsk_attention(int dtype, const void* q, const void* k_rows, const void* v_rows, void* out,
+                  const dsk_batch_t* queries, const dsk_batch_t* prefix, int64_t own_row0, int n_q_heads,
+                  int n_kv_heads, int head_dim, void* scratch, int64_t scratch_bytes, void* stream) {
+  if (!q || !k_rows || !v_rows || !out || own_row0 < 0 || !aligned16(scratch)) return DSK_EINVAL;
+  if (dtype != DSK_F32 && dtype != DSK_BF16) return DSK_EDTYPE;
+  if (n_q_heads < 1 || n_kv_heads < 1 || n_q_heads % n_kv_heads || head_dim < 2 || (head_dim & 1) || head_dim > 256)
+    return DSK_ESHAPE;
+  if (!aligned16(q) || !aligned16(k_rows) || !aligned16(v_rows) || !aligned16(out)) return DSK_EINVAL;
+  int rc = check_batch(queries, false);
+  if (rc) return rc;
+  if (prefix) {
+    if ((rc = check_batch(prefix, false))) return rc;
+    if (prefix->n_seqs != queries->n_seqs) return DSK_EINVAL;
+  }
+  AttnArgs a;
+  a.q = q; a.ldq = (int64_t)n_q_heads * head_dim; a.k_rows = k_rows; a.v_rows = v_rows; a.out = out;
+  a.q_cu = queries->cu_seqlens_dev; a.q_cu_host = queries->cu_seqlens_host;
+  a.p_cu = prefix ? prefix->cu_seqlens_dev : nullptr;
+  a.n_seqs = queries->n_seqs; a.own_row0 = own_row0; a.n_q = queries->n_tokens;
+  a.Hq = n_q_heads; a.Hkv = n_kv_heads; a.dh = head_dim;
+  a.vt = nullptr; a.ldvt = 0;
+  const int64_t kvw = (int64_t)n_kv_heads * head_dim;
+  const int64_t rows64 = (own_row0 + queries->n_tokens + 63) / 64 * 64;
+  if (dtype == DSK_BF16 && !g_force_generic && scratch && kvw % 64 == 0 && scratch_bytes >= kvw * rows64 * 2) {
+    HIP_TRY(launch_transpose_v(v_rows, scratch, rows64, (int)kvw, prefix ? prefix->n_tokens : 0, own_row0,
+                               queries->n_tokens, (hipStream_t)stream));
+    a.vt = scratch; a.ldvt = rows64;
+  }
+  HIP_TRY(attention_any(dtype, a, (hipStream_t)stream));
+  return DSK_OK;
+}
+
+int dsk_set_option(const char* name, int value) {
+  if (!name) return DSK_EINVAL;
+  if (!strcmp(name, "gemm_variant")) gemm_mfma_set_variant(value);
+  else if (!strcmp(name, "attn_variant")) attn_mfma_set_variant(value);
+  else if (!strcmp(name, "force_generic")) g_force_generic = value;
+  else if (!strcmp(name, "time_gemm")) g_time_gemm = value;
+  else if (!strcmp(name, "reset_stats")) {
+    g_stats.gemm_mfma = g_stats.gemm_generic = g_stats.attn_mfma = g_stats.attn_generic = 0;
+    g_stats.n_timed = 0;
+    g_stats.timed_flops = 0.0;
+  } else return DSK_EINVAL;
+  return DSK_OK;
+}
+
+int dsk_get_stat(const char* name, double* value) {
+  if (!name || !value) return DSK_EINVAL;
+  if (!strcmp(name, "gemm_mfma_launches")) *value = (double)g_stats.gemm_mfma;
+  else if (!strcmp(name, "gemm_generic_launches")) *value = (double)g_stats.gemm_generic;
+  else if (!strcmp(name, "attn_mfma_launches")) *value = (double)g_stats.attn_mfma;
+  else if (!strcmp(name, "attn_generic_launches")) *value = (double)g_stats.attn_generic;
+  else if (!strcmp(name, "timed_gemm_launches")) *value = (double)g_stats.n_timed;
+  else if (!strcmp(name, "timed_gemm_flops")) *value = g_stats.timed_flops;
+  else if (!strcmp(name, "timed_gemm_ms")) {
+    double total = 0.0;
+    for (int i = 0; i < g_stats.n_timed; ++i) {
+      HIP_TRY(hipEventSynchronize(g_stats.ev[2 * i + 1]));
+      float ms = 0.f;
+      HIP_TRY(hipEventElapsedTime(&ms, g_stats.ev[2 * i], g_stats.ev[2 * i + 1]));
+      total += ms;
+    }
+    *value = total;
+  } else return DSK_EINVAL;
   return DSK_OK;
 }
 

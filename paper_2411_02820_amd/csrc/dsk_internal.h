@@ -32,6 +32,7 @@ struct dsk_model {
   dsk_config_t cfg;
   int elem;         // bytes per element
   int64_t max_tokens;
+  int64_t max_kv_rows;
   int gu_block;
   int n_qkv;        // (Hq+2Hkv)*dh
   LayerWeights* layers;
@@ -45,6 +46,8 @@ struct dsk_model {
   void* h;          // [maxT, d]      residual stream
   float2* rope_cs;  // [maxT, dh/2]   cos, sin
   double* theta;    // [dh/2]         rope_base^(-2i/dh)
+  void* vt;         // [Hkv*dh, ldvt] transposed V of the layer in flight (bf16 MFMA attention)
+  int64_t ldvt;     // max_kv_rows rounded up to 64
   int64_t workspace_bytes;
   // load pipeline
   hipStream_t load_stream;
@@ -83,9 +86,14 @@ struct AttnArgs {
   void* out;
   const int32_t* q_cu; const int32_t* p_cu; const int32_t* q_cu_host; int n_seqs;
   int64_t own_row0; int n_q; int Hq, Hkv, dh;
+  const void* vt; int64_t ldvt;  // transposed V (see launch_transpose_v); NULL: not available
 };
 hipError_t launch_attn_generic(int dtype, const AttnArgs& a, hipStream_t s);
 hipError_t launch_attn_mfma_bf16(const AttnArgs& a, hipStream_t s);
+// vt[(c)*ldvt + row] = v_rows[row][c] for valid rows (row < n_pre or own_row0 <= row < own_row0+n_own), 0 otherwise,
+// over whole 64-row tiles up to own_row0+n_own; width = Hkv*dh must be a multiple of 64.
+hipError_t launch_transpose_v(const void* v_rows, void* vt, int64_t ldvt, int width, int64_t n_pre, int64_t own_row0,
+                              int64_t n_own, hipStream_t s);
 
 hipError_t launch_fill_normal(void* dst, int64_t n, uint64_t seed, uint64_t stream_id, float std, float offset,
                               int64_t idx0, int dtype, hipStream_t s);
@@ -94,3 +102,7 @@ hipError_t launch_pack_rows(int dtype, void* packed, const void* logical, int64_
                             int gu_block, int64_t row_off, int to_packed, hipStream_t s);
 hipError_t launch_fill_weight(int dtype, void* packed, int64_t rows, int64_t cols, int map, int gu_block, int64_t row_off,
                               uint64_t seed, uint64_t stream_id, float std, float offset, hipStream_t s);
+
+// tuning knobs (dsk_set_option)
+void gemm_mfma_set_variant(int v);
+void attn_mfma_set_variant(int v);

@@ -27,9 +27,10 @@ def to_np(t):
 
 
 class GpuModel:
-    def __init__(self, shape: synth.ModelShape, max_tokens: int):
+    def __init__(self, shape: synth.ModelShape, max_tokens: int, max_kv_rows: int = None):
         self.shape = shape
-        self.handle = B.dsk_model_create(B.config_from_shape(shape), max_tokens)
+        self.handle = B.dsk_model_create(B.config_from_shape(shape), max_tokens,
+                                         max_tokens if max_kv_rows is None else max_kv_rows)
 
     def close(self):
         if self.handle:

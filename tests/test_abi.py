@@ -31,5 +31,5 @@ def test_error_strings_without_gpu():
     assert B.lib.dsk_strerror(B.DSK_OK) == b"ok"
     assert B.lib.dsk_strerror(B.DSK_EINVAL) == b"invalid argument"
     # null arguments are rejected before any device call
-    assert B.lib.dsk_model_create(None, 1, None) == B.DSK_EINVAL
+    assert B.lib.dsk_model_create(None, 1, 1, None) == B.DSK_EINVAL
     assert B.lib.dsk_partial_prefill(None, None, 0, 0, 0, None, None, None, None, 0, None) == B.DSK_EINVAL

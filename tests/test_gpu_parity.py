@@ -48,7 +48,7 @@ def run_case(G, shape, lens, lo, hi, slens, scale, pinned_kv=False, pinned_e=Fal
     kv_r = synth.kv_cache(shape, T)
     w = scaled_weights(shape, synth.SEED_RECEIVER, scale)
 
-    with G.GpuModel(shape, max(T, S, 1)) as m:
+    with G.GpuModel(shape, max(T, S, 1), T + S) as m:
         m.load_from_generator(synth.SEED_RECEIVER, scale=scale)
         kv_out, h_out = m.partial(G.to_dev(hidden_in, shape, pinned=pinned_e), lo, hi,
                                   G.to_dev(kv_r, shape, pinned=pinned_kv), lens, n_rows=T + S)
@@ -178,7 +178,7 @@ def test_deferred_join_then_suffix(G):
     hidden_in = G.to_dev(synth.hidden_states(shape, T), shape)
     kv_r = G.to_dev(synth.kv_cache(shape, T), shape, pinned=True)
     xs = G.to_dev(synth.hidden_states(shape, S, seed=synth.SEED_SUFFIX), shape)
-    with G.GpuModel(shape, T) as m:
+    with G.GpuModel(shape, T, T + S) as m:
         m.load_from_generator(0, scale=8.0)
         kv_a, _ = m.partial(hidden_in, 1, 3, kv_r, [T], n_rows=T + S)
         h_a = m.suffix(xs, kv_a, [T], [S])
@@ -239,5 +239,5 @@ def test_argument_errors(G):
         torch.cuda.synchronize()
     bad = synth.ModelShape(2, 64, 6, 4, 16, 64, 1e4, 1e-5, "f32")
     with pytest.raises(B.DskError) as e:
-        B.dsk_model_create(B.config_from_shape(bad), 8)
+        B.dsk_model_create(B.config_from_shape(bad), 8, 8)
     assert e.value.status == B.DSK_ESHAPE
