@@ -86,6 +86,7 @@ inline char* kv_v(const dsk_kv_t* kv, int l) { return kv_k(kv, l) + kv->v_offset
 
 int g_force_generic = 0;
 int g_time_gemm = 0;
+int g_linear_ld_pad = 0;  // experiment knob: dsk_linear reads x and w with row stride K + pad
 
 // launch counters and the event pairs recorded under "time_gemm"
 struct Stats {
@@ -493,7 +494,7 @@ int dsk_linear(int dtype, const void* x, const void* w, void* y, const void* r, 
   if (dtype != DSK_F32 && dtype != DSK_BF16) return DSK_EDTYPE;
   if (!aligned16(x) || !aligned16(w) || !aligned16(y) || !aligned16(r)) return DSK_EINVAL;
   const int epi = r ? EPI_RESIDUAL : EPI_STORE;
-  HIP_TRY(gemm_any(dtype, x, K, w, K, y, N, r, N, M, N, K, epi, (hipStream_t)stream));
+  HIP_TRY(gemm_any(dtype, x, K + g_linear_ld_pad, w, K + g_linear_ld_pad, y, N, r, N, M, N, K, epi, (hipStream_t)stream));
   return DSK_OK;
 }
 
@@ -535,6 +536,7 @@ int dsk_set_option(const char* name, int value) {
   else if (!strcmp(name, "attn_variant")) attn_mfma_set_variant(value);
   else if (!strcmp(name, "force_generic")) g_force_generic = value;
   else if (!strcmp(name, "time_gemm")) g_time_gemm = value;
+  else if (!strcmp(name, "linear_ld_pad")) g_linear_ld_pad = value;
   else if (!strcmp(name, "reset_stats")) {
     g_stats.gemm_mfma = g_stats.gemm_generic = g_stats.attn_mfma = g_stats.attn_generic = 0;
     g_stats.n_timed = 0;
