@@ -45,7 +45,7 @@ void free_model(dsk_model* m) {
     free(m->layers);
   }
   (void)hipFree(m->xn); (void)hipFree(m->qkv); (void)hipFree(m->attn); (void)hipFree(m->gu);
-  (void)hipFree(m->act); (void)hipFree(m->h); (void)hipFree(m->rope_cs); (void)hipFree(m->theta); (void)hipFree(m->vt);
+  (void)hipFree(m->act); (void)hipFree(m->h); (void)hipFree(m->rope_cs); (void)hipFree(m->theta); (void)hipFree(m->vt); (void)hipFree(m->gemm_ws);
   if (m->ev_kv) {
     for (int l = 0; l < m->cfg.n_layers; ++l)
       if (m->ev_kv[l]) (void)hipEventDestroy(m->ev_kv[l]);
@@ -98,7 +98,7 @@ struct Stats {
 } g_stats;
 
 hipError_t gemm_any(int dtype, const void* A, int64_t lda, const void* W, int64_t ldw, void* C, int64_t ldc,
-                    const void* R, int64_t ldr, int M, int N, int K, int epi, hipStream_t s) {
+                    const void* R, int64_t ldr, int M, int N, int K, int epi, void* ws, int64_t ws_bytes, hipStream_t s) {
   if (dtype == DSK_BF16 && !g_force_generic) {
     const bool timed = g_time_gemm && M >= 1024 && g_stats.n_timed < Stats::kMaxTimed;
     if (timed) {
@@ -113,7 +113,7 @@ hipError_t gemm_any(int dtype, const void* A, int64_t lda, const void* W, int64_
       hipError_t ee = hipEventRecord(g_stats.ev[2 * g_stats.n_timed], s);
       if (ee != hipSuccess) return ee;
     }
-    hipError_t e = launch_gemm_mfma_bf16(A, lda, W, ldw, C, ldc, R, ldr, M, N, K, epi, s);
+    hipError_t e = launch_gemm_mfma_bf16(A, lda, W, ldw, C, ldc, R, ldr, M, N, K, epi, ws, ws_bytes, s);
     if (e != hipErrorNotSupported) {
       if (e == hipSuccess) {
         ++g_stats.gemm_mfma;
@@ -132,7 +132,7 @@ hipError_t gemm_any(int dtype, const void* A, int64_t lda, const void* W, int64_
 
 hipError_t gemm(const dsk_model* m, const void* A, int64_t lda, const void* W, int64_t ldw, void* C, int64_t ldc,
                 const void* R, int64_t ldr, int M, int N, int K, int epi, hipStream_t s) {
-  return gemm_any(m->cfg.dtype, A, lda, W, ldw, C, ldc, R, ldr, M, N, K, epi, s);
+  return gemm_any(m->cfg.dtype, A, lda, W, ldw, C, ldc, R, ldr, M, N, K, epi, m->gemm_ws, m->gemm_ws_bytes, s);
 }
 
 hipError_t attention_any(int dtype, const AttnArgs& a, hipStream_t s) {
@@ -261,6 +261,12 @@ int dsk_model_create(const dsk_config_t* cfg, int64_t max_tokens, int64_t max_kv
   const int64_t kvw = (int64_t)cfg->n_kv_heads * cfg->head_dim;
   if (rc == DSK_OK && cfg->dtype == DSK_BF16 && kvw % 64 == 0 && (cfg->head_dim == 64 || cfg->head_dim == 128))
     rc = alloc_dev(&m->vt, kvw * m->ldvt * elem, &m->workspace_bytes);
+  if (rc == DSK_OK && cfg->dtype == DSK_BF16) {
+    int max_n = m->n_qkv > 2 * cfg->ffn ? m->n_qkv : 2 * cfg->ffn;
+    if (cfg->hidden > max_n) max_n = cfg->hidden;
+    m->gemm_ws_bytes = gemm_mfma_workspace_bytes(max_n);
+    rc = alloc_dev(&m->gemm_ws, m->gemm_ws_bytes, &m->workspace_bytes);
+  }
   if (rc == DSK_OK) {
     double* th = (double*)malloc(half * sizeof(double));
     if (!th) rc = DSK_ENOMEM;
@@ -494,7 +500,7 @@ int dsk_linear(int dtype, const void* x, const void* w, void* y, const void* r, 
   if (dtype != DSK_F32 && dtype != DSK_BF16) return DSK_EDTYPE;
   if (!aligned16(x) || !aligned16(w) || !aligned16(y) || !aligned16(r)) return DSK_EINVAL;
   const int epi = r ? EPI_RESIDUAL : EPI_STORE;
-  HIP_TRY(gemm_any(dtype, x, K + g_linear_ld_pad, w, K + g_linear_ld_pad, y, N, r, N, M, N, K, epi, (hipStream_t)stream));
+  HIP_TRY(gemm_any(dtype, x, K + g_linear_ld_pad, w, K + g_linear_ld_pad, y, N, r, N, M, N, K, epi, nullptr, 0, (hipStream_t)stream));
   return DSK_OK;
 }
 

@@ -48,6 +48,8 @@ struct dsk_model {
   double* theta;    // [dh/2]         rope_base^(-2i/dh)
   void* vt;         // [Hkv*dh, ldvt] transposed V of the layer in flight (bf16 MFMA attention)
   int64_t ldvt;     // max_kv_rows rounded up to 64
+  void* gemm_ws;    // fp32 partial tiles of the K-split small-M GEMM
+  int64_t gemm_ws_bytes;
   int64_t workspace_bytes;
   // load pipeline
   hipStream_t load_stream;
@@ -66,8 +68,11 @@ enum { EPI_STORE = 0, EPI_RESIDUAL = 1 };
 hipError_t launch_gemm_generic(int dtype, const void* A, int64_t lda, const void* W, int64_t ldw, void* C, int64_t ldc,
                                const void* R, int64_t ldr, int M, int N, int K, int epi, hipStream_t s);
 // bf16 MFMA GEMM; returns hipErrorNotSupported when the shape is outside what it handles.
+// ws: optional fp32 scratch for the K-split partial tiles of the small-M path (see gemm_mfma_workspace_bytes).
 hipError_t launch_gemm_mfma_bf16(const void* A, int64_t lda, const void* W, int64_t ldw, void* C, int64_t ldc,
-                                 const void* R, int64_t ldr, int M, int N, int K, int epi, hipStream_t s);
+                                 const void* R, int64_t ldr, int M, int N, int K, int epi, void* ws, int64_t ws_bytes,
+                                 hipStream_t s);
+int64_t gemm_mfma_workspace_bytes(int max_n);
 
 hipError_t launch_rmsnorm(int dtype, const void* x, const void* g, void* y, int T, int d, float eps, hipStream_t s);
 hipError_t launch_rope_table(const int32_t* pos, const double* theta, float2* cs, int T, int half, hipStream_t s);

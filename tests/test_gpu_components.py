@@ -1,0 +1,125 @@
+"""Parity of single steps (projection GEMM, attention) with the oracle, through the C-ABI component calls."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dsk_oracle as O
+from paper_2411_02820_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2411_02820_amd import binding
+    return binding
+
+
+def _bf16(a):
+    return synth.bf16_bits_to_f32(synth.f32_to_bf16_bits(a))
+
+
+# shapes span: several tiles + ragged M tail, small-M weight-streaming path, N not a multiple of the tile, K tail
+@pytest.mark.parametrize("M,N,K,residual", [
+    (300, 512, 256, False), (1000, 768, 512, True), (64, 1024, 2048, True), (17, 4096, 1024, False),
+    (1, 256, 64, True), (513, 320, 192, False), (130, 6144, 4096, True), (100, 96, 100, False),
+])
+def test_linear_bf16(B, M, N, K, residual):
+    x = _bf16(synth.normal(M * K, 11, 0, 1.0).reshape(M, K))
+    w = _bf16(synth.normal(N * K, 11, 1, 0.05).reshape(N, K))
+    r = _bf16(synth.normal(M * N, 11, 2, 1.0).reshape(M, N)) if residual else None
+    ref = x.astype(np.float64) @ w.astype(np.float64).T + (0 if r is None else r.astype(np.float64))
+    dev = lambda a: torch.from_numpy(a).to(torch.bfloat16).cuda()
+    y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    B.dsk_linear(B.DSK_BF16, dev(x), dev(w), y, None if r is None else dev(r), M, N, K)
+    torch.cuda.synchronize()
+    # one bf16 rounding of the result: 2^-9 relative to the element, bounded here by max|ref|
+    assert O.max_rel_err(y.float().cpu().numpy(), ref) <= 2 ** -8
+
+
+@pytest.mark.parametrize("M,N,K", [(70, 96, 40), (128, 64, 256)])
+def test_linear_fp32(B, M, N, K):
+    x = synth.normal(M * K, 12, 0, 1.0).reshape(M, K)
+    w = synth.normal(N * K, 12, 1, 0.05).reshape(N, K)
+    ref = x.astype(np.float64) @ w.astype(np.float64).T
+    y = torch.empty((M, N), dtype=torch.float32, device="cuda")
+    B.dsk_linear(B.DSK_F32, torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda(), y, None, M, N, K)
+    torch.cuda.synchronize()
+    assert O.max_rel_err(y.cpu().numpy(), ref) <= 1e-5
+
+
+def test_linear_in_place_residual(B):
+    M, N, K = 64, 512, 512
+    x = _bf16(synth.normal(M * K, 13, 0, 1.0).reshape(M, K))
+    w = _bf16(synth.normal(N * K, 13, 1, 0.05).reshape(N, K))
+    r = _bf16(synth.normal(M * N, 13, 2, 1.0).reshape(M, N))
+    ref = x.astype(np.float64) @ w.astype(np.float64).T + r
+    dev = lambda a: torch.from_numpy(a).to(torch.bfloat16).cuda()
+    y = dev(r)
+    B.dsk_linear(B.DSK_BF16, dev(x), dev(w), y, y, M, N, K)
+    torch.cuda.synchronize()
+    assert O.max_rel_err(y.float().cpu().numpy(), ref) <= 2 ** -8
+
+
+def _attention_case(B, lens, plens, Hq, Hkv, dh, dtype, use_scratch):
+    from paper_2411_02820_amd import binding
+    cu = synth.cu_seqlens(lens)
+    n_q = int(cu[-1])
+    pcu = synth.cu_seqlens(plens) if plens else None
+    n_pre = int(pcu[-1]) if plens else 0
+    own_row0 = n_pre + 3 if plens else 0          # a gap between the two ranges
+    rows = own_row0 + n_q
+    rnd = (lambda a: _bf16(a)) if dtype == "bf16" else (lambda a: a)
+    q = rnd(synth.normal(n_q * Hq * dh, 21, 0, 1.0).reshape(n_q, Hq, dh))
+    k = rnd(synth.normal(rows * Hkv * dh, 21, 1, 1.0).reshape(rows, Hkv, dh))
+    v = rnd(synth.normal(rows * Hkv * dh, 21, 2, 1.0).reshape(rows, Hkv, dh))
+    seq = np.repeat(np.arange(len(lens)), lens)
+    ref = np.empty((n_q, Hq, dh))
+    for i in range(n_q):
+        b = seq[i]
+        vis = list(range(pcu[b], pcu[b + 1])) if plens else []
+        vis += list(range(own_row0 + cu[b], own_row0 + i + 1))
+        ref[i] = O.attend_row(q[i].astype(np.float64), k[vis].astype(np.float64), v[vis].astype(np.float64))
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(tdt).cuda()
+    out = torch.empty((n_q, Hq * dh), dtype=tdt, device="cuda")
+    qb = binding.Batch(cu)
+    pb = binding.Batch(pcu) if plens else None
+    scratch = torch.empty(Hkv * dh * ((rows + 63) // 64 * 64), dtype=tdt, device="cuda") if use_scratch else None
+    B.dsk_set_option("reset_stats", 0)
+    B.dsk_attention(B.DSK_BF16 if dtype == "bf16" else B.DSK_F32, dev(q), dev(k), dev(v), out, qb.desc,
+                    None if pb is None else pb.desc, own_row0, Hq, Hkv, dh, scratch)
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy().reshape(n_q, Hq, dh)
+    return O.max_rel_err(got, ref)
+
+
+@pytest.mark.parametrize("lens,plens", [([300], None), ([129, 1, 64, 200], None), ([40, 7], [200, 130]), ([1], [65])])
+def test_attention_bf16_tensor_core_kernel(B, lens, plens):
+    err = _attention_case(B, lens, plens, 8, 2, 128, "bf16", True)
+    assert B.dsk_get_stat("attn_mfma_launches") == 1, "the MFMA kernel must be the one that ran"
+    assert err <= 1e-2
+
+
+def test_attention_bf16_dh64_and_mha(B):
+    assert _attention_case(B, [150, 70], None, 4, 4, 64, "bf16", True) <= 1e-2
+    assert B.dsk_get_stat("attn_mfma_launches") == 1
+
+
+def test_attention_plain_kernel_both_dtypes(B):
+    assert _attention_case(B, [90, 33], [50, 20], 4, 2, 64, "f32", False) <= 1e-5
+    assert _attention_case(B, [90, 33], [50, 20], 4, 2, 64, "bf16", False) <= 1e-2
+    assert B.dsk_get_stat("attn_generic_launches") == 1
+
+
+def test_bf16_model_runs_on_tensor_core_kernels(B):
+    from tests import gpu_util as G
+    shape = synth.ModelShape(2, 512, 8, 2, 128, 1536, 500000.0, 1e-5, "bf16")
+    T = 200
+    with G.GpuModel(shape, T) as m:
+        m.init_random(0)
+        B.dsk_set_option("reset_stats", 0)
+        m.partial(G.to_dev(synth.hidden_states(shape, T), shape), 0, 2, None, [T])
+        torch.cuda.synchronize()
+        assert B.dsk_get_stat("gemm_mfma_launches") == 8 and B.dsk_get_stat("gemm_generic_launches") == 0
+        assert B.dsk_get_stat("attn_mfma_launches") == 2 and B.dsk_get_stat("attn_generic_launches") == 0
