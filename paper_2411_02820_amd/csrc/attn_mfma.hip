@@ -3,9 +3,12 @@
 // queries' own causal range), online softmax in fp32.
 //
 // A workgroup (4 waves) owns 128 query rows of one (sequence, q head); each wave 32 of them.
-// Keys are walked in tiles of 64 cache rows (aligned to multiples of 64), staged in LDS:
+// Keys are walked in tiles of 64 cache rows (aligned to multiples of 64), staged in a two-stage LDS ring
+// by direct global->LDS loads (global_load_lds_dwordx4):
 //   K tile  [64 keys][dh]   - rows permuted (bits 2 and 3 of the key offset swapped), see below
 //   Vt tile [dh][64 keys]   - from a transposed copy of V kept in the model's workspace
+// Both the row permutation and the 16-byte slot swizzle are applied on the global side (which address a
+// lane fetches), since the LDS destination of such a load is fixed by the lane id.
 // Scores are computed transposed, S^T = K Q^T, with v_mfma_f32_32x32x16_bf16 (K rows as the MFMA A
 // operand, Q rows as B): a lane then owns ONE query (column lane%32) and 16 keys per 32-key tile in its
 // accumulator registers, so the softmax row maximum/sum are in-lane reductions plus a single exchange
@@ -13,6 +16,10 @@
 // (16t + 8*(lane/32) + 0..7), i.e. exactly the B-operand layout of P^T for O^T += Vt P^T, and the
 // matching Vt fragment is one 16-byte LDS read.  The output accumulator O^T[d][q] keeps the query in the
 // lane as well, so rescaling by the running maximum is a per-lane scalar multiply.
+//
+// Few queries against many keys (the suffix pass) would leave most CUs idle, so the key tiles of a
+// workgroup can be split over blockIdx.z; each split writes its unnormalised fp32 output with its running
+// maximum and sum, and a second kernel merges the splits in a fixed order.
 #include "dsk_internal.h"
 
 namespace {
@@ -20,7 +27,7 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 constexpr int BQ = 128;  // query rows per workgroup
 constexpr int BKV = 64;  // keys per tile
@@ -29,24 +36,28 @@ struct AttnParams {
   const bf16_t* q; int64_t ldq;
   const bf16_t* k; const bf16_t* vt; int64_t ldvt;
   bf16_t* out;
+  float* part_o; float* part_ml;  // split mode: [n_q][Hq][splits][dh] and [n_q][Hq][splits][2]
   const int32_t* q_cu; const int32_t* p_cu;
-  int n_seqs; int64_t own_row0; int Hq, Hkv; int total_tiles;
-  float c;              // softmax scale * log2(e)
-  int64_t k_row_max;    // last cache row that may be read
+  int n_seqs; int own_row0; int Hq, Hkv; int total_tiles; int splits;
+  float c;         // softmax scale * log2(e)
+  int k_row_max;   // last cache row that may be read
 };
 
-// MFMA row of key offset u inside a 64-key tile: bits 2 and 3 swapped
+// MFMA row of key offset u inside a 64-key tile: bits 2 and 3 swapped (an involution)
 __device__ __forceinline__ int perm_key(int u) { return (u & ~0xC) | ((u & 4) << 1) | ((u & 8) >> 1); }
 
-template <int DH>
-__global__ void __launch_bounds__(256) attn_bf16_kernel(AttnParams p) {
-  constexpr int KCH = DH / 8;            // 16-byte chunks per K row
-  constexpr int K_LOADS = BKV * KCH / 256, V_LOADS = DH * (BKV / 8) / 256;
+template <int DH, bool SPLIT>
+__global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
+  constexpr int KCH = DH / 8;             // 16-byte slots per K row
+  constexpr int K_RPI = 64 / KCH;         // K rows per wave load instruction
+  constexpr int K_INST = BKV / K_RPI / 4; // per wave
+  constexpr int V_INST = DH / 8 / 4;      // Vt rows are 64 keys = 8 slots -> 8 rows per instruction
   constexpr int NKS = DH / 16, NDT = DH / 32;
   __shared__ __attribute__((aligned(16))) bf16_t sK[2][BKV * DH];
   __shared__ __attribute__((aligned(16))) bf16_t sV[2][DH * BKV];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lq = lane & 31, hh = lane >> 5;
   const int h = blockIdx.y, kvh = h / (p.Hq / p.Hkv);
 
@@ -60,21 +71,28 @@ __global__ void __launch_bounds__(256) attn_bf16_kernel(AttnParams p) {
     if (tile < nt || b + 1 >= p.n_seqs) break;
     tile -= nt;
   }
-  const int q0 = seq_begin + tile * BQ;          // first query row (packed index) of this workgroup
-  if (q0 >= seq_end) return;                      // cannot happen for a well-formed grid
-  const int qw0 = q0 + 32 * wave;                 // first query row of this wave
+  const int q0 = seq_begin + tile * BQ;  // first query row (packed index) of this workgroup
+  if (q0 >= seq_end) return;              // cannot happen for a well-formed grid
+  const int qw0 = q0 + 32 * wave;         // first query row of this wave
   const bool wave_active = qw0 < seq_end;
-  const int qi = min(qw0 + lq, seq_end - 1);      // this lane's query (clamped for the padding rows)
+  const int qi = min(qw0 + lq, seq_end - 1);  // this lane's query (clamped for the padding rows)
 
-  const int64_t own_begin = p.own_row0 + seq_begin;
-  const int64_t lim = p.own_row0 + qi;                                   // last own row this lane's query sees
-  const int64_t wave_lim_min = p.own_row0 + min(qw0, seq_end - 1);       // smallest limit in the wave
-  const int64_t wave_lim_max = p.own_row0 + min(qw0 + 31, seq_end - 1);  // largest limit in the wave
-  const int64_t blk_lim = p.own_row0 + min(q0 + BQ, seq_end) - 1;
-  const int64_t pre_begin = p.p_cu ? p.p_cu[b] : 0, pre_end = p.p_cu ? p.p_cu[b + 1] : 0;
-  const int ta0 = (int)(pre_begin / BKV), nA = pre_end > pre_begin ? (int)((pre_end - 1) / BKV) - ta0 + 1 : 0;
-  const int tb0 = (int)(own_begin / BKV), nB = (int)(blk_lim / BKV) - tb0 + 1;
+  const int own_begin = p.own_row0 + seq_begin;
+  const int lim = p.own_row0 + qi;                                   // last own row this lane's query sees
+  const int wave_lim_min = p.own_row0 + min(qw0, seq_end - 1);       // smallest limit in the wave
+  const int wave_lim_max = p.own_row0 + min(qw0 + 31, seq_end - 1);  // largest limit in the wave
+  const int blk_lim = p.own_row0 + min(q0 + BQ, seq_end) - 1;
+  const int pre_begin = p.p_cu ? p.p_cu[b] : 0, pre_end = p.p_cu ? p.p_cu[b + 1] : 0;
+  const int ta0 = pre_begin / BKV, nA = pre_end > pre_begin ? (pre_end - 1) / BKV - ta0 + 1 : 0;
+  const int tb0 = own_begin / BKV, nB = blk_lim / BKV - tb0 + 1;
   const int n_tiles = nA + nB;
+  // key-tile range of this split
+  int it_begin = 0, it_end = n_tiles;
+  if (SPLIT) {
+    const int per = (n_tiles + p.splits - 1) / p.splits;
+    it_begin = min(n_tiles, (int)blockIdx.z * per);
+    it_end = min(n_tiles, it_begin + per);
+  }
 
   // ---- Q fragments (B operand): query = lane%32, d = 16*ks + 8*(lane/32) .. +7 ----
   bf16x8 qf[NKS];
@@ -84,40 +102,38 @@ __global__ void __launch_bounds__(256) attn_bf16_kernel(AttnParams p) {
     for (int ks = 0; ks < NKS; ++ks) qf[ks] = *(const bf16x8*)(qp + 16 * ks);
   }
 
-  // ---- tile loads: global -> registers -> LDS ----
+  // ---- tile loads, direct to LDS.  K: LDS row rho (MFMA row) holds key offset perm_key(rho); slot s of a
+  //      row holds chunk s ^ (rho & 7).  Vt: LDS row d, slot s holds key chunk s ^ (d & 7). ----
   const int64_t ldkv = (int64_t)p.Hkv * DH;
-  u32x4 k_reg[K_LOADS], v_reg[V_LOADS];
-  int k_lds[K_LOADS], v_lds[V_LOADS], k_u[K_LOADS], k_ch[K_LOADS];
-  const bf16_t* v_ptr[V_LOADS];
+  const bf16_t* k_base = p.k + kvh * DH;
+  int k_u[K_INST], k_coff[K_INST];
+  const bf16_t* v_src[V_INST];
 #pragma unroll
-  for (int i = 0; i < K_LOADS; ++i) {
-    int id = tid + i * 256, u = id / KCH, ch = id % KCH, r = perm_key(u);
-    k_u[i] = u;
-    k_ch[i] = ch;
-    k_lds[i] = r * DH + ((ch ^ (r & 7)) * 8);
+  for (int i = 0; i < K_INST; ++i) {
+    const int rho = K_RPI * (wave * K_INST + i) + lane / KCH, s = lane % KCH;
+    k_u[i] = perm_key(rho);
+    k_coff[i] = (s ^ (rho & 7)) * 8;
   }
 #pragma unroll
-  for (int i = 0; i < V_LOADS; ++i) {
-    int id = tid + i * 256, d = id / 8, ch = id % 8;
-    v_ptr[i] = p.vt + ((int64_t)kvh * DH + d) * p.ldvt + ch * 8;
-    v_lds[i] = d * BKV + ((ch ^ (d & 7)) * 8);
+  for (int i = 0; i < V_INST; ++i) {
+    const int d = 8 * (wave * V_INST + i) + (lane >> 3), s = lane & 7;
+    v_src[i] = p.vt + ((int64_t)kvh * DH + d) * p.ldvt + (s ^ (d & 7)) * 8;
   }
-  auto tile_row0 = [&](int it) -> int64_t { return (int64_t)(it < nA ? ta0 + it : tb0 + (it - nA)) * BKV; };
-  auto load_global = [&](int it) {
-    const int64_t r0 = tile_row0(it);
+  typedef __attribute__((address_space(3))) void lds_void;
+  typedef const __attribute__((address_space(1))) void glb_void;
+  auto tile_row0 = [&](int it) { return (it < nA ? ta0 + it : tb0 + (it - nA)) * BKV; };
+  auto issue_loads = [&](int stage, int it) {
+    const int r0 = tile_row0(it);
 #pragma unroll
-    for (int i = 0; i < K_LOADS; ++i) {
-      int64_t row = min(r0 + k_u[i], p.k_row_max);
-      k_reg[i] = *(const u32x4*)(p.k + row * ldkv + kvh * DH + k_ch[i] * 8);
+    for (int i = 0; i < K_INST; ++i) {
+      const int row = min(r0 + k_u[i], p.k_row_max);
+      __builtin_amdgcn_global_load_lds((glb_void*)(k_base + (int64_t)row * ldkv + k_coff[i]),
+                                       (lds_void*)(&sK[stage][K_RPI * (wave * K_INST + i) * DH]), 16, 0, 0);
     }
 #pragma unroll
-    for (int i = 0; i < V_LOADS; ++i) v_reg[i] = *(const u32x4*)(v_ptr[i] + r0);
-  };
-  auto store_lds = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < K_LOADS; ++i) *(u32x4*)(&sK[buf][k_lds[i]]) = k_reg[i];
-#pragma unroll
-    for (int i = 0; i < V_LOADS; ++i) *(u32x4*)(&sV[buf][v_lds[i]]) = v_reg[i];
+    for (int i = 0; i < V_INST; ++i)
+      __builtin_amdgcn_global_load_lds((glb_void*)(v_src[i] + r0),
+                                       (lds_void*)(&sV[stage][8 * (wave * V_INST + i) * BKV]), 16, 0, 0);
   };
 
   f32x16 o[NDT];
@@ -127,18 +143,19 @@ __global__ void __launch_bounds__(256) attn_bf16_kernel(AttnParams p) {
     for (int r = 0; r < 16; ++r) o[dt][r] = 0.f;
   float m = -INFINITY, l = 0.f;
 
-  load_global(0);
-  store_lds(0);
-  __syncthreads();
-  for (int it = 0; it < n_tiles; ++it) {
-    const bool more = it + 1 < n_tiles;
-    if (more) load_global(it + 1);
-    const int buf = it & 1;
-    const int64_t r0 = tile_row0(it);
+  if (it_begin < it_end) {
+    issue_loads(0, it_begin);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+  }
+  for (int it = it_begin; it < it_end; ++it) {
+    const int stage = (it - it_begin) & 1;
+    if (it + 1 < it_end) issue_loads(stage ^ 1, it + 1);
+    const int r0 = tile_row0(it);
     const bool segA = it < nA;
     // visible key rows for this lane in this segment: [lo, hi]
-    const int64_t lo = segA ? pre_begin : own_begin;
-    const int64_t hi = segA ? pre_end - 1 : lim;
+    const int lo = segA ? pre_begin : own_begin;
+    const int hi = segA ? pre_end - 1 : lim;
     const bool skip = !wave_active || (!segA && r0 > wave_lim_max);
     if (!skip) {
       // S^T = K Q^T for the two 32-key halves of the tile
@@ -148,20 +165,22 @@ __global__ void __launch_bounds__(256) attn_bf16_kernel(AttnParams p) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[kt][r] = 0.f;
         const int row = 32 * kt + lq;
+        const bf16_t* kr = &sK[stage][row * DH];
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
-          bf16x8 kf = *(const bf16x8*)(&sK[buf][row * DH + (((2 * ks + hh) ^ (row & 7)) * 8)]);
+          bf16x8 kf = *(const bf16x8*)(kr + (((2 * ks + hh) ^ (row & 7)) * 8));
           s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kt], 0, 0, 0);
         }
       }
       // mask: register r of half kt is key r0 + 32*kt + 16*(r/8) + 8*(lane/32) + r%8
       const bool full = r0 >= lo && r0 + BKV - 1 <= (segA ? pre_end - 1 : wave_lim_min);
       if (!full) {
+        const int kb = r0 + 8 * hh;
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            int64_t key = r0 + 32 * kt + 16 * (r >> 3) + 8 * hh + (r & 7);
+            const int key = kb + 32 * kt + 16 * (r >> 3) + (r & 7);
             s[kt][r] = (key >= lo && key <= hi) ? s[kt][r] : -INFINITY;
           }
       }
@@ -196,34 +215,74 @@ __global__ void __launch_bounds__(256) attn_bf16_kernel(AttnParams p) {
 #pragma unroll
       for (int dt = 0; dt < NDT; ++dt) {
         const int d = 32 * dt + lq;
+        const bf16_t* vr = &sV[stage][d * BKV];
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
           for (int t = 0; t < 2; ++t) {
-            bf16x8 vf = *(const bf16x8*)(&sV[buf][d * BKV + (((4 * kt + 2 * t + hh) ^ (d & 7)) * 8)]);
+            bf16x8 vf = *(const bf16x8*)(vr + (((4 * kt + 2 * t + hh) ^ (d & 7)) * 8));
             o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kt][t], o[dt], 0, 0, 0);
           }
       }
     }
-    if (more) store_lds((it + 1) & 1);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
   }
 
-  // ---- normalise and store: register 4g+e of d-tile dt is out[q][32dt + 8g + 4*(lane/32) + e] ----
+  // ---- store: register 4g+e of d-tile dt is out[q][32dt + 8g + 4*(lane/32) + e] ----
   const float l_tot = l + __shfl_xor(l, 32, 64);
   if (wave_active && qw0 + lq < seq_end) {
-    const float inv = 1.0f / l_tot;
-    bf16_t* op = p.out + (int64_t)(qw0 + lq) * p.Hq * DH + h * DH;
+    const int64_t qrow = qw0 + lq;
+    if (SPLIT) {
+      float* po = p.part_o + ((qrow * p.Hq + h) * p.splits + blockIdx.z) * DH;
 #pragma unroll
-    for (int dt = 0; dt < NDT; ++dt)
+      for (int dt = 0; dt < NDT; ++dt)
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        bf16x4 v;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = (bf16_t)(o[dt][4 * g + e] * inv);
-        *(bf16x4*)(op + 32 * dt + 8 * g + 4 * hh) = v;
+        for (int g = 0; g < 4; ++g) {
+          f32x4 v = {o[dt][4 * g], o[dt][4 * g + 1], o[dt][4 * g + 2], o[dt][4 * g + 3]};
+          *(f32x4*)(po + 32 * dt + 8 * g + 4 * hh) = v;
+        }
+      if (hh == 0) {
+        float* pm = p.part_ml + ((qrow * p.Hq + h) * p.splits + blockIdx.z) * 2;
+        pm[0] = m;
+        pm[1] = l_tot;
       }
+    } else {
+      const float inv = 1.0f / l_tot;
+      bf16_t* op = p.out + qrow * p.Hq * DH + h * DH;
+#pragma unroll
+      for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          bf16x4 v;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = (bf16_t)(o[dt][4 * g + e] * inv);
+          *(bf16x4*)(op + 32 * dt + 8 * g + 4 * hh) = v;
+        }
+    }
   }
+}
+
+// out[q][h][:] = sum_s o_s * 2^((m_s - M) c) / sum_s l_s * 2^((m_s - M) c), M = max_s m_s; one wave per (q, h).
+template <int DH>
+__global__ void __launch_bounds__(64) attn_combine_kernel(const float* __restrict__ part_o, const float* __restrict__ part_ml,
+                                                          bf16_t* __restrict__ out, int Hq, int splits, float c) {
+  const int64_t qh = (int64_t)blockIdx.x * Hq + blockIdx.y;
+  const float* ml = part_ml + qh * splits * 2;
+  float M = -INFINITY;
+  for (int s = 0; s < splits; ++s) M = fmaxf(M, ml[2 * s]);
+  float den = 0.f, acc[DH / 64] = {};
+  for (int s = 0; s < splits; ++s) {
+    const float ms = ml[2 * s];
+    if (ms == -INFINITY) continue;  // this split saw no visible key
+    const float w = __builtin_amdgcn_exp2f((ms - M) * c);
+    den += ml[2 * s + 1] * w;
+#pragma unroll
+    for (int a = 0; a < DH / 64; ++a) acc[a] += part_o[(qh * splits + s) * DH + threadIdx.x + 64 * a] * w;
+  }
+  const float inv = 1.0f / den;
+#pragma unroll
+  for (int a = 0; a < DH / 64; ++a) out[qh * DH + threadIdx.x + 64 * a] = (bf16_t)(acc[a] * inv);
 }
 
 // Vt[(kvh*dh + d)*ldvt + row] = V[row][kvh*dh + d] for the valid rows, 0 for the others, over whole
@@ -264,9 +323,15 @@ __global__ void __launch_bounds__(256) transpose_v_kernel(const bf16_t* __restri
   }
 }
 
+int g_variant = 0;
+
 }  // namespace
 
-void attn_mfma_set_variant(int) {}
+void attn_mfma_set_variant(int v) { g_variant = v; }
+
+// fp32 scratch for the split mode: n_q * splits <= kMaxSplitRows partial rows of (dh + 2) floats per q head
+constexpr int64_t kMaxSplitRows = 4096;
+int64_t attn_mfma_workspace_bytes(int Hq, int dh) { return kMaxSplitRows * Hq * (dh + 2) * 4; }
 
 hipError_t launch_transpose_v(const void* v_rows, void* vt, int64_t ldvt, int width, int64_t n_pre, int64_t own_row0,
                               int64_t n_own, hipStream_t s) {
@@ -280,18 +345,55 @@ hipError_t launch_transpose_v(const void* v_rows, void* vt, int64_t ldvt, int wi
 
 hipError_t launch_attn_mfma_bf16(const AttnArgs& a, hipStream_t s) {
   if (a.n_q <= 0) return hipSuccess;
-  if ((a.dh != 128 && a.dh != 64) || !a.vt || (a.ldq & 7)) return hipErrorNotSupported;
+  if ((a.dh != 128 && a.dh != 64) || !a.vt || (a.ldq & 7) || a.own_row0 + a.n_q >= ((int64_t)1 << 31))
+    return hipErrorNotSupported;
   AttnParams p;
   p.q = (const bf16_t*)a.q; p.ldq = a.ldq; p.k = (const bf16_t*)a.k_rows; p.vt = (const bf16_t*)a.vt; p.ldvt = a.ldvt;
-  p.out = (bf16_t*)a.out; p.q_cu = a.q_cu; p.p_cu = a.p_cu; p.n_seqs = a.n_seqs; p.own_row0 = a.own_row0;
+  p.out = (bf16_t*)a.out; p.q_cu = a.q_cu; p.p_cu = a.p_cu; p.n_seqs = a.n_seqs; p.own_row0 = (int)a.own_row0;
   p.Hq = a.Hq; p.Hkv = a.Hkv;
   int total = 0;
-  for (int b = 0; b < a.n_seqs; ++b) total += (a.q_cu_host[b + 1] - a.q_cu_host[b] + BQ - 1) / BQ;
+  int64_t max_keys = 0;
+  for (int b = 0; b < a.n_seqs; ++b) {
+    const int len = a.q_cu_host[b + 1] - a.q_cu_host[b];
+    total += (len + BQ - 1) / BQ;
+    int64_t keys = len + (a.p_cu_host ? a.p_cu_host[b + 1] - a.p_cu_host[b] : 0);
+    if (keys > max_keys) max_keys = keys;
+  }
   p.total_tiles = total;
   p.c = (float)(1.4426950408889634 / sqrt((double)a.dh));
-  p.k_row_max = a.own_row0 + a.n_q - 1;
+  p.k_row_max = (int)(a.own_row0 + a.n_q - 1);
+  // split the key tiles when the grid alone cannot fill the chip
+  int splits = 1;
+  const int64_t blocks = (int64_t)total * a.Hq;
+  const int key_tiles = (int)((max_keys + BKV - 1) / BKV) + 1;
+  if (a.ws && blocks < 512 && key_tiles >= 8) {
+    splits = (int)((1024 + blocks - 1) / blocks);
+    if (splits > key_tiles / 4) splits = key_tiles / 4;
+    while (splits > 1 && ((int64_t)a.n_q * splits > kMaxSplitRows ||
+                          (int64_t)a.n_q * splits * a.Hq * (a.dh + 2) * 4 > a.ws_bytes))
+      --splits;
+  }
+  if (g_variant == 1) splits = 1;
+  p.splits = splits;
+  p.part_o = nullptr;
+  p.part_ml = nullptr;
+  if (splits > 1) {
+    p.part_o = (float*)a.ws;
+    p.part_ml = p.part_o + (int64_t)a.n_q * a.Hq * splits * a.dh;
+    dim3 grid(total, a.Hq, splits);
+    if (a.dh == 128) hipLaunchKernelGGL((attn_bf16_kernel<128, true>), grid, dim3(256), 0, s, p);
+    else hipLaunchKernelGGL((attn_bf16_kernel<64, true>), grid, dim3(256), 0, s, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    dim3 cgrid(a.n_q, a.Hq);
+    if (a.dh == 128)
+      hipLaunchKernelGGL(attn_combine_kernel<128>, cgrid, dim3(64), 0, s, p.part_o, p.part_ml, p.out, a.Hq, splits, p.c);
+    else
+      hipLaunchKernelGGL(attn_combine_kernel<64>, cgrid, dim3(64), 0, s, p.part_o, p.part_ml, p.out, a.Hq, splits, p.c);
+    return hipGetLastError();
+  }
   dim3 grid(total, a.Hq);
-  if (a.dh == 128) hipLaunchKernelGGL(attn_bf16_kernel<128>, grid, dim3(256), 0, s, p);
-  else hipLaunchKernelGGL(attn_bf16_kernel<64>, grid, dim3(256), 0, s, p);
+  if (a.dh == 128) hipLaunchKernelGGL((attn_bf16_kernel<128, false>), grid, dim3(256), 0, s, p);
+  else hipLaunchKernelGGL((attn_bf16_kernel<64, false>), grid, dim3(256), 0, s, p);
   return hipGetLastError();
 }

@@ -45,7 +45,7 @@ void free_model(dsk_model* m) {
     free(m->layers);
   }
   (void)hipFree(m->xn); (void)hipFree(m->qkv); (void)hipFree(m->attn); (void)hipFree(m->gu);
-  (void)hipFree(m->act); (void)hipFree(m->h); (void)hipFree(m->rope_cs); (void)hipFree(m->theta); (void)hipFree(m->vt); (void)hipFree(m->gemm_ws);
+  (void)hipFree(m->act); (void)hipFree(m->h); (void)hipFree(m->rope_cs); (void)hipFree(m->theta); (void)hipFree(m->vt); (void)hipFree(m->gemm_ws); (void)hipFree(m->attn_ws);
   if (m->ev_kv) {
     for (int l = 0; l < m->cfg.n_layers; ++l)
       if (m->ev_kv[l]) (void)hipEventDestroy(m->ev_kv[l]);
@@ -153,8 +153,8 @@ hipError_t attention(const dsk_model* m, const AttnArgs& a, hipStream_t s) { ret
 // state leaving the layer is written (may equal h_in).  K/V of the tokens go to rows own_row0.. of the
 // cache layer (k_rows, v_rows); attention additionally sees the prefix rows delimited by p_cu.
 int run_layer(dsk_model* m, int l, const void* h_in, void* h_out, char* k_layer, char* v_layer, int64_t own_row0,
-              const int32_t* q_cu, const int32_t* q_cu_host, const int32_t* p_cu, int64_t n_pre_rows, int n_seqs, int n,
-              hipStream_t s) {
+              const int32_t* q_cu, const int32_t* q_cu_host, const int32_t* p_cu, const int32_t* p_cu_host,
+              int64_t n_pre_rows, int n_seqs, int n, hipStream_t s) {
   const dsk_config_t& c = m->cfg;
   const LayerWeights& w = m->layers[l];
   const int d = c.hidden, F = c.ffn, nq = c.n_q_heads * c.head_dim;
@@ -166,7 +166,8 @@ int run_layer(dsk_model* m, int l, const void* h_in, void* h_out, char* k_layer,
   HIP_TRY(launch_rope_kv_write(c.dtype, m->qkv, m->rope_cs, k_own, v_own, n, c.n_q_heads, c.n_kv_heads, c.head_dim, s));
   AttnArgs a;
   a.q = m->qkv; a.ldq = m->n_qkv; a.k_rows = k_layer; a.v_rows = v_layer; a.out = m->attn;
-  a.q_cu = q_cu; a.p_cu = p_cu; a.q_cu_host = q_cu_host; a.n_seqs = n_seqs; a.own_row0 = own_row0; a.n_q = n;
+  a.q_cu = q_cu; a.p_cu = p_cu; a.q_cu_host = q_cu_host; a.p_cu_host = p_cu_host; a.n_seqs = n_seqs;
+  a.own_row0 = own_row0; a.n_q = n; a.ws = m->attn_ws; a.ws_bytes = m->attn_ws_bytes;
   a.Hq = c.n_q_heads; a.Hkv = c.n_kv_heads; a.dh = c.head_dim;
   a.vt = nullptr; a.ldvt = 0;
   if (m->vt && !g_force_generic) {
@@ -261,6 +262,10 @@ int dsk_model_create(const dsk_config_t* cfg, int64_t max_tokens, int64_t max_kv
   const int64_t kvw = (int64_t)cfg->n_kv_heads * cfg->head_dim;
   if (rc == DSK_OK && cfg->dtype == DSK_BF16 && kvw % 64 == 0 && (cfg->head_dim == 64 || cfg->head_dim == 128))
     rc = alloc_dev(&m->vt, kvw * m->ldvt * elem, &m->workspace_bytes);
+  if (rc == DSK_OK && m->vt) {
+    m->attn_ws_bytes = attn_mfma_workspace_bytes(cfg->n_q_heads, cfg->head_dim);
+    rc = alloc_dev(&m->attn_ws, m->attn_ws_bytes, &m->workspace_bytes);
+  }
   if (rc == DSK_OK && cfg->dtype == DSK_BF16) {
     int max_n = m->n_qkv > 2 * cfg->ffn ? m->n_qkv : 2 * cfg->ffn;
     if (cfg->hidden > max_n) max_n = cfg->hidden;
@@ -429,7 +434,7 @@ int dsk_partial_prefill(dsk_model_t* model, const void* hidden_in, int hidden_in
     for (int l = lo; l < hi; ++l) {
       void* h_next = (l == hi - 1 && hidden_out) ? hidden_out : m->h;
       rc = run_layer(m, l, h_cur, h_next, kv_k(kv_out, l), kv_v(kv_out, l), 0, batch->cu_seqlens_dev,
-                     batch->cu_seqlens_host, nullptr, 0, batch->n_seqs, T, s);
+                     batch->cu_seqlens_host, nullptr, nullptr, 0, batch->n_seqs, T, s);
       if (rc) return rc;
       h_cur = h_next;
     }
@@ -471,7 +476,8 @@ int dsk_suffix_prefill(dsk_model_t* model, const void* suffix_hidden_in, const d
     }
     void* h_next = (l == c.n_layers - 1) ? hidden_out : m->h;
     rc = run_layer(m, l, h_cur, h_next, kv_k(kv, l), kv_v(kv, l), suffix_row0, suffix->cu_seqlens_dev,
-                   suffix->cu_seqlens_host, prefix->cu_seqlens_dev, prefix->n_tokens, suffix->n_seqs, S, s);
+                   suffix->cu_seqlens_host, prefix->cu_seqlens_dev, prefix->cu_seqlens_host, prefix->n_tokens,
+                   suffix->n_seqs, S, s);
     if (rc) return rc;
     h_cur = h_next;
   }
@@ -522,6 +528,8 @@ int dsk_attention(int dtype, const void* q, const void* k_rows, const void* v_ro
   a.q = q; a.ldq = (int64_t)n_q_heads * head_dim; a.k_rows = k_rows; a.v_rows = v_rows; a.out = out;
   a.q_cu = queries->cu_seqlens_dev; a.q_cu_host = queries->cu_seqlens_host;
   a.p_cu = prefix ? prefix->cu_seqlens_dev : nullptr;
+  a.p_cu_host = prefix ? prefix->cu_seqlens_host : nullptr;
+  a.ws = nullptr; a.ws_bytes = 0;
   a.n_seqs = queries->n_seqs; a.own_row0 = own_row0; a.n_q = queries->n_tokens;
   a.Hq = n_q_heads; a.Hkv = n_kv_heads; a.dh = head_dim;
   a.vt = nullptr; a.ldvt = 0;

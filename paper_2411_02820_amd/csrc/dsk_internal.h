@@ -50,6 +50,8 @@ struct dsk_model {
   int64_t ldvt;     // max_kv_rows rounded up to 64
   void* gemm_ws;    // fp32 partial tiles of the K-split small-M GEMM
   int64_t gemm_ws_bytes;
+  void* attn_ws;    // fp32 partial outputs of the key-split attention
+  int64_t attn_ws_bytes;
   int64_t workspace_bytes;
   // load pipeline
   hipStream_t load_stream;
@@ -89,12 +91,14 @@ struct AttnArgs {
   const void* q; int64_t ldq;
   const void* k_rows; const void* v_rows;  // layer base of K and V rows (row stride Hkv*dh)
   void* out;
-  const int32_t* q_cu; const int32_t* p_cu; const int32_t* q_cu_host; int n_seqs;
+  const int32_t* q_cu; const int32_t* p_cu; const int32_t* q_cu_host; const int32_t* p_cu_host; int n_seqs;
   int64_t own_row0; int n_q; int Hq, Hkv, dh;
   const void* vt; int64_t ldvt;  // transposed V (see launch_transpose_v); NULL: not available
+  void* ws; int64_t ws_bytes;    // fp32 scratch for key-split partial results (attn_mfma_workspace_bytes); optional
 };
 hipError_t launch_attn_generic(int dtype, const AttnArgs& a, hipStream_t s);
 hipError_t launch_attn_mfma_bf16(const AttnArgs& a, hipStream_t s);
+int64_t attn_mfma_workspace_bytes(int Hq, int dh);
 // vt[(c)*ldvt + row] = v_rows[row][c] for valid rows (row < n_pre or own_row0 <= row < own_row0+n_own), 0 otherwise,
 // over whole 64-row tiles up to own_row0+n_own; width = Hkv*dh must be a multiple of 64.
 hipError_t launch_transpose_v(const void* v_rows, void* vt, int64_t ldvt, int width, int64_t n_pre, int64_t own_row0,
