@@ -45,7 +45,7 @@ void free_model(dsk_model* m) {
     free(m->layers);
   }
   (void)hipFree(m->xn); (void)hipFree(m->qkv); (void)hipFree(m->attn); (void)hipFree(m->gu);
-  (void)hipFree(m->act); (void)hipFree(m->h); (void)hipFree(m->rope_cs); (void)hipFree(m->theta); (void)hipFree(m->vt); (void)hipFree(m->gemm_ws); (void)hipFree(m->attn_ws);
+  (void)hipFree(m->act); (void)hipFree(m->h); (void)hipFree(m->e_stage); (void)hipFree(m->rope_cs); (void)hipFree(m->theta); (void)hipFree(m->vt); (void)hipFree(m->gemm_ws); (void)hipFree(m->attn_ws);
   if (m->ev_kv) {
     for (int l = 0; l < m->cfg.n_layers; ++l)
       if (m->ev_kv[l]) (void)hipEventDestroy(m->ev_kv[l]);
@@ -152,7 +152,9 @@ hipError_t attention(const dsk_model* m, const AttnArgs& a, hipStream_t s) { ret
 // One decoder layer over n token rows.  h_in: residual stream entering the layer; h_out: where the
 // state leaving the layer is written (may equal h_in).  K/V of the tokens go to rows own_row0.. of the
 // cache layer (k_rows, v_rows); attention additionally sees the prefix rows delimited by p_cu.
-int run_layer(dsk_model* m, int l, const void* h_in, void* h_out, char* k_layer, char* v_layer, int64_t own_row0,
+// h_in is the model dtype unless h_in_f32; h_out likewise unless h_out_f32 (the workspace stream m->h is fp32).
+int run_layer(dsk_model* m, int l, const void* h_in, int h_in_f32, void* h_out, int h_out_f32, char* k_layer,
+              char* v_layer, int64_t own_row0,
               const int32_t* q_cu, const int32_t* q_cu_host, const int32_t* p_cu, const int32_t* p_cu_host,
               int64_t n_pre_rows, int n_seqs, int n, hipStream_t s) {
   const dsk_config_t& c = m->cfg;
@@ -161,7 +163,8 @@ int run_layer(dsk_model* m, int l, const void* h_in, void* h_out, char* k_layer,
   const int64_t row_bytes = (int64_t)c.n_kv_heads * c.head_dim * m->elem;
   char* k_own = k_layer + own_row0 * row_bytes;
   char* v_own = v_layer + own_row0 * row_bytes;
-  HIP_TRY(launch_rmsnorm(c.dtype, h_in, w.g1, m->xn, n, d, (float)c.rms_eps, s));
+  const int all_f32 = c.dtype == DSK_F32;  // an fp32 model: every buffer is fp32 anyway
+  HIP_TRY(launch_rmsnorm(c.dtype, h_in, h_in_f32 || all_f32, w.g1, m->xn, n, d, (float)c.rms_eps, s));
   HIP_TRY(gemm(m, m->xn, d, w.wqkv, d, m->qkv, m->n_qkv, nullptr, 0, n, m->n_qkv, d, EPI_STORE, s));
   HIP_TRY(launch_rope_kv_write(c.dtype, m->qkv, m->rope_cs, k_own, v_own, n, c.n_q_heads, c.n_kv_heads, c.head_dim, s));
   AttnArgs a;
@@ -175,11 +178,13 @@ int run_layer(dsk_model* m, int l, const void* h_in, void* h_out, char* k_layer,
     a.vt = m->vt; a.ldvt = m->ldvt;
   }
   HIP_TRY(attention(m, a, s));
-  HIP_TRY(gemm(m, m->attn, nq, w.wo, nq, m->h, d, h_in, d, n, d, nq, EPI_RESIDUAL, s));
-  HIP_TRY(launch_rmsnorm(c.dtype, m->h, w.g2, m->xn, n, d, (float)c.rms_eps, s));
+  HIP_TRY(gemm(m, m->attn, nq, w.wo, nq, m->h, d, h_in, d, n, d, nq,
+               EPI_RESIDUAL | EPI_C_F32 | ((h_in_f32 || all_f32) ? EPI_R_F32 : 0), s));
+  HIP_TRY(launch_rmsnorm(c.dtype, m->h, 1, w.g2, m->xn, n, d, (float)c.rms_eps, s));
   HIP_TRY(gemm(m, m->xn, d, w.wgu, d, m->gu, 2 * (int64_t)F, nullptr, 0, n, 2 * F, d, EPI_STORE, s));
   HIP_TRY(launch_swiglu(c.dtype, m->gu, m->act, n, F, m->gu_block, s));
-  HIP_TRY(gemm(m, m->act, F, w.wd, F, h_out, d, m->h, d, n, d, F, EPI_RESIDUAL, s));
+  HIP_TRY(gemm(m, m->act, F, w.wd, F, h_out, d, m->h, d, n, d, F,
+               EPI_RESIDUAL | EPI_R_F32 | ((h_out_f32 || all_f32) ? EPI_C_F32 : 0), s));
   return DSK_OK;
 }
 
@@ -256,7 +261,8 @@ int dsk_model_create(const dsk_config_t* cfg, int64_t max_tokens, int64_t max_kv
   if (rc == DSK_OK) rc = alloc_dev(&m->attn, T * nq * elem, &m->workspace_bytes);
   if (rc == DSK_OK) rc = alloc_dev(&m->gu, T * 2 * F * elem, &m->workspace_bytes);
   if (rc == DSK_OK) rc = alloc_dev(&m->act, T * F * elem, &m->workspace_bytes);
-  if (rc == DSK_OK) rc = alloc_dev(&m->h, T * d * elem, &m->workspace_bytes);
+  if (rc == DSK_OK) rc = alloc_dev((void**)&m->h, T * d * 4, &m->workspace_bytes);
+  if (rc == DSK_OK) rc = alloc_dev(&m->e_stage, T * d * elem, &m->workspace_bytes);
   if (rc == DSK_OK) rc = alloc_dev((void**)&m->rope_cs, T * half * (int64_t)sizeof(float2), &m->workspace_bytes);
   if (rc == DSK_OK) rc = alloc_dev((void**)&m->theta, half * (int64_t)sizeof(double), &m->workspace_bytes);
   const int64_t kvw = (int64_t)cfg->n_kv_heads * cfg->head_dim;
@@ -400,10 +406,10 @@ int dsk_partial_prefill(dsk_model_t* model, const void* hidden_in, int hidden_in
   // the E cache goes first (Fig. 13(c)): recomputation can start as soon as it has arrived
   const void* h_cur = hidden_in;
   if (hidden_in_mem == DSK_MEM_HOST_PINNED) {
-    HIP_TRY(hipMemcpyAsync(m->h, hidden_in, (size_t)hid_bytes, hipMemcpyHostToDevice, ls));
+    HIP_TRY(hipMemcpyAsync(m->e_stage, hidden_in, (size_t)hid_bytes, hipMemcpyHostToDevice, ls));
     HIP_TRY(hipEventRecord(m->ev_e, ls));
     HIP_TRY(hipStreamWaitEvent(s, m->ev_e, 0));
-    h_cur = m->h;
+    h_cur = m->e_stage;
   }
 
   // reused layers, ascending (the order the suffix prefill consumes them), one event per layer
@@ -432,8 +438,9 @@ int dsk_partial_prefill(dsk_model_t* model, const void* hidden_in, int hidden_in
   if (hi > lo) {
     HIP_TRY(launch_rope_table(batch->positions_dev, m->theta, m->rope_cs, T, c.head_dim / 2, s));
     for (int l = lo; l < hi; ++l) {
-      void* h_next = (l == hi - 1 && hidden_out) ? hidden_out : m->h;
-      rc = run_layer(m, l, h_cur, h_next, kv_k(kv_out, l), kv_v(kv_out, l), 0, batch->cu_seqlens_dev,
+      const bool last = l == hi - 1 && hidden_out;
+      void* h_next = last ? hidden_out : (void*)m->h;
+      rc = run_layer(m, l, h_cur, l > lo, h_next, !last, kv_k(kv_out, l), kv_v(kv_out, l), 0, batch->cu_seqlens_dev,
                      batch->cu_seqlens_host, nullptr, nullptr, 0, batch->n_seqs, T, s);
       if (rc) return rc;
       h_cur = h_next;
@@ -474,8 +481,9 @@ int dsk_suffix_prefill(dsk_model_t* model, const void* suffix_hidden_in, const d
       HIP_TRY(hipStreamWaitEvent(s, m->ev_kv[l], 0));
       m->pending[l] = 0;
     }
-    void* h_next = (l == c.n_layers - 1) ? hidden_out : m->h;
-    rc = run_layer(m, l, h_cur, h_next, kv_k(kv, l), kv_v(kv, l), suffix_row0, suffix->cu_seqlens_dev,
+    const bool last = l == c.n_layers - 1;
+    void* h_next = last ? hidden_out : (void*)m->h;
+    rc = run_layer(m, l, h_cur, l > 0, h_next, !last, kv_k(kv, l), kv_v(kv, l), suffix_row0, suffix->cu_seqlens_dev,
                    suffix->cu_seqlens_host, prefix->cu_seqlens_dev, prefix->cu_seqlens_host, prefix->n_tokens,
                    suffix->n_seqs, S, s);
     if (rc) return rc;

@@ -43,7 +43,8 @@ struct dsk_model {
   void* attn;       // [maxT, Hq*dh]
   void* gu;         // [maxT, 2F]
   void* act;        // [maxT, F]
-  void* h;          // [maxT, d]      residual stream
+  float* h;         // [maxT, d]      residual stream between the layers of one call, kept in fp32
+  void* e_stage;    // [maxT, d]      landing buffer for an E cache that arrives from pinned host memory
   float2* rope_cs;  // [maxT, dh/2]   cos, sin
   double* theta;    // [dh/2]         rope_base^(-2i/dh)
   void* vt;         // [Hkv*dh, ldvt] transposed V of the layer in flight (bf16 MFMA attention)
@@ -63,10 +64,11 @@ struct dsk_model {
 };
 
 // epilogues of the GEMM family
-enum { EPI_STORE = 0, EPI_RESIDUAL = 1 };
+// bit 0: add R; bit 1: R is fp32 (else the model dtype); bit 2: C is fp32 (else the model dtype)
+enum { EPI_STORE = 0, EPI_RESIDUAL = 1, EPI_R_F32 = 2, EPI_C_F32 = 4 };
 
 // ---- launchers (each validates nothing: the C-ABI layer has checked shapes) ----
-// C[M,N] = A[M,K] * W[N,K]^T (+ R[M,N] when epi == EPI_RESIDUAL); row strides in elements.
+// C[M,N] = A[M,K] * W[N,K]^T (+ R[M,N] when epi has EPI_RESIDUAL); row strides in elements.
 hipError_t launch_gemm_generic(int dtype, const void* A, int64_t lda, const void* W, int64_t ldw, void* C, int64_t ldc,
                                const void* R, int64_t ldr, int M, int N, int K, int epi, hipStream_t s);
 // bf16 MFMA GEMM; returns hipErrorNotSupported when the shape is outside what it handles.
@@ -76,7 +78,8 @@ hipError_t launch_gemm_mfma_bf16(const void* A, int64_t lda, const void* W, int6
                                  hipStream_t s);
 int64_t gemm_mfma_workspace_bytes(int max_n);
 
-hipError_t launch_rmsnorm(int dtype, const void* x, const void* g, void* y, int T, int d, float eps, hipStream_t s);
+// x is fp32 when x_f32 is set, else the model dtype; g and y are the model dtype
+hipError_t launch_rmsnorm(int dtype, const void* x, int x_f32, const void* g, void* y, int T, int d, float eps, hipStream_t s);
 hipError_t launch_rope_table(const int32_t* pos, const double* theta, float2* cs, int T, int half, hipStream_t s);
 // rotates q (in place) and k of qkv [T, n_qkv]; writes rotated k and v to the cache rows row0..row0+T-1
 hipError_t launch_rope_kv_write(int dtype, void* qkv, const float2* cs, void* k_rows, void* v_rows, int T, int Hq,

@@ -37,11 +37,31 @@ constexpr int GROUP_M = 4;    // M-tiles per scheduling group
 
 __device__ __forceinline__ int slot(int row, int chunk) { return (row * CH + (chunk ^ ((row >> 1) & (CH - 1)))) * 8; }
 
+// C[m][n..n+3] = v (+ R[m][n..n+3]); R and C are bf16 or fp32 as the epilogue flags say.
+__device__ __forceinline__ void store_quad(void* C, int64_t ldc, const void* R, int64_t ldr, int m, int n, f32x4 v, int epi) {
+  if (epi & EPI_RESIDUAL) {
+    if (epi & EPI_R_F32) {
+      f32x4 r = *(const f32x4*)((const float*)R + (int64_t)m * ldr + n);
+      v += r;
+    } else {
+      bf16x4 r = *(const bf16x4*)((const bf16_t*)R + (int64_t)m * ldr + n);
+      v[0] += (float)r[0]; v[1] += (float)r[1]; v[2] += (float)r[2]; v[3] += (float)r[3];
+    }
+  }
+  if (epi & EPI_C_F32) {
+    *(f32x4*)((float*)C + (int64_t)m * ldc + n) = v;
+  } else {
+    bf16x4 o;
+    o[0] = (bf16_t)v[0]; o[1] = (bf16_t)v[1]; o[2] = (bf16_t)v[2]; o[3] = (bf16_t)v[3];
+    *(bf16x4*)((bf16_t*)C + (int64_t)m * ldc + n) = o;
+  }
+}
+
 // PARTIAL: write the fp32 accumulators of this K split to P[split][M][N] instead of the bf16 result.
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool PARTIAL>
 __global__ void __launch_bounds__(WAVES_M* WAVES_N * 64)
     gemm_bf16_kernel(const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ W, int64_t ldw,
-                     bf16_t* __restrict__ C, int64_t ldc, const bf16_t* __restrict__ R, int64_t ldr,
+                     void* __restrict__ C, int64_t ldc, const void* __restrict__ R, int64_t ldr,
                      float* __restrict__ P, int M, int N, int K, int epi, int tiles_m, int tiles_n, int kt_per_split) {
   constexpr int NW = WAVES_M * WAVES_N;
   constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;  // wave tile
@@ -165,13 +185,8 @@ __global__ void __launch_bounds__(WAVES_M* WAVES_N * 64)
           f32x4 o = {v0, v1, v2, v3};
           *(f32x4*)(P + ((int64_t)blockIdx.y * M + m) * N + n) = o;
         } else {
-          if (epi == EPI_RESIDUAL) {
-            bf16x4 r = *(const bf16x4*)(R + (int64_t)m * ldr + n);
-            v0 += (float)r[0]; v1 += (float)r[1]; v2 += (float)r[2]; v3 += (float)r[3];
-          }
-          bf16x4 o;
-          o[0] = (bf16_t)v0; o[1] = (bf16_t)v1; o[2] = (bf16_t)v2; o[3] = (bf16_t)v3;
-          *(bf16x4*)(C + (int64_t)m * ldc + n) = o;
+          f32x4 v = {v0, v1, v2, v3};
+          store_quad(C, ldc, R, ldr, m, n, v, epi);
         }
       }
     }
@@ -179,8 +194,8 @@ __global__ void __launch_bounds__(WAVES_M* WAVES_N * 64)
 }
 
 // C[m][n] = bf16( sum_s P[s][m][n] (+ R[m][n]) ), the partials added in split order.
-__global__ void __launch_bounds__(256) splitk_reduce_kernel(const float* __restrict__ P, bf16_t* __restrict__ C, int64_t ldc,
-                                                            const bf16_t* __restrict__ R, int64_t ldr, int M, int N,
+__global__ void __launch_bounds__(256) splitk_reduce_kernel(const float* __restrict__ P, void* __restrict__ C, int64_t ldc,
+                                                            const void* __restrict__ R, int64_t ldr, int M, int N,
                                                             int splits, int epi) {
   const int64_t quads = (int64_t)M * (N / 4);
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -191,13 +206,7 @@ __global__ void __launch_bounds__(256) splitk_reduce_kernel(const float* __restr
     f32x4 v = *(const f32x4*)(P + ((int64_t)k * M + m) * N + n);
     s[0] += v[0]; s[1] += v[1]; s[2] += v[2]; s[3] += v[3];
   }
-  if (epi == EPI_RESIDUAL) {
-    bf16x4 r = *(const bf16x4*)(R + (int64_t)m * ldr + n);
-    s[0] += (float)r[0]; s[1] += (float)r[1]; s[2] += (float)r[2]; s[3] += (float)r[3];
-  }
-  bf16x4 o;
-  o[0] = (bf16_t)s[0]; o[1] = (bf16_t)s[1]; o[2] = (bf16_t)s[2]; o[3] = (bf16_t)s[3];
-  *(bf16x4*)(C + (int64_t)m * ldc + n) = o;
+  store_quad(C, ldc, R, ldr, m, n, s, epi);
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool PARTIAL>
@@ -213,8 +222,7 @@ hipError_t launch(const void* A, int64_t lda, const void* W, int64_t ldw, void* 
   }
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n, splits), dim3(WAVES_M * WAVES_N * 64), lds, s, (const bf16_t*)A, lda,
-                     (const bf16_t*)W, ldw, (bf16_t*)C, ldc, (const bf16_t*)R, ldr, P, M, N, K, epi, tiles_m, tiles_n,
-                     kt_per_split);
+                     (const bf16_t*)W, ldw, C, ldc, R, ldr, P, M, N, K, epi, tiles_m, tiles_n, kt_per_split);
   return hipGetLastError();
 }
 
@@ -230,7 +238,7 @@ hipError_t launch_gemm_mfma_bf16(const void* A, int64_t lda, const void* W, int6
                                  const void* R, int64_t ldr, int M, int N, int K, int epi, void* ws, int64_t ws_bytes,
                                  hipStream_t s) {
   if (M <= 0 || N <= 0) return hipSuccess;
-  if (K < BK || K % BK || N % 4 || (lda & 7) || (ldw & 7) || (ldc & 3) || (epi == EPI_RESIDUAL && (ldr & 3)))
+  if (K < BK || K % BK || N % 4 || (lda & 7) || (ldw & 7) || (ldc & 3) || ((epi & EPI_RESIDUAL) && (ldr & 3)))
     return hipErrorNotSupported;
   const int KT = K / BK;
   int variant = g_variant;
@@ -251,7 +259,7 @@ hipError_t launch_gemm_mfma_bf16(const void* A, int64_t lda, const void* W, int6
         if (e != hipSuccess) return e;
         const int64_t quads = (int64_t)M * (N / 4);
         hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s, (const float*)ws,
-                           (bf16_t*)C, ldc, (const bf16_t*)R, ldr, M, N, splits, epi);
+                           C, ldc, R, ldr, M, N, splits, epi);
         return hipGetLastError();
       }
       return launch<64, 64, 1, 2, false>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);

@@ -10,8 +10,8 @@ constexpr int TM = 64, TN = 64, TK = 16;
 // C[M,N] = A[M,K] * W[N,K]^T (+R).  256 threads, each a 4x4 micro-tile; tiles are zero-padded at the edges.
 template <typename T>
 __global__ void __launch_bounds__(256) gemm_generic_kernel(const T* __restrict__ A, int64_t lda, const T* __restrict__ W,
-                                                           int64_t ldw, T* __restrict__ C, int64_t ldc,
-                                                           const T* __restrict__ R, int64_t ldr, int M, int N, int K,
+                                                           int64_t ldw, void* __restrict__ Cv, int64_t ldc,
+                                                           const void* __restrict__ Rv, int64_t ldr, int M, int N, int K,
                                                            int epi) {
   __shared__ float sa[TK][TM + 4];
   __shared__ float sw[TK][TN + 4];
@@ -51,8 +51,10 @@ __global__ void __launch_bounds__(256) gemm_generic_kernel(const T* __restrict__
       int n = n0 + tx * 4 + j;
       if (n >= N) continue;
       float v = acc[i][j];
-      if (epi == EPI_RESIDUAL) v += to_f32(R[(int64_t)m * ldr + n]);
-      C[(int64_t)m * ldc + n] = from_f32<T>(v);
+      if (epi & EPI_RESIDUAL)
+        v += (epi & EPI_R_F32) ? ((const float*)Rv)[(int64_t)m * ldr + n] : to_f32(((const T*)Rv)[(int64_t)m * ldr + n]);
+      if (epi & EPI_C_F32) ((float*)Cv)[(int64_t)m * ldc + n] = v;
+      else ((T*)Cv)[(int64_t)m * ldc + n] = from_f32<T>(v);
     }
   }
 }
@@ -132,11 +134,11 @@ hipError_t launch_gemm_generic(int dtype, const void* A, int64_t lda, const void
   if (M <= 0 || N <= 0) return hipSuccess;
   dim3 grid((N + TN - 1) / TN, (M + TM - 1) / TM);
   if (dtype == DSK_F32)
-    hipLaunchKernelGGL(gemm_generic_kernel<float>, grid, dim3(256), 0, s, (const float*)A, lda, (const float*)W, ldw,
-                       (float*)C, ldc, (const float*)R, ldr, M, N, K, epi);
+    hipLaunchKernelGGL(gemm_generic_kernel<float>, grid, dim3(256), 0, s, (const float*)A, lda, (const float*)W, ldw, C,
+                       ldc, R, ldr, M, N, K, epi);
   else
     hipLaunchKernelGGL(gemm_generic_kernel<bf16_t>, grid, dim3(256), 0, s, (const bf16_t*)A, lda, (const bf16_t*)W, ldw,
-                       (bf16_t*)C, ldc, (const bf16_t*)R, ldr, M, N, K, epi);
+                       C, ldc, R, ldr, M, N, K, epi);
   return hipGetLastError();
 }
 

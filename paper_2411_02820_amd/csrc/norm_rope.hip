@@ -11,11 +11,11 @@ __device__ __forceinline__ float wave_sum(float v) {
 }
 
 // y = x * rsqrt(mean(x^2) + eps) * g, one 256-thread block per token row.
-template <typename T>
-__global__ void __launch_bounds__(256) rmsnorm_kernel(const T* __restrict__ x, const T* __restrict__ g, T* __restrict__ y,
+template <typename TX, typename T>
+__global__ void __launch_bounds__(256) rmsnorm_kernel(const TX* __restrict__ x, const T* __restrict__ g, T* __restrict__ y,
                                                       int d, float eps) {
   __shared__ float part[4];
-  const T* xr = x + (int64_t)blockIdx.x * d;
+  const TX* xr = x + (int64_t)blockIdx.x * d;
   T* yr = y + (int64_t)blockIdx.x * d;
   float ss = 0.f;
   for (int i = threadIdx.x; i < d; i += 256) {
@@ -90,12 +90,14 @@ __global__ void swiglu_kernel(const T* __restrict__ gu, T* __restrict__ act, int
 
 }  // namespace
 
-hipError_t launch_rmsnorm(int dtype, const void* x, const void* g, void* y, int T, int d, float eps, hipStream_t s) {
+hipError_t launch_rmsnorm(int dtype, const void* x, int x_f32, const void* g, void* y, int T, int d, float eps, hipStream_t s) {
   if (T <= 0) return hipSuccess;
   if (dtype == DSK_F32)
-    hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(T), dim3(256), 0, s, (const float*)x, (const float*)g, (float*)y, d, eps);
+    hipLaunchKernelGGL((rmsnorm_kernel<float, float>), dim3(T), dim3(256), 0, s, (const float*)x, (const float*)g, (float*)y, d, eps);
+  else if (x_f32)
+    hipLaunchKernelGGL((rmsnorm_kernel<float, bf16_t>), dim3(T), dim3(256), 0, s, (const float*)x, (const bf16_t*)g, (bf16_t*)y, d, eps);
   else
-    hipLaunchKernelGGL(rmsnorm_kernel<bf16_t>, dim3(T), dim3(256), 0, s, (const bf16_t*)x, (const bf16_t*)g, (bf16_t*)y, d, eps);
+    hipLaunchKernelGGL((rmsnorm_kernel<bf16_t, bf16_t>), dim3(T), dim3(256), 0, s, (const bf16_t*)x, (const bf16_t*)g, (bf16_t*)y, d, eps);
   return hipGetLastError();
 }
 

@@ -103,9 +103,8 @@ def _n_workers() -> int:
     return max(1, min(16, os.cpu_count() or 1))
 
 
-def normal_f32(n: int, seed: int, stream: int, std: float, offset: float = 0.0,
-               idx0: int = 0, chunk: int = 1 << 20) -> np.ndarray:
-    """n fp32 values offset + std*z of the ih8 generator, elements idx0.."""
+def _generate(n: int, seed: int, stream: int, std: float, offset: float, idx0: int, bf16: bool,
+              chunk: int = 1 << 20) -> np.ndarray:
     out = np.empty(n, dtype=np.float32)
     scale = scale_for_std(std)
     off = np.float32(offset)
@@ -115,6 +114,8 @@ def normal_f32(n: int, seed: int, stream: int, std: float, offset: float = 0.0,
         v = lane_sums(seed, stream, idx0 + s, m).astype(np.float32) * scale
         if offset != 0.0:
             v = v + off
+        if bf16:
+            v = bf16_bits_to_f32(f32_to_bf16_bits(v))
         out[s:s + m] = v
 
     starts = range(0, n, chunk)
@@ -127,15 +128,18 @@ def normal_f32(n: int, seed: int, stream: int, std: float, offset: float = 0.0,
     return out
 
 
+def normal_f32(n: int, seed: int, stream: int, std: float, offset: float = 0.0,
+               idx0: int = 0, chunk: int = 1 << 20) -> np.ndarray:
+    """n fp32 values offset + std*z of the ih8 generator, elements idx0.."""
+    return _generate(n, seed, stream, std, offset, idx0, False, chunk)
+
+
 def normal(n: int, seed: int, stream: int, std: float, offset: float = 0.0,
            dtype: str = "f32", idx0: int = 0) -> np.ndarray:
     """fp32 array of generated values; for dtype 'bf16' each value is bf16-representable."""
-    v = normal_f32(n, seed, stream, std, offset, idx0)
-    if dtype == "bf16":
-        v = bf16_bits_to_f32(f32_to_bf16_bits(v))
-    elif dtype != "f32":
+    if dtype not in ("f32", "bf16"):
         raise ValueError(dtype)
-    return v
+    return _generate(n, seed, stream, std, offset, idx0, dtype == "bf16")
 
 
 @dataclass(frozen=True)

@@ -1,0 +1,250 @@
+"""Parity at the full sizes of the five workloads, in the launch configuration bench.py times.
+
+The oracle cannot run 15-240 TFLOP, so each case compares what it can compute exactly:
+  * truncated prefix: by causality the first t rows of every tensor depend only on the first t tokens,
+    so the device's rows [0,t) of a full-size run are compared with an oracle run on t tokens;
+  * one layer at full length: K and V of all rows (they depend on the token's own hidden state only) and
+    the layer output for sampled rows, the last row of the sequence included;
+  * bit-exact properties at any size: the splice, untouched rows, composition of two calls.
+Inputs come from the seeded generator (host side for the oracle, device side for the 14-137 GB weight
+sets; the two generators are checked bit for bit in test_gpu_parity.py)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dsk_oracle as O
+from paper_2411_02820_amd import synth
+from tests.helpers import oracle_config
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-2
+
+
+@pytest.fixture(scope="module")
+def G():
+    from tests import gpu_util
+    return gpu_util
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2411_02820_amd import binding
+    return binding
+
+
+def host_weights(shape, seed, layers):
+    cache = {}
+
+    def get(l):
+        assert l in layers, f"layer {l} was not requested"
+        if l not in cache:
+            cache[l] = {k: v.astype(np.float64) for k, v in synth.layer_weights(shape, seed, l).items()}
+        return cache[l]
+    return get
+
+
+def device_normal(B, shape_tuple, seed, stream, dtype=torch.bfloat16, pinned=False):
+    t = torch.empty(shape_tuple, dtype=dtype, device="cuda")
+    B.dsk_fill_normal(t, t.numel(), seed, stream, 1.0, 0.0, 0, B.DSK_BF16)
+    if pinned:
+        h = torch.empty(shape_tuple, dtype=dtype, pin_memory=True)
+        h.copy_(t)
+        torch.cuda.synchronize()
+        return h
+    return t
+
+
+def device_kv_cache(B, shape, n_rows, n_fill_rows, pinned=False):
+    """[L,2,n_rows,Hkv,dh]; rows [0,n_fill_rows) of slab (l,j) are stream l*2+j of seed SEED_KV, like synth.kv_cache."""
+    kv = torch.full((shape.n_layers, 2, n_rows, shape.n_kv_heads, shape.head_dim), float("nan"), dtype=torch.bfloat16,
+                    device="cuda")
+    for l in range(shape.n_layers):
+        for j in range(2):
+            B.dsk_fill_normal(kv[l, j], n_fill_rows * shape.kv_width, synth.SEED_KV, l * 2 + j, 1.0, 0.0, 0, B.DSK_BF16)
+    torch.cuda.synchronize()
+    if pinned:
+        h = torch.empty(kv.shape, dtype=kv.dtype, pin_memory=True)
+        h.copy_(kv)
+        return h
+    return kv
+
+
+def host_kv_rows(shape, layer, n_rows):
+    return tuple(synth.normal(n_rows * shape.kv_width, synth.SEED_KV, layer * 2 + j, 1.0, 0.0, "bf16")
+                 .reshape(n_rows, shape.n_kv_heads, shape.head_dim).astype(np.float64) for j in range(2))
+
+
+def check_truncated(G, shape, kv_out, h_out, hidden_in_host, lo, hi_checked, lens, t_trunc, seed=synth.SEED_RECEIVER):
+    """Oracle on the first t_trunc tokens of every sequence, layers [lo, hi_checked)."""
+    cfg = oracle_config(shape)
+    cu = synth.cu_seqlens(lens)
+    tl = [min(t_trunc, n) for n in lens]
+    cut = synth.cu_seqlens(tl)
+    rows = np.concatenate([np.arange(cu[b], cu[b] + tl[b]) for b in range(len(lens))])
+    w = host_weights(shape, seed, range(lo, hi_checked))
+    dummy = [(None, None)] * shape.n_layers
+    kv_ref, h_ref = O.partial_prefill(cfg, w, hidden_in_host[rows].astype(np.float64), lo, hi_checked, dummy,
+                                      synth.packed_positions(tl), cut)
+    rows_t = torch.from_numpy(rows).cuda()
+    errs = {}
+    for l in range(lo, hi_checked):
+        errs[f"K{l}"] = O.max_rel_err(G.to_np(kv_out[l, 0].index_select(0, rows_t)), kv_ref[l][0])
+        errs[f"V{l}"] = O.max_rel_err(G.to_np(kv_out[l, 1].index_select(0, rows_t)), kv_ref[l][1])
+    if h_out is not None:
+        errs["hidden"] = O.max_rel_err(G.to_np(h_out.index_select(0, rows_t)), h_ref)
+    print("max-rel-err:", {k: f"{v:.2e}" for k, v in errs.items()})
+    assert max(errs.values()) <= TOL, errs
+
+
+def test_config2_8b_prefix4096_layers_8_16(G, B):
+    shape, T, lo, hi, S = synth.LLAMA_8B, 4096, 8, 16, 64
+    hidden_host = synth.hidden_states(shape, T)
+    with G.GpuModel(shape, T, T + S) as m:
+        m.init_random(synth.SEED_RECEIVER)
+        kv_r = device_kv_cache(B, shape, T, T)
+        kv_out, h_out = m.partial(G.to_dev(hidden_host, shape), lo, hi, kv_r, [T], n_rows=T + S)
+        xs = device_normal(B, (S, shape.hidden), synth.SEED_SUFFIX, 0)
+        hs = m.suffix(xs, kv_out, [T], [S])
+        torch.cuda.synchronize()
+        # splice and untouched rows: bit-exact at full size (suffix rows were written by the suffix pass)
+        for l in list(range(0, lo)) + list(range(hi, shape.n_layers)):
+            assert torch.equal(kv_out[l, :, :T], kv_r[l]), f"splice of layer {l}"
+        assert torch.isfinite(hs.float()).all() and torch.isfinite(kv_out.float()).all()
+        # the whole recomputed chain on the first 256 tokens
+        check_truncated(G, shape, kv_out, h_out, hidden_host, lo, hi, [T], 256)
+        # composition at full size: [8,12) then [12,16) through hidden_out reproduces [8,16) up to the one bf16
+        # rounding of hidden_out at the seam (bit for bit before the seam); a repeated call reproduces every bit
+        kv_1, h_1 = m.partial(G.to_dev(hidden_host, shape), lo, 12, kv_r, [T], n_rows=T + S)
+        kv_2, h_2 = m.partial(h_1, 12, hi, kv_1, [T], n_rows=T + S)
+        kv_3, h_3 = m.partial(G.to_dev(hidden_host, shape), lo, hi, kv_r, [T], n_rows=T + S)
+        torch.cuda.synchronize()
+        assert torch.equal(h_3, h_out) and torch.equal(kv_3[:, :, :T], kv_out[:, :, :T])
+        assert torch.equal(kv_2[lo:12, :, :T], kv_out[lo:12, :, :T])
+        assert O.max_rel_err(G.to_np(h_2), G.to_np(h_out)) <= 1e-2
+        assert O.max_rel_err(G.to_np(kv_2[12:hi, :, :T]), G.to_np(kv_out[12:hi, :, :T])) <= 1e-2
+
+
+def test_8b_one_layer_full_length_sampled_rows(G, B):
+    # T = 8192 (the headline point): K, V of every row and the layer output of sampled late rows
+    shape, T, l = synth.LLAMA_8B, 8192, 8
+    cfg = oracle_config(shape)
+    hidden_host = synth.hidden_states(shape, T)
+    with G.GpuModel(shape, T) as m:
+        m.init_random(synth.SEED_RECEIVER)
+        kv_r = device_kv_cache(B, shape, T, 0)
+        kv_out, h_out = m.partial(G.to_dev(hidden_host, shape), l, l + 1, kv_r, [T], kv_out=kv_r)
+        torch.cuda.synchronize()
+        w = host_weights(shape, synth.SEED_RECEIVER, [l])(l)
+        rows = [0, 63, 64, 1000, 4095, 4096, 6001, 8190, 8191]
+        h_ref, K, V = O.prefix_layer(cfg, w, hidden_host.astype(np.float64), np.arange(T), np.array([0, T]), rows=rows)
+        errs = {"K": O.max_rel_err(G.to_np(kv_out[l, 0]), K), "V": O.max_rel_err(G.to_np(kv_out[l, 1]), V),
+                "hidden_rows": O.max_rel_err(G.to_np(h_out)[rows], h_ref)}
+        print("max-rel-err:", {k: f"{v:.2e}" for k, v in errs.items()})
+        assert max(errs.values()) <= TOL, errs
+
+
+def test_config3_8b_ragged_batch(G, B):
+    # 8 prefixes with seeded lengths in [1024, 8192], 4 layers from a seeded start layer, packed
+    shape = synth.LLAMA_8B
+    lens = [int(x) for x in synth.ragged_lengths(8, 1024, 8192)]
+    lo = int(synth.uniform_ints(1, 0, 28, synth.SEED_LENGTHS, 1)[0])
+    hi = lo + 4
+    T = sum(lens)
+    hidden_host = synth.hidden_states(shape, T)
+    with G.GpuModel(shape, T) as m:
+        m.init_random(synth.SEED_RECEIVER)
+        kv_r = device_kv_cache(B, shape, T, T)
+        kv_out, h_out = m.partial(G.to_dev(hidden_host, shape), lo, hi, kv_r, lens)
+        torch.cuda.synchronize()
+        for l in (0, lo - 1, hi, shape.n_layers - 1):
+            if 0 <= l < shape.n_layers and not (lo <= l < hi):
+                assert torch.equal(kv_out[l], kv_r[l]), f"splice of layer {l}"
+        # every sequence's first 48 tokens, with its own positions, against the oracle's ragged batch
+        check_truncated(G, shape, kv_out, h_out, hidden_host, lo, hi, lens, 48)
+        # the last row of the shortest sequence through one layer: full-length attention inside a packed batch
+        b = int(np.argmin(lens))
+        cu = synth.cu_seqlens(lens)
+        s, e = int(cu[b]), int(cu[b + 1])
+        cfg = oracle_config(shape)
+        w = host_weights(shape, synth.SEED_RECEIVER, [lo])(lo)
+        n = e - s
+        h_ref, K, V = O.prefix_layer(cfg, w, hidden_host[s:e].astype(np.float64), np.arange(n), np.array([0, n]),
+                                     rows=[n - 1])
+        assert O.max_rel_err(G.to_np(kv_out[lo, 0, s:e]), K) <= TOL
+        kv1, h1 = m.partial(G.to_dev(hidden_host, shape), lo, lo + 1, kv_r, lens)
+        torch.cuda.synchronize()
+        assert O.max_rel_err(G.to_np(h1[e - 1:e]), h_ref) <= TOL
+
+
+def test_8b_shape_suffix_ragged_against_oracle(G, B):
+    # the 8B layer shape with 3 layers: ragged prefixes, 128-token suffixes, whole suffix pass against the oracle
+    shape = synth.ModelShape(3, 4096, 32, 8, 128, 14336, 500000.0, 1e-5, "bf16")
+    cfg = oracle_config(shape)
+    lens, slens = [300, 1100], [128, 128]
+    T, S = sum(lens), sum(slens)
+    cu, cus = synth.cu_seqlens(lens), synth.cu_seqlens(slens)
+    hidden_host = synth.hidden_states(shape, T)
+    xs_host = synth.hidden_states(shape, S, seed=synth.SEED_SUFFIX)
+    with G.GpuModel(shape, T, T + S) as m:
+        m.init_random(synth.SEED_RECEIVER)
+        kv_r = device_kv_cache(B, shape, T, T)
+        kv_out, h_out = m.partial(G.to_dev(hidden_host, shape), 1, 2, kv_r, lens, n_rows=T + S)
+        hs = m.suffix(G.to_dev(xs_host, shape), kv_out, lens, slens)
+        torch.cuda.synchronize()
+        w = host_weights(shape, synth.SEED_RECEIVER, range(3))
+        kv_host = [host_kv_rows(shape, l, T) for l in range(3)]
+        kv_ref, h_ref = O.partial_prefill(cfg, w, hidden_host.astype(np.float64), 1, 2, kv_host,
+                                          synth.packed_positions(lens), cu)
+        kv_s, hs_ref = O.suffix_prefill(cfg, w, xs_host.astype(np.float64), kv_ref,
+                                        synth.packed_positions(slens, start=lens), cu, cus)
+        errs = {"hidden": O.max_rel_err(G.to_np(h_out), h_ref), "suffix_hidden": O.max_rel_err(G.to_np(hs), hs_ref)}
+        for l in range(3):
+            errs[f"sK{l}"] = O.max_rel_err(G.to_np(kv_out[l, 0, T:]), kv_s[l][0])
+            errs[f"sV{l}"] = O.max_rel_err(G.to_np(kv_out[l, 1, T:]), kv_s[l][1])
+        print("max-rel-err:", {k: f"{v:.2e}" for k, v in errs.items()})
+        assert max(errs.values()) <= TOL, errs
+        assert B.dsk_get_stat("attn_generic_launches") == 0 and B.dsk_get_stat("gemm_generic_launches") == 0
+
+
+def test_config4_8b_prefix16384_kv_in_pinned_host_memory(G, B):
+    # reused KV (2 GiB, bf16) and the E cache live in pinned host memory; loads are pipelined under layers [4,12)
+    shape, T, lo, hi, S = synth.LLAMA_8B, 16384, 4, 12, 64
+    hidden_host = synth.hidden_states(shape, T)
+    with G.GpuModel(shape, T, T + S) as m:
+        m.init_random(synth.SEED_RECEIVER)
+        kv_r = device_kv_cache(B, shape, T, T, pinned=True)
+        assert kv_r.numel() * 2 == 2 << 30
+        e_host = G.to_dev(hidden_host, shape, pinned=True)
+        kv_out, h_out = m.partial(e_host, lo, hi, kv_r, [T], n_rows=T + S, flags=B.DSK_DEFER_JOIN)
+        xs = device_normal(B, (S, shape.hidden), synth.SEED_SUFFIX, 0)
+        hs = m.suffix(xs, kv_out, [T], [S])
+        torch.cuda.synchronize()
+        for l in list(range(0, lo)) + list(range(hi, shape.n_layers)):
+            assert torch.equal(kv_out[l, :, :T].cpu(), kv_r[l]), f"splice of layer {l}"
+        assert torch.isfinite(hs.float()).all()
+        # first two recomputed layers on a truncated prefix (the whole chain is covered at 4096 tokens)
+        check_truncated(G, shape, kv_out, None, hidden_host, lo, lo + 2, [T], 128)
+        # the three loading strategies give the same bits
+        B.dsk_set_load_mode(m.handle, B.DSK_LOAD_ALL_FIRST)
+        kv_2, h_2 = m.partial(e_host, lo, hi, kv_r, [T], n_rows=T + S)
+        torch.cuda.synchronize()
+        assert torch.equal(kv_2[:, :, :T], kv_out[:, :, :T]) and torch.equal(h_2, h_out)
+
+
+def test_config5_70b_prefix8192_layers_20_36(G, B):
+    shape, T, lo, hi, S = synth.LLAMA_70B, 8192, 20, 36, 64
+    hidden_host = synth.hidden_states(shape, T)
+    with G.GpuModel(shape, T, T + S) as m:
+        m.init_random(synth.SEED_RECEIVER)
+        assert B.dsk_model_weight_bytes(m.handle) > 136e9
+        kv_r = device_kv_cache(B, shape, T, T)
+        kv_out, h_out = m.partial(G.to_dev(hidden_host, shape), lo, hi, kv_r, [T], n_rows=T + S)
+        torch.cuda.synchronize()
+        for l in (0, lo - 1, hi, shape.n_layers - 1):
+            assert torch.equal(kv_out[l, :, :T], kv_r[l]), f"splice of layer {l}"
+        assert torch.isfinite(h_out.float()).all()
+        # device-generated weights of one layer against the host generator, bit for bit (largest tensors)
+        for kind in (synth.WQ, synth.WD):
+            assert np.array_equal(m.get_tensor(lo, kind).float().cpu().numpy(), synth.layer_tensor(shape, 0, lo, kind))
+        check_truncated(G, shape, kv_out, None, hidden_host, lo, lo + 2, [T], 64)

@@ -136,21 +136,30 @@ def test_pure_splice_and_aliasing(G):
         assert not np.array_equal(got[1], kv_r[1])
 
 
-def test_composition_is_bit_exact_on_device(G):
-    # partial(lo,m) then partial(m,hi) chained through hidden_out == partial(lo,hi): the path is deterministic
-    shape = SMALL_BF16
-    lens = [150, 43]
-    T = sum(lens)
-    hidden_in = G.to_dev(synth.hidden_states(shape, T), shape)
-    kv_r = G.to_dev(synth.kv_cache(shape, T), shape)
-    with G.GpuModel(shape, T) as m:
-        m.load_from_generator(0, scale=2.0)
-        kv_a, h_a = m.partial(hidden_in, 0, 3, kv_r, lens)
-        kv_1, h_1 = m.partial(hidden_in, 0, 1, kv_r, lens)
-        kv_2, h_2 = m.partial(h_1, 1, 3, kv_1, lens)
-        torch.cuda.synchronize()
-        assert torch.equal(h_a, h_2)
-        assert torch.equal(kv_a, kv_2)
+def test_composition_and_determinism_on_device(G):
+    # partial(lo,m) then partial(m,hi) chained through hidden_out == partial(lo,hi).  For the fp32 model the two
+    # are bit-identical.  The bf16 model keeps its residual stream in fp32 between the layers of one call, so the
+    # chained run differs by the one bf16 rounding of hidden_out at the seam: equal up to that, and the layers
+    # before the seam bit-identical.  Repeating a call reproduces every bit (no atomics, fixed reduction orders).
+    for shape, scale, tol in ((synth.TINY, 8.0, 0.0), (SMALL_BF16, 2.0, 1e-2)):
+        lens = [150, 43]
+        T = sum(lens)
+        hidden_in = G.to_dev(synth.hidden_states(shape, T), shape)
+        kv_r = G.to_dev(synth.kv_cache(shape, T), shape)
+        with G.GpuModel(shape, T) as m:
+            m.load_from_generator(0, scale=scale)
+            kv_a, h_a = m.partial(hidden_in, 0, 3, kv_r, lens)
+            kv_b, h_b = m.partial(hidden_in, 0, 3, kv_r, lens)
+            kv_1, h_1 = m.partial(hidden_in, 0, 1, kv_r, lens)
+            kv_2, h_2 = m.partial(h_1, 1, 3, kv_1, lens)
+            torch.cuda.synchronize()
+            assert torch.equal(h_a, h_b) and torch.equal(kv_a, kv_b)
+            assert torch.equal(kv_a[0], kv_2[0])
+            if tol == 0.0:
+                assert torch.equal(h_a, h_2) and torch.equal(kv_a, kv_2)
+            else:
+                assert O.max_rel_err(G.to_np(h_2), G.to_np(h_a)) <= tol
+                assert O.max_rel_err(G.to_np(kv_2), G.to_np(kv_a)) <= tol
 
 
 def test_load_strategies_give_identical_results(G):
