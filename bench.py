@@ -6,7 +6,7 @@ from the sender's E cache while the other layers' KV is spliced in on the side s
 dsk_suffix_prefill (the new tokens through all layers against the mixed cache).  Inputs are
 synthetic and resident in HBM before the timed region.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 8b-8k|8b-4k|70b-8k|tiny]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 8b-8k|8b-4k|8b-ragged|8b-16k-hostkv|70b-8k|tiny]
 """
 import argparse
 import json
@@ -21,19 +21,21 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
 
 WORKLOADS = {
-    # name: (shape name, prefix tokens, lo, hi, suffix tokens)
-    "8b-8k": ("LLAMA_8B", 8192, 8, 16, 64),    # the point the headline metric is quoted on
-    "8b-4k": ("LLAMA_8B", 4096, 8, 16, 64),    # config 2
-    "70b-8k": ("LLAMA_70B", 8192, 20, 36, 64),  # config 5
-    "tiny": ("TINY", 128, 1, 3, 16),           # config 1
+    # name: (shape name, prefix lengths (None: seeded ragged batch), lo, hi, suffix tokens per sequence, KV/E in pinned host memory)
+    "8b-8k": ("LLAMA_8B", [8192], 8, 16, 64, False),         # the point the headline metric is quoted on
+    "8b-4k": ("LLAMA_8B", [4096], 8, 16, 64, False),         # workload 2
+    "8b-ragged": ("LLAMA_8B", None, None, None, 128, False),  # workload 3: 8 prefixes U[1024,8192], 4 layers
+    "8b-16k-hostkv": ("LLAMA_8B", [16384], 4, 12, 64, True),  # workload 4: reused KV + E cache in pinned host memory
+    "70b-8k": ("LLAMA_70B", [8192], 20, 36, 64, False),      # workload 5
+    "tiny": ("TINY", [128], 1, 3, 16, False),                # workload 1
 }
 
 
-def recompute_flops(shape, T, n_layers):
-    """Algorithmic flops of recomputing n_layers over one T-token prefix (MAC = 2, attention causal)."""
+def recompute_flops(shape, lens, n_layers):
+    """Algorithmic flops of recomputing n_layers over the packed prefixes (MAC = 2, attention causal)."""
     d, hq, hkv, dh, f = shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.ffn
-    gemm = 2.0 * T * (d * (hq + 2 * hkv) * dh + hq * dh * d + 3 * d * f)
-    attn = 2.0 * hq * dh * T * (T + 1)
+    gemm = 2.0 * sum(lens) * (d * (hq + 2 * hkv) * dh + hq * dh * d + 3 * d * f)
+    attn = sum(2.0 * hq * dh * t * (t + 1) for t in lens)
     return n_layers * (gemm + attn)
 
 
@@ -54,9 +56,9 @@ def cpu_baseline(shape, lo, hi):
     import numpy as np
     from oracle import dsk_oracle as O
     from paper_2411_02820_amd import synth
-    n_tok = 128 if shape.hidden <= 4096 else 64
+    n_tok = 4096 if shape.hidden <= 4096 else 1536   # about 10-30 s of host work
     if shape.hidden <= 256:
-        n_tok = 128
+        n_tok = 8192
     cfg = O.Config(shape.n_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.ffn,
                    shape.rope_base, shape.rms_eps)
     w = {k: v.astype(np.float64) for k, v in synth.layer_weights(shape, synth.SEED_RECEIVER, lo).items()}
@@ -82,6 +84,8 @@ def main():
     ap.add_argument("--workload", default="8b-8k", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full-prefill", action="store_true")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy, the known-size kernel that scales FETCH_SIZE/WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no sharding or collectives); use --gpus 1")
@@ -90,27 +94,33 @@ def main():
     from paper_2411_02820_amd import binding as B
     from paper_2411_02820_amd import synth
 
-    shape_name, T, lo, hi, S = WORKLOADS[args.workload]
+    shape_name, lens, lo, hi, S1, host_kv = WORKLOADS[args.workload]
     shape = getattr(synth, shape_name)
     L = shape.n_layers
+    if lens is None:  # workload 3: seeded ragged batch and start layer
+        lens = [int(x) for x in synth.ragged_lengths(8, 1024, 8192)]
+        lo = int(synth.uniform_ints(1, 0, 28, synth.SEED_LENGTHS, 1)[0])
+        hi = lo + 4
+    slens = [S1] * len(lens)
+    T, S = sum(lens), sum(slens)
     tdt = torch.float32 if shape.dtype == "f32" else torch.bfloat16
     code = B.DSK_F32 if shape.dtype == "f32" else B.DSK_BF16
     dev = "cuda"
     cfg = B.config_from_shape(shape)
     rows = T + S
 
-    def new_cache():
-        return torch.empty((L, 2, rows, shape.n_kv_heads, shape.head_dim), dtype=tdt, device=dev)
+    def new_cache(n_rows=rows):
+        return torch.empty((L, 2, n_rows, shape.n_kv_heads, shape.head_dim), dtype=tdt, device=dev)
 
-    prefix = B.Batch([0, T], synth.packed_positions([T]))
-    suffix = B.Batch([0, S], synth.packed_positions([S], start=[T]))
+    prefix = B.Batch(synth.cu_seqlens(lens), synth.packed_positions(lens))
+    suffix = B.Batch(synth.cu_seqlens(slens), synth.packed_positions(slens, start=lens))
     hidden_in = torch.empty((T, shape.hidden), dtype=tdt, device=dev)
-    kv_sender = new_cache()
+    kv_sender = new_cache(T)
 
     # ---- sender (seed 1): its KV for all layers and its hidden state entering layer lo (Sec. 4.1) ----
     sender_fits = shape.hidden <= 4096
     if sender_fits:
-        sender = B.dsk_model_create(cfg, T, rows)
+        sender = B.dsk_model_create(cfg, T, T)
         B.dsk_model_init_random(sender, synth.SEED_SENDER, synth.WEIGHT_STD)
         x0 = torch.empty((T, shape.hidden), dtype=tdt, device=dev)
         B.dsk_fill_normal(x0, x0.numel(), synth.SEED_HIDDEN, 0, 1.0, 0.0, 0, code)
@@ -137,7 +147,19 @@ def main():
     xs = torch.empty((S, shape.hidden), dtype=tdt, device=dev)
     B.dsk_fill_normal(xs, xs.numel(), synth.SEED_SUFFIX, 0, 1.0, 0.0, 0, code)
     hs_out = torch.empty_like(xs)
-    kv_r, kv_o = B.kv_desc(kv_sender), B.kv_desc(kv_out)
+    kv_dev_desc = B.kv_desc(kv_sender)
+    hidden_dev = hidden_in
+    if host_kv:  # workload 4: the sender's KV and E cache wait in pinned host memory
+        kv_host = torch.empty(kv_sender.shape, dtype=tdt, pin_memory=True)
+        kv_host.copy_(kv_sender)
+        e_host = torch.empty(hidden_in.shape, dtype=tdt, pin_memory=True)
+        e_host.copy_(hidden_in)
+        torch.cuda.synchronize()
+        kv_r, hidden_in = B.kv_desc(kv_host), e_host
+        data += "; reused KV and E cache staged in pinned host memory (loads timed, PCIe-inclusive)"
+    else:
+        kv_r = kv_dev_desc
+    kv_o = B.kv_desc(kv_out)
     torch.cuda.synchronize()
 
     def partial(a=lo, b=hi):
@@ -149,6 +171,14 @@ def main():
     def step():
         partial()
         suffix_pass()
+
+    if args.pmc_calibration:
+        cal_src = torch.empty(1 << 28, dtype=torch.float32, device=dev)
+        cal_src.fill_(1.0)
+        cal_dst = torch.empty_like(cal_src)
+        cal_dst.copy_(cal_src)  # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del cal_src, cal_dst
 
     for _ in range(args.warmup):
         step()
@@ -184,7 +214,26 @@ def main():
         extra["full_prefill_ms"] = round(t_full, 3)
         extra["speedup_vs_full_prefill"] = round((t_full + t_suffix) / (t_partial + t_suffix), 3)
         extra["full_prefill_tokens_per_s"] = round(T / (t_full / 1e3), 1)
-    flops = recompute_flops(shape, T, hi - lo)
+    if host_kv:
+        # overlap of the per-layer loads with the recompute: device-resident inputs, sequential (load, then
+        # compute) and pipelined runs of the same call
+        def run_mode(mode, kv_desc, e):
+            B.dsk_set_load_mode(model, mode)
+            def f():
+                B.dsk_partial_prefill(model, e, lo, hi, kv_desc, kv_o, prefix.desc, None, 0)
+            f()
+            return time_region(torch, f, 3)
+        t_dev = run_mode(B.DSK_LOAD_PIPELINED, kv_dev_desc, hidden_dev)
+        t_seq = run_mode(B.DSK_LOAD_REUSED_FIRST, kv_r, hidden_in)
+        t_pipe = run_mode(B.DSK_LOAD_PIPELINED, kv_r, hidden_in)
+        load_ms = max(t_seq - t_dev, 1e-6)
+        reused_bytes = (L - (hi - lo)) * 2 * T * shape.kv_width * shape.elem_bytes + T * shape.hidden * shape.elem_bytes
+        extra["host_kv"] = {"partial_ms_device_resident": round(t_dev, 3), "partial_ms_load_then_compute": round(t_seq, 3),
+                            "partial_ms_pipelined": round(t_pipe, 3), "exposed_load_ms": round(t_pipe - t_dev, 3),
+                            "overlap_efficiency": round(1.0 - (t_pipe - t_dev) / load_ms, 4),
+                            "h2d_gb_per_s": round(reused_bytes / (load_ms * 1e-3) / 1e9, 1),
+                            "loaded_bytes": int(reused_bytes)}
+    flops = recompute_flops(shape, lens, hi - lo)
     extra.update({
         "partial_prefill_ms": round(t_partial, 3), "suffix_prefill_ms": round(t_suffix, 3),
         "ttft_ms": round(t_partial + t_suffix, 3),
@@ -201,8 +250,9 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if shape.dtype == "bf16" else "f32", "data": data,
-        "config": {"workload": f"{shape_name} shape, one {T}-token prefix, recompute layers [{lo},{hi}) of {L}, "
-                               f"suffix {S} tokens; step = dsk_partial_prefill + dsk_suffix_prefill",
+        "config": {"workload": f"{shape_name} shape, {len(lens)} prefix(es) of {lens if len(lens) > 1 else lens[0]} tokens, "
+                               f"recompute layers [{lo},{hi}) of {L}, suffix {S1} tokens per sequence; "
+                               f"step = dsk_partial_prefill + dsk_suffix_prefill",
                    "prefix_tokens": T, "lo": lo, "hi": hi, "suffix_tokens": S},
     }
     if shape.dtype == "bf16" and gemm_n > 0:
