@@ -1,6 +1,7 @@
 // C-ABI entry points and the host-side scheduler (streams, per-layer load events) of libdsk.
 #include <math.h>
 #include <stdlib.h>
+#include <stdio.h>
 #include <string.h>
 
 #include <new>
@@ -86,7 +87,8 @@ inline char* kv_v(const dsk_kv_t* kv, int l) { return kv_k(kv, l) + kv->v_offset
 
 int g_force_generic = 0;
 int g_time_gemm = 0;
-int g_linear_ld_pad = 0;  // experiment knob: dsk_linear reads x and w with row stride K + pad
+int g_linear_ld_pad = 0;
+void* g_dbg_trace = nullptr;  // experiment knob: dsk_linear reads x and w with row stride K + pad
 
 // launch counters and the event pairs recorded under "time_gemm"
 struct Stats {
@@ -181,8 +183,12 @@ int run_layer(dsk_model* m, int l, const void* h_in, int h_in_f32, void* h_out, 
   HIP_TRY(gemm(m, m->attn, nq, w.wo, nq, m->h, d, h_in, d, n, d, nq,
                EPI_RESIDUAL | EPI_C_F32 | ((h_in_f32 || all_f32) ? EPI_R_F32 : 0), s));
   HIP_TRY(launch_rmsnorm(c.dtype, m->h, 1, w.g2, m->xn, n, d, (float)c.rms_eps, s));
-  HIP_TRY(gemm(m, m->xn, d, w.wgu, d, m->gu, 2 * (int64_t)F, nullptr, 0, n, 2 * F, d, EPI_STORE, s));
-  HIP_TRY(launch_swiglu(c.dtype, m->gu, m->act, n, F, m->gu_block, s));
+  if (c.dtype == DSK_BF16 && !g_force_generic && m->gu_block == 32 && gemm_mfma_swiglu_supported(n, 2 * F, d)) {
+    HIP_TRY(gemm(m, m->xn, d, w.wgu, d, m->act, F, nullptr, 0, n, 2 * F, d, EPI_SWIGLU, s));  // SwiGLU in the epilogue
+  } else {
+    HIP_TRY(gemm(m, m->xn, d, w.wgu, d, m->gu, 2 * (int64_t)F, nullptr, 0, n, 2 * F, d, EPI_STORE, s));
+    HIP_TRY(launch_swiglu(c.dtype, m->gu, m->act, n, F, m->gu_block, s));
+  }
   HIP_TRY(gemm(m, m->act, F, w.wd, F, h_out, d, m->h, d, n, d, F,
                EPI_RESIDUAL | EPI_R_F32 | ((h_out_f32 || all_f32) ? EPI_C_F32 : 0), s));
   return DSK_OK;
@@ -514,7 +520,7 @@ int dsk_linear(int dtype, const void* x, const void* w, void* y, const void* r, 
   if (dtype != DSK_F32 && dtype != DSK_BF16) return DSK_EDTYPE;
   if (!aligned16(x) || !aligned16(w) || !aligned16(y) || !aligned16(r)) return DSK_EINVAL;
   const int epi = r ? EPI_RESIDUAL : EPI_STORE;
-  HIP_TRY(gemm_any(dtype, x, K + g_linear_ld_pad, w, K + g_linear_ld_pad, y, N, r, N, M, N, K, epi, nullptr, 0, (hipStream_t)stream));
+  HIP_TRY(gemm_any(dtype, x, K + g_linear_ld_pad, w, K + g_linear_ld_pad, y, N, r, N, M, N, K, epi, g_dbg_trace, 0, (hipStream_t)stream));
   return DSK_OK;
 }
 
@@ -559,6 +565,20 @@ int dsk_set_option(const char* name, int value) {
   else if (!strcmp(name, "force_generic")) g_force_generic = value;
   else if (!strcmp(name, "time_gemm")) g_time_gemm = value;
   else if (!strcmp(name, "linear_ld_pad")) g_linear_ld_pad = value;
+  else if (!strcmp(name, "dbg_trace_alloc")) { if (!g_dbg_trace) (void)hipMalloc(&g_dbg_trace, 8 * 64 * 3 * 8); }
+  else if (!strcmp(name, "dbg_trace_dump")) {
+    unsigned long long h[8 * 64 * 3];
+    (void)hipMemcpy(h, g_dbg_trace, sizeof(h), hipMemcpyDeviceToHost);
+    for (int t = 8; t < 8 + value; ++t) {
+      printf("it %2d:", t);
+      for (int w = 0; w < 8; ++w) {
+        unsigned long long* a = h + (w * 64 + t) * 3;
+        unsigned long long* pa = h + (w * 64 + t - 1) * 3;
+        printf(" | w%d comp %4llu vm %4llu bar %4llu", w, a[0] - pa[2], a[1] - a[0], a[2] - a[1]);
+      }
+      printf("\n");
+    }
+  }
   else if (!strcmp(name, "reset_stats")) {
     g_stats.gemm_mfma = g_stats.gemm_generic = g_stats.attn_mfma = g_stats.attn_generic = 0;
     g_stats.n_timed = 0;

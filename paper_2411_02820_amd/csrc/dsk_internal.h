@@ -65,7 +65,8 @@ struct dsk_model {
 
 // epilogues of the GEMM family
 // bit 0: add R; bit 1: R is fp32 (else the model dtype); bit 2: C is fp32 (else the model dtype)
-enum { EPI_STORE = 0, EPI_RESIDUAL = 1, EPI_R_F32 = 2, EPI_C_F32 = 4 };
+// bit 3 (bf16 MFMA kernel only): W is the interleaved gate/up matrix, C[M, N/2] = silu(gate) * up
+enum { EPI_STORE = 0, EPI_RESIDUAL = 1, EPI_R_F32 = 2, EPI_C_F32 = 4, EPI_SWIGLU = 8 };
 
 // ---- launchers (each validates nothing: the C-ABI layer has checked shapes) ----
 // C[M,N] = A[M,K] * W[N,K]^T (+ R[M,N] when epi has EPI_RESIDUAL); row strides in elements.
@@ -77,6 +78,7 @@ hipError_t launch_gemm_mfma_bf16(const void* A, int64_t lda, const void* W, int6
                                  const void* R, int64_t ldr, int M, int N, int K, int epi, void* ws, int64_t ws_bytes,
                                  hipStream_t s);
 int64_t gemm_mfma_workspace_bytes(int max_n);
+bool gemm_mfma_swiglu_supported(int M, int N, int K);
 
 // x is fp32 when x_f32 is set, else the model dtype; g and y are the model dtype
 hipError_t launch_rmsnorm(int dtype, const void* x, int x_f32, const void* g, void* y, int T, int d, float eps, hipStream_t s);

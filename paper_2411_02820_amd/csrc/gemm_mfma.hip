@@ -58,11 +58,14 @@ __device__ __forceinline__ void store_quad(void* C, int64_t ldc, const void* R, 
 }
 
 // PARTIAL: write the fp32 accumulators of this K split to P[split][M][N] instead of the bf16 result.
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool PARTIAL>
+// SWIGLU: W holds gate and up rows interleaved in blocks of 32 (packed rows 64b..64b+31 = gate rows 32b.., the
+// next 32 = the same up rows), so MFMA tiles j (even) and j+1 of a wave are gate and up of the same 32 FFN
+// indices at the same lane/register; the epilogue writes silu(gate)*up to C[M, N/2].
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool PARTIAL, bool SWIGLU = false>
 __global__ void __launch_bounds__(WAVES_M* WAVES_N * 64)
     gemm_bf16_kernel(const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ W, int64_t ldw,
                      void* __restrict__ C, int64_t ldc, const void* __restrict__ R, int64_t ldr,
-                     float* __restrict__ P, int M, int N, int K, int epi, int tiles_m, int tiles_n, int kt_per_split) {
+                     float* __restrict__ P, int M, int N, int K, int epi, int tiles_m, int tiles_n, int kt_per_split, int dbg) {
   constexpr int NW = WAVES_M * WAVES_N;
   constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;  // wave tile
   constexpr int TM = WTM / 32, TN = WTN / 32;            // 32x32 MFMA tiles per wave
@@ -111,11 +114,13 @@ __global__ void __launch_bounds__(WAVES_M* WAVES_N * 64)
   }
   typedef __attribute__((address_space(3))) void lds_void;
   typedef const __attribute__((address_space(1))) void glb_void;
-  auto issue_loads = [&](int stage, int k0) {
+  auto issue_loads = [&](int stage, int k0, int skip = 0) {
+    if (!(skip & 2))
 #pragma unroll
     for (int i = 0; i < A_INST; ++i)
       __builtin_amdgcn_global_load_lds((glb_void*)(a_src[i] + k0),
                                        (lds_void*)(sA + stage * BM * BK + RPI * (wave * A_INST + i) * BK), 16, 0, 0);
+    if (!(skip & 1))
 #pragma unroll
     for (int i = 0; i < W_INST; ++i)
       __builtin_amdgcn_global_load_lds((glb_void*)(w_src[i] + k0),
@@ -144,32 +149,86 @@ __global__ void __launch_bounds__(WAVES_M* WAVES_N * 64)
   const int kt_begin = PARTIAL ? (int)blockIdx.y * kt_per_split : 0;
   const int kt_end = PARTIAL ? min(KT_all, kt_begin + kt_per_split) : KT_all;
 
+  // Software pipeline over k-tiles with ONE barrier per tile, placed between the MFMAs of k-step NKS-2 and
+  // NKS-1: by then every LDS read of the current tile has been issued and waited for, so the barrier both
+  // publishes tile kt+1 (each wave has waited for its own loads) and frees the current stage for the loads of
+  // tile kt+2.  After the barrier a wave still owns the MFMAs of the last k-step (fragments already in
+  // registers) and issues the first fragment reads of tile kt+1 under them, so the restart after a barrier
+  // never waits on LDS.
+  constexpr int PER_TILE = A_INST + W_INST;
+  const int n_kt = kt_end - kt_begin;
   issue_loads(0, kt_begin * BK);
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  if (n_kt > 1) {
+    issue_loads(1, (kt_begin + 1) * BK);
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PER_TILE) : "memory");
+  } else {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  }
   __syncthreads();
-  for (int kt = kt_begin; kt < kt_end; ++kt) {
-    const int stage = (kt - kt_begin) & 1;
-    if (kt + 1 < kt_end) issue_loads(stage ^ 1, (kt + 1) * BK);
+  bf16x8 xf[2][TM], wf[2][TN];
+  load_frags(sA, sW, 0, xf[0], wf[0]);
+  for (int t = 0; t < n_kt; ++t) {
+    const int stage = t & 1;
     const bf16_t* a_s = sA + stage * BM * BK;
     const bf16_t* w_s = sW + stage * BN * BK;
-    bf16x8 xf[2][TM], wf[2][TN];
-    load_frags(a_s, w_s, 0, xf[0], wf[0]);
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) {
       const int cur = ks & 1;
-      if (ks + 1 < NKS) load_frags(a_s, w_s, ks + 1, xf[cur ^ 1], wf[cur ^ 1]);
+      if (ks + 1 < NKS) {
+        load_frags(a_s, w_s, ks + 1, xf[cur ^ 1], wf[cur ^ 1]);
+      } else {
+        // all reads of this tile are done; tile t+1 has landed (only its loads are outstanding)
+        unsigned long long t0 = 0, t1 = 0, t2 = 0;
+        if (dbg & 4) t0 = __builtin_readcyclecounter();
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+        if (dbg & 4) t1 = __builtin_readcyclecounter();
+        __syncthreads();
+        if (dbg & 4) {
+          t2 = __builtin_readcyclecounter();
+          if (blockIdx.x == 300 && lane == 0 && t < 64) {
+            unsigned long long* tr = (unsigned long long*)P + (wave * 64 + t) * 3;
+            tr[0] = t0; tr[1] = t1; tr[2] = t2;
+          }
+        }
+        if (t + 2 < n_kt) issue_loads(stage, (kt_begin + t + 2) * BK, dbg);
+        if (t + 1 < n_kt)
+          load_frags(sA + (stage ^ 1) * BM * BK, sW + (stage ^ 1) * BN * BK, 0, xf[cur ^ 1], wf[cur ^ 1]);
+      }
 #pragma unroll
       for (int j = 0; j < TN; ++j)
 #pragma unroll
         for (int i = 0; i < TM; ++i)
           acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[cur][j], xf[cur][i], acc[j][i], 0, 0, 0);
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // k-tile kt+1 has landed (this wave's part)
-    __syncthreads();
   }
 
   // ---- epilogue: accumulator register 4q+e of tile (j,i) is C[m][n + e],
   //      m = tile row base + lane%32, n = tile col base + 8q + 4*(lane/32) ----
+  if constexpr (SWIGLU) {
+    static_assert(TN % 2 == 0 && !PARTIAL, "gate/up tiles come in pairs");
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const int m = m0 + wm * WTM + i * 32 + frag_row;
+      if (m >= M) continue;
+#pragma unroll
+      for (int j = 0; j < TN; j += 2) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int f = (n0 + wn * WTN + j * 32) / 2 + 8 * q + 4 * frag_hi;
+          if (f >= N / 2) continue;
+          bf16x4 o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float g = acc[j][i][4 * q + e], u = acc[j + 1][i][4 * q + e];
+            const float sig = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * g));
+            o[e] = (bf16_t)(g * sig * u);
+          }
+          *(bf16x4*)((bf16_t*)C + (int64_t)m * ldc + f) = o;
+        }
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
     const int m = m0 + wm * WTM + i * 32 + frag_row;
@@ -209,10 +268,12 @@ __global__ void __launch_bounds__(256) splitk_reduce_kernel(const float* __restr
   store_quad(C, ldc, R, ldr, m, n, s, epi);
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool PARTIAL>
+int g_dbg = 0;
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool PARTIAL, bool SWIGLU = false>
 hipError_t launch(const void* A, int64_t lda, const void* W, int64_t ldw, void* C, int64_t ldc, const void* R, int64_t ldr,
                   float* P, int M, int N, int K, int epi, int splits, int kt_per_split, hipStream_t s) {
-  auto kern = gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, PARTIAL>;
+  auto kern = gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, PARTIAL, SWIGLU>;
   constexpr int lds = NSTAGE * (BM + BN) * BK * 2;
   static bool configured = false;
   if (!configured) {
@@ -222,7 +283,7 @@ hipError_t launch(const void* A, int64_t lda, const void* W, int64_t ldw, void* 
   }
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n, splits), dim3(WAVES_M * WAVES_N * 64), lds, s, (const bf16_t*)A, lda,
-                     (const bf16_t*)W, ldw, C, ldc, R, ldr, P, M, N, K, epi, tiles_m, tiles_n, kt_per_split);
+                     (const bf16_t*)W, ldw, C, ldc, R, ldr, P, M, N, K, epi, tiles_m, tiles_n, kt_per_split, g_dbg);
   return hipGetLastError();
 }
 
@@ -230,7 +291,10 @@ int g_variant = 0;
 
 }  // namespace
 
-void gemm_mfma_set_variant(int v) { g_variant = v; }
+void gemm_mfma_set_variant(int v) { g_variant = v % 10; g_dbg = v / 10; }
+
+// the fused gate/up epilogue needs whole 64-row gate/up blocks and is not offered on the split-K path
+bool gemm_mfma_swiglu_supported(int M, int N, int K) { return M > 64 && N % 64 == 0 && K >= BK && K % BK == 0; }
 
 int64_t gemm_mfma_workspace_bytes(int max_n) { return (int64_t)64 * 4 * ((int64_t)768 * 64 + max_n); }
 
@@ -242,6 +306,12 @@ hipError_t launch_gemm_mfma_bf16(const void* A, int64_t lda, const void* W, int6
     return hipErrorNotSupported;
   const int KT = K / BK;
   int variant = g_variant;
+  if (epi & EPI_SWIGLU) {
+    if (!gemm_mfma_swiglu_supported(M, N, K)) return hipErrorNotSupported;
+    if ((int64_t)((M + 255) / 256) * ((N + 255) / 256) >= 192 || variant == 1)
+      return launch<256, 256, 2, 4, false, true>(A, lda, W, ldw, C, ldc, R, ldr, (float*)ws, M, N, K, epi, 1, KT, s);
+    return launch<128, 128, 2, 2, false, true>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
+  }
   if (variant == 0) {
     if (M <= 64) variant = 3;
     else if ((int64_t)((M + 255) / 256) * ((N + 255) / 256) >= 192) variant = 1;
@@ -265,6 +335,8 @@ hipError_t launch_gemm_mfma_bf16(const void* A, int64_t lda, const void* W, int6
       return launch<64, 64, 1, 2, false>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
     }
     case 2: return launch<128, 128, 2, 2, false>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
-    default: return launch<256, 256, 2, 4, false>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
+    default:
+      if ((g_dbg & 4) && !ws) return hipErrorInvalidValue;  // the trace build writes timestamps through P
+      return launch<256, 256, 2, 4, false>(A, lda, W, ldw, C, ldc, R, ldr, (float*)ws, M, N, K, epi, 1, KT, s);
   }
 }

@@ -10,7 +10,7 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
-// y = x * rsqrt(mean(x^2) + eps) * g, one 256-thread block per token row.
+// y = x * rsqrt(mean(x^2) + eps) * g, one 256-thread block per token row (any d; scalar accesses).
 template <typename TX, typename T>
 __global__ void __launch_bounds__(256) rmsnorm_kernel(const TX* __restrict__ x, const T* __restrict__ g, T* __restrict__ y,
                                                       int d, float eps) {
@@ -28,6 +28,51 @@ __global__ void __launch_bounds__(256) rmsnorm_kernel(const TX* __restrict__ x, 
   float tot = part[0] + part[1] + part[2] + part[3];
   float r = 1.0f / sqrtf(tot / (float)d + eps);
   for (int i = threadIdx.x; i < d; i += 256) yr[i] = from_f32<T>(to_f32(xr[i]) * r * to_f32(g[i]));
+}
+
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
+__device__ __forceinline__ f32x4_t load4(const float* p) { return *(const f32x4_t*)p; }
+__device__ __forceinline__ f32x4_t load4(const bf16_t* p) {
+  bf16x4_t v = *(const bf16x4_t*)p;
+  f32x4_t r = {(float)v[0], (float)v[1], (float)v[2], (float)v[3]};
+  return r;
+}
+
+// Same for bf16 output with d a multiple of 4 and d <= 4*256*NCH: the row is read once (16- or 8-byte
+// vectors), kept in registers across the reduction, and written as 8-byte vectors.
+template <typename TX, int NCH>
+__global__ void __launch_bounds__(256) rmsnorm_vec_kernel(const TX* __restrict__ x, const bf16_t* __restrict__ g,
+                                                          bf16_t* __restrict__ y, int d, float eps) {
+  __shared__ float part[4];
+  const TX* xr = x + (int64_t)blockIdx.x * d;
+  bf16_t* yr = y + (int64_t)blockIdx.x * d;
+  f32x4_t v[NCH];
+  float ss = 0.f;
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int i = (threadIdx.x + c * 256) * 4;
+    if (i < d) {
+      v[c] = load4(xr + i);
+      ss += v[c][0] * v[c][0] + v[c][1] * v[c][1] + v[c][2] * v[c][2] + v[c][3] * v[c][3];
+    }
+  }
+  ss = wave_sum(ss);
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  const float tot = part[0] + part[1] + part[2] + part[3];
+  const float r = 1.0f / sqrtf(tot / (float)d + eps);
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int i = (threadIdx.x + c * 256) * 4;
+    if (i < d) {
+      f32x4_t gg = load4(g + i);
+      bf16x4_t o;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[e] = (bf16_t)(v[c][e] * r * gg[e]);
+      *(bf16x4_t*)(yr + i) = o;
+    }
+  }
 }
 
 // cos/sin of position * theta_i, angle and sincos in fp64, stored as fp32.
@@ -94,7 +139,17 @@ hipError_t launch_rmsnorm(int dtype, const void* x, int x_f32, const void* g, vo
   if (T <= 0) return hipSuccess;
   if (dtype == DSK_F32)
     hipLaunchKernelGGL((rmsnorm_kernel<float, float>), dim3(T), dim3(256), 0, s, (const float*)x, (const float*)g, (float*)y, d, eps);
-  else if (x_f32)
+  else if (d % 4 == 0 && d <= 4096) {
+    if (x_f32)
+      hipLaunchKernelGGL((rmsnorm_vec_kernel<float, 4>), dim3(T), dim3(256), 0, s, (const float*)x, (const bf16_t*)g, (bf16_t*)y, d, eps);
+    else
+      hipLaunchKernelGGL((rmsnorm_vec_kernel<bf16_t, 4>), dim3(T), dim3(256), 0, s, (const bf16_t*)x, (const bf16_t*)g, (bf16_t*)y, d, eps);
+  } else if (d % 4 == 0 && d <= 8192) {
+    if (x_f32)
+      hipLaunchKernelGGL((rmsnorm_vec_kernel<float, 8>), dim3(T), dim3(256), 0, s, (const float*)x, (const bf16_t*)g, (bf16_t*)y, d, eps);
+    else
+      hipLaunchKernelGGL((rmsnorm_vec_kernel<bf16_t, 8>), dim3(T), dim3(256), 0, s, (const bf16_t*)x, (const bf16_t*)g, (bf16_t*)y, d, eps);
+  } else if (x_f32)
     hipLaunchKernelGGL((rmsnorm_kernel<float, bf16_t>), dim3(T), dim3(256), 0, s, (const float*)x, (const bf16_t*)g, (bf16_t*)y, d, eps);
   else
     hipLaunchKernelGGL((rmsnorm_kernel<bf16_t, bf16_t>), dim3(T), dim3(256), 0, s, (const bf16_t*)x, (const bf16_t*)g, (bf16_t*)y, d, eps);
