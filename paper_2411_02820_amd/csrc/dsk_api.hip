@@ -1,7 +1,6 @@
 // C-ABI entry points and the host-side scheduler (streams, per-layer load events) of libdsk.
 #include <math.h>
 #include <stdlib.h>
-#include <stdio.h>
 #include <string.h>
 
 #include <new>
@@ -87,8 +86,7 @@ inline char* kv_v(const dsk_kv_t* kv, int l) { return kv_k(kv, l) + kv->v_offset
 
 int g_force_generic = 0;
 int g_time_gemm = 0;
-int g_linear_ld_pad = 0;
-void* g_dbg_trace = nullptr;  // experiment knob: dsk_linear reads x and w with row stride K + pad
+int g_linear_ld_pad = 0;  // experiment knob: dsk_linear reads x and w with row stride K + pad
 
 // launch counters and the event pairs recorded under "time_gemm"
 struct Stats {
@@ -520,7 +518,7 @@ int dsk_linear(int dtype, const void* x, const void* w, void* y, const void* r, 
   if (dtype != DSK_F32 && dtype != DSK_BF16) return DSK_EDTYPE;
   if (!aligned16(x) || !aligned16(w) || !aligned16(y) || !aligned16(r)) return DSK_EINVAL;
   const int epi = r ? EPI_RESIDUAL : EPI_STORE;
-  HIP_TRY(gemm_any(dtype, x, K + g_linear_ld_pad, w, K + g_linear_ld_pad, y, N, r, N, M, N, K, epi, g_dbg_trace, 0, (hipStream_t)stream));
+  HIP_TRY(gemm_any(dtype, x, K + g_linear_ld_pad, w, K + g_linear_ld_pad, y, N, r, N, M, N, K, epi, nullptr, 0, (hipStream_t)stream));
   return DSK_OK;
 }
 
@@ -565,20 +563,6 @@ int dsk_set_option(const char* name, int value) {
   else if (!strcmp(name, "force_generic")) g_force_generic = value;
   else if (!strcmp(name, "time_gemm")) g_time_gemm = value;
   else if (!strcmp(name, "linear_ld_pad")) g_linear_ld_pad = value;
-  else if (!strcmp(name, "dbg_trace_alloc")) { if (!g_dbg_trace) (void)hipMalloc(&g_dbg_trace, 8 * 64 * 3 * 8); }
-  else if (!strcmp(name, "dbg_trace_dump")) {
-    unsigned long long h[8 * 64 * 3];
-    (void)hipMemcpy(h, g_dbg_trace, sizeof(h), hipMemcpyDeviceToHost);
-    for (int t = 8; t < 8 + value; ++t) {
-      printf("it %2d:", t);
-      for (int w = 0; w < 8; ++w) {
-        unsigned long long* a = h + (w * 64 + t) * 3;
-        unsigned long long* pa = h + (w * 64 + t - 1) * 3;
-        printf(" | w%d comp %4llu vm %4llu bar %4llu", w, a[0] - pa[2], a[1] - a[0], a[2] - a[1]);
-      }
-      printf("\n");
-    }
-  }
   else if (!strcmp(name, "reset_stats")) {
     g_stats.gemm_mfma = g_stats.gemm_generic = g_stats.attn_mfma = g_stats.attn_generic = 0;
     g_stats.n_timed = 0;

@@ -19,6 +19,8 @@
 // Small M (the suffix pass: tens of rows) is a weight-streaming problem: a 64 x 64 tile, K split over
 // blockIdx.y so that enough workgroups stream W to fill HBM; each split writes an fp32 partial tile and a
 // second kernel adds the partials in a fixed order (deterministic), applies the residual and rounds.
+#include <type_traits>
+
 #include "dsk_internal.h"
 
 namespace {
@@ -65,7 +67,7 @@ template <int BM, int BN, int WAVES_M, int WAVES_N, bool PARTIAL, bool SWIGLU = 
 __global__ void __launch_bounds__(WAVES_M* WAVES_N * 64)
     gemm_bf16_kernel(const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ W, int64_t ldw,
                      void* __restrict__ C, int64_t ldc, const void* __restrict__ R, int64_t ldr,
-                     float* __restrict__ P, int M, int N, int K, int epi, int tiles_m, int tiles_n, int kt_per_split, int dbg) {
+                     float* __restrict__ P, int M, int N, int K, int epi, int tiles_m, int tiles_n, int kt_per_split) {
   constexpr int NW = WAVES_M * WAVES_N;
   constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;  // wave tile
   constexpr int TM = WTM / 32, TN = WTN / 32;            // 32x32 MFMA tiles per wave
@@ -114,17 +116,19 @@ __global__ void __launch_bounds__(WAVES_M* WAVES_N * 64)
   }
   typedef __attribute__((address_space(3))) void lds_void;
   typedef const __attribute__((address_space(1))) void glb_void;
-  auto issue_loads = [&](int stage, int k0, int skip = 0) {
-    if (!(skip & 2))
+  constexpr int PER_TILE = A_INST + W_INST;  // load instructions per wave per k-tile
+  auto issue_load = [&](int stage, int k0, int idx) {
+    if (idx < A_INST)
+      __builtin_amdgcn_global_load_lds((glb_void*)(a_src[idx] + k0),
+                                       (lds_void*)(sA + stage * BM * BK + RPI * (wave * A_INST + idx) * BK), 16, 0, 0);
+    else
+      __builtin_amdgcn_global_load_lds((glb_void*)(w_src[idx - A_INST] + k0),
+                                       (lds_void*)(sW + stage * BN * BK + RPI * (wave * W_INST + idx - A_INST) * BK), 16,
+                                       0, 0);
+  };
+  auto issue_loads = [&](int stage, int k0) {
 #pragma unroll
-    for (int i = 0; i < A_INST; ++i)
-      __builtin_amdgcn_global_load_lds((glb_void*)(a_src[i] + k0),
-                                       (lds_void*)(sA + stage * BM * BK + RPI * (wave * A_INST + i) * BK), 16, 0, 0);
-    if (!(skip & 1))
-#pragma unroll
-    for (int i = 0; i < W_INST; ++i)
-      __builtin_amdgcn_global_load_lds((glb_void*)(w_src[i] + k0),
-                                       (lds_void*)(sW + stage * BN * BK + RPI * (wave * W_INST + i) * BK), 16, 0, 0);
+    for (int i = 0; i < PER_TILE; ++i) issue_load(stage, k0, i);
   };
 
   f32x16 acc[TN][TM];
@@ -155,7 +159,6 @@ __global__ void __launch_bounds__(WAVES_M* WAVES_N * 64)
   // tile kt+2.  After the barrier a wave still owns the MFMAs of the last k-step (fragments already in
   // registers) and issues the first fragment reads of tile kt+1 under them, so the restart after a barrier
   // never waits on LDS.
-  constexpr int PER_TILE = A_INST + W_INST;
   const int n_kt = kt_end - kt_begin;
   issue_loads(0, kt_begin * BK);
   if (n_kt > 1) {
@@ -167,40 +170,57 @@ __global__ void __launch_bounds__(WAVES_M* WAVES_N * 64)
   __syncthreads();
   bf16x8 xf[2][TM], wf[2][TN];
   load_frags(sA, sW, 0, xf[0], wf[0]);
-  for (int t = 0; t < n_kt; ++t) {
+  // one k-tile; the two flags are compile-time so that the steady-state loop body is a single basic block
+  // (precise s_waitcnt counts) and the tail tiles are peeled
+  auto tile_step = [&](int t, auto has_next, auto has_next2) {
     const int stage = t & 1;
     const bf16_t* a_s = sA + stage * BM * BK;
     const bf16_t* w_s = sW + stage * BN * BK;
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) {
       const int cur = ks & 1;
-      if (ks + 1 < NKS) {
-        load_frags(a_s, w_s, ks + 1, xf[cur ^ 1], wf[cur ^ 1]);
-      } else {
+      constexpr int NM = TN * TM;
+      constexpr int LEAD = NM >= 8 ? 2 : 1;  // MFMAs issued before the next fragment reads
+      if (ks + 1 == NKS) {
         // all reads of this tile are done; tile t+1 has landed (only its loads are outstanding)
-        unsigned long long t0 = 0, t1 = 0, t2 = 0;
-        if (dbg & 4) t0 = __builtin_readcyclecounter();
         asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-        if (dbg & 4) t1 = __builtin_readcyclecounter();
         __syncthreads();
-        if (dbg & 4) {
-          t2 = __builtin_readcyclecounter();
-          if (blockIdx.x == 300 && lane == 0 && t < 64) {
-            unsigned long long* tr = (unsigned long long*)P + (wave * 64 + t) * 3;
-            tr[0] = t0; tr[1] = t1; tr[2] = t2;
-          }
-        }
-        if (t + 2 < n_kt) issue_loads(stage, (kt_begin + t + 2) * BK, dbg);
-        if (t + 1 < n_kt)
+        if (has_next)
           load_frags(sA + (stage ^ 1) * BM * BK, sW + (stage ^ 1) * BN * BK, 0, xf[cur ^ 1], wf[cur ^ 1]);
       }
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TM; ++i) {
+          const int m = j * TM + i;
+          if (ks + 1 < NKS && m == LEAD) {
+            // Fragment reads of the next k-step go out after the first MFMAs of this one: the s_waitcnt the
+            // compiler puts in front of this k-step then only covers reads issued a whole k-step earlier, and
+            // the new reads have the remaining MFMAs to land.
+            __builtin_amdgcn_sched_barrier(0);
+            load_frags(a_s, w_s, ks + 1, xf[cur ^ 1], wf[cur ^ 1]);
+            __builtin_amdgcn_sched_barrier(0);
+          }
           acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[cur][j], xf[cur][i], acc[j][i], 0, 0, 0);
+          if (ks + 1 == NKS && has_next2) {
+            // the loads of tile t+2 (its stage was freed by the barrier) go out one by one between the MFMAs of
+            // the last k-step: a wave that queues several vector-memory instructions back to back cannot issue
+            // its MFMAs until the address unit has taken them
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int q = m * PER_TILE / NM; q < (m + 1) * PER_TILE / NM; ++q)
+              issue_load(stage, (kt_begin + t + 2) * BK, q);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
+      __builtin_amdgcn_sched_barrier(0);
     }
-  }
+  };
+  int t = 0;
+  for (; t + 2 < n_kt; ++t) tile_step(t, std::true_type{}, std::true_type{});
+  if (t + 1 < n_kt) { tile_step(t, std::true_type{}, std::false_type{}); ++t; }
+  if (t < n_kt) tile_step(t, std::false_type{}, std::false_type{});
 
   // ---- epilogue: accumulator register 4q+e of tile (j,i) is C[m][n + e],
   //      m = tile row base + lane%32, n = tile col base + 8q + 4*(lane/32) ----
@@ -268,8 +288,6 @@ __global__ void __launch_bounds__(256) splitk_reduce_kernel(const float* __restr
   store_quad(C, ldc, R, ldr, m, n, s, epi);
 }
 
-int g_dbg = 0;
-
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool PARTIAL, bool SWIGLU = false>
 hipError_t launch(const void* A, int64_t lda, const void* W, int64_t ldw, void* C, int64_t ldc, const void* R, int64_t ldr,
                   float* P, int M, int N, int K, int epi, int splits, int kt_per_split, hipStream_t s) {
@@ -283,7 +301,7 @@ hipError_t launch(const void* A, int64_t lda, const void* W, int64_t ldw, void* 
   }
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n, splits), dim3(WAVES_M * WAVES_N * 64), lds, s, (const bf16_t*)A, lda,
-                     (const bf16_t*)W, ldw, C, ldc, R, ldr, P, M, N, K, epi, tiles_m, tiles_n, kt_per_split, g_dbg);
+                     (const bf16_t*)W, ldw, C, ldc, R, ldr, P, M, N, K, epi, tiles_m, tiles_n, kt_per_split);
   return hipGetLastError();
 }
 
@@ -291,7 +309,7 @@ int g_variant = 0;
 
 }  // namespace
 
-void gemm_mfma_set_variant(int v) { g_variant = v % 10; g_dbg = v / 10; }
+void gemm_mfma_set_variant(int v) { g_variant = v; }
 
 // the fused gate/up epilogue needs whole 64-row gate/up blocks and is not offered on the split-K path
 bool gemm_mfma_swiglu_supported(int M, int N, int K) { return M > 64 && N % 64 == 0 && K >= BK && K % BK == 0; }
@@ -309,7 +327,7 @@ hipError_t launch_gemm_mfma_bf16(const void* A, int64_t lda, const void* W, int6
   if (epi & EPI_SWIGLU) {
     if (!gemm_mfma_swiglu_supported(M, N, K)) return hipErrorNotSupported;
     if ((int64_t)((M + 255) / 256) * ((N + 255) / 256) >= 192 || variant == 1)
-      return launch<256, 256, 2, 4, false, true>(A, lda, W, ldw, C, ldc, R, ldr, (float*)ws, M, N, K, epi, 1, KT, s);
+      return launch<256, 256, 2, 4, false, true>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
     return launch<128, 128, 2, 2, false, true>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
   }
   if (variant == 0) {
@@ -335,8 +353,6 @@ hipError_t launch_gemm_mfma_bf16(const void* A, int64_t lda, const void* W, int6
       return launch<64, 64, 1, 2, false>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
     }
     case 2: return launch<128, 128, 2, 2, false>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
-    default:
-      if ((g_dbg & 4) && !ws) return hipErrorInvalidValue;  // the trace build writes timestamps through P
-      return launch<256, 256, 2, 4, false>(A, lda, W, ldw, C, ldc, R, ldr, (float*)ws, M, N, K, epi, 1, KT, s);
+    default: return launch<256, 256, 2, 4, false>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
   }
 }
