@@ -39,6 +39,19 @@ def recompute_flops(shape, lens, n_layers):
     return n_layers * (gemm + attn)
 
 
+def measured_traffic(workload):
+    """HBM-side bytes per launch of the dominant kernel, from the committed rocprofv3 --pmc summary
+    (FETCH_SIZE and WRITE_SIZE runs scaled by a known-size copy); None if this workload has none."""
+    path = os.path.join(ROOT, "profiles", f"bench_{workload}_gemm_pmc_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch"):
+                return float(line.split()[1])
+    except OSError:
+        pass
+    return None
+
+
 def time_region(torch, fn, reps):
     s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
@@ -258,8 +271,9 @@ def main():
     if shape.dtype == "bf16" and gemm_n > 0:
         achieved = gemm_flops / (gemm_ms * 1e-3) / 1e12
         out["roofline"] = {"bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                           "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
-                           "kernel": "gemm_bf16_kernel (prefill GEMMs: QKV, O, gate/up, down)",
+                           "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": measured_traffic(args.workload),
+                           "traffic_unit": "bytes per launch (L2<->fabric reads + writes, rocprofv3 --pmc, see profiles/)",
+                           "kernel": "gemm_bf16_kernel<256,256,2,4> (prefill GEMMs: QKV, O, gate/up, down)",
                            "launches": int(gemm_n), "avg_launch_ms": round(gemm_ms / gemm_n, 4),
                            "flops_per_launch": round(gemm_flops / gemm_n / 1e9, 1), "flops_unit": "GFLOP"}
     else:

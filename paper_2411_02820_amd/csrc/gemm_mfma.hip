@@ -60,10 +60,11 @@ __device__ __forceinline__ void store_quad(void* C, int64_t ldc, const void* R, 
 }
 
 // PARTIAL: write the fp32 accumulators of this K split to P[split][M][N] instead of the bf16 result.
-// SWIGLU: W holds gate and up rows interleaved in blocks of 32 (packed rows 64b..64b+31 = gate rows 32b.., the
-// next 32 = the same up rows), so MFMA tiles j (even) and j+1 of a wave are gate and up of the same 32 FFN
-// indices at the same lane/register; the epilogue writes silu(gate)*up to C[M, N/2].
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool PARTIAL, bool SWIGLU = false>
+// EPI_SWIGLU (run-time flag; wave tiles with an even number of 32-column MFMA tiles): W holds gate and up
+// rows interleaved in blocks of 32 (packed rows 64b..64b+31 = gate rows 32b.., the next 32 = the same up
+// rows), so MFMA tiles j (even) and j+1 of a wave are gate and up of the same 32 FFN indices at the same
+// lane/register; the epilogue writes silu(gate)*up to C[M, N/2].
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool PARTIAL>
 __global__ void __launch_bounds__(WAVES_M* WAVES_N * 64)
     gemm_bf16_kernel(const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ W, int64_t ldw,
                      void* __restrict__ C, int64_t ldc, const void* __restrict__ R, int64_t ldr,
@@ -224,8 +225,7 @@ __global__ void __launch_bounds__(WAVES_M* WAVES_N * 64)
 
   // ---- epilogue: accumulator register 4q+e of tile (j,i) is C[m][n + e],
   //      m = tile row base + lane%32, n = tile col base + 8q + 4*(lane/32) ----
-  if constexpr (SWIGLU) {
-    static_assert(TN % 2 == 0 && !PARTIAL, "gate/up tiles come in pairs");
+  if constexpr (TN % 2 == 0 && !PARTIAL) if (epi & EPI_SWIGLU) {
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
       const int m = m0 + wm * WTM + i * 32 + frag_row;
@@ -288,10 +288,10 @@ __global__ void __launch_bounds__(256) splitk_reduce_kernel(const float* __restr
   store_quad(C, ldc, R, ldr, m, n, s, epi);
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool PARTIAL, bool SWIGLU = false>
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool PARTIAL>
 hipError_t launch(const void* A, int64_t lda, const void* W, int64_t ldw, void* C, int64_t ldc, const void* R, int64_t ldr,
                   float* P, int M, int N, int K, int epi, int splits, int kt_per_split, hipStream_t s) {
-  auto kern = gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, PARTIAL, SWIGLU>;
+  auto kern = gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, PARTIAL>;
   constexpr int lds = NSTAGE * (BM + BN) * BK * 2;
   static bool configured = false;
   if (!configured) {
@@ -327,8 +327,8 @@ hipError_t launch_gemm_mfma_bf16(const void* A, int64_t lda, const void* W, int6
   if (epi & EPI_SWIGLU) {
     if (!gemm_mfma_swiglu_supported(M, N, K)) return hipErrorNotSupported;
     if ((int64_t)((M + 255) / 256) * ((N + 255) / 256) >= 192 || variant == 1)
-      return launch<256, 256, 2, 4, false, true>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
-    return launch<128, 128, 2, 2, false, true>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
+      return launch<256, 256, 2, 4, false>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
+    return launch<128, 128, 2, 2, false>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
   }
   if (variant == 0) {
     if (M <= 64) variant = 3;
