@@ -101,31 +101,38 @@ __global__ void __launch_bounds__(WAVES_M* WAVES_N * 64)
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave % WAVES_M, wn = wave / WAVES_M;
 
-  // ---- per-lane global source of each wave load instruction ----
+  // ---- per-lane global source of each wave load instruction: a 32-bit byte offset from the (uniform) matrix
+  //      base, so that the loads use the scalar-base + vector-offset address form and the walk along K only
+  //      moves the scalar base ----
   const int lr = lane / CH, lp = lane % CH;
-  const bf16_t* a_src[A_INST];
-  const bf16_t* w_src[W_INST];
+  uint32_t a_off[A_INST], w_off[W_INST];
 #pragma unroll
   for (int i = 0; i < A_INST; ++i) {
     int row = RPI * (wave * A_INST + i) + lr;
-    a_src[i] = A + (int64_t)min(m0 + row, M - 1) * lda + (lp ^ ((row >> 1) & (CH - 1))) * 8;
+    a_off[i] = (uint32_t)(((int64_t)min(m0 + row, M - 1) * lda + (lp ^ ((row >> 1) & (CH - 1))) * 8) * 2);
   }
 #pragma unroll
   for (int i = 0; i < W_INST; ++i) {
     int row = RPI * (wave * W_INST + i) + lr;
-    w_src[i] = W + (int64_t)min(n0 + row, N - 1) * ldw + (lp ^ ((row >> 1) & (CH - 1))) * 8;
+    w_off[i] = (uint32_t)(((int64_t)min(n0 + row, N - 1) * ldw + (lp ^ ((row >> 1) & (CH - 1))) * 8) * 2);
   }
   typedef __attribute__((address_space(3))) void lds_void;
   typedef const __attribute__((address_space(1))) void glb_void;
   constexpr int PER_TILE = A_INST + W_INST;  // load instructions per wave per k-tile
+  // global_load_lds_dwordx4 in its scalar-base + 32-bit vector-offset form; M0 carries the LDS byte address
+  // of the 1 KB the wave fills (lane i lands at M0 + 16*i)
+  const uint32_t sA_lds = (uint32_t)(uintptr_t)sA, sW_lds = (uint32_t)(uintptr_t)sW;
   auto issue_load = [&](int stage, int k0, int idx) {
-    if (idx < A_INST)
-      __builtin_amdgcn_global_load_lds((glb_void*)(a_src[idx] + k0),
-                                       (lds_void*)(sA + stage * BM * BK + RPI * (wave * A_INST + idx) * BK), 16, 0, 0);
-    else
-      __builtin_amdgcn_global_load_lds((glb_void*)(w_src[idx - A_INST] + k0),
-                                       (lds_void*)(sW + stage * BN * BK + RPI * (wave * W_INST + idx - A_INST) * BK), 16,
-                                       0, 0);
+    const bool is_a = idx < A_INST;
+    const int li = is_a ? idx : idx - A_INST;
+    const char* base = (is_a ? (const char*)A : (const char*)W) + (int64_t)k0 * 2;
+    const uint32_t voff = is_a ? a_off[li] : w_off[li];
+    const uint32_t dst = is_a ? sA_lds + (uint32_t)(stage * BM * BK + RPI * (wave * A_INST + li) * BK) * 2
+                              : sW_lds + (uint32_t)(stage * BN * BK + RPI * (wave * W_INST + li) * BK) * 2;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(dst), "v"(voff), "s"(base)
+                 : "memory", "m0");
   };
   auto issue_loads = [&](int stage, int k0) {
 #pragma unroll
@@ -322,6 +329,8 @@ hipError_t launch_gemm_mfma_bf16(const void* A, int64_t lda, const void* W, int6
   if (M <= 0 || N <= 0) return hipSuccess;
   if (K < BK || K % BK || N % 4 || (lda & 7) || (ldw & 7) || (ldc & 3) || ((epi & EPI_RESIDUAL) && (ldr & 3)))
     return hipErrorNotSupported;
+  // rows are addressed by 32-bit byte offsets from the matrix base
+  if ((int64_t)M * lda * 2 >= ((int64_t)1 << 32) || (int64_t)N * ldw * 2 >= ((int64_t)1 << 32)) return hipErrorNotSupported;
   const int KT = K / BK;
   int variant = g_variant;
   if (epi & EPI_SWIGLU) {
