@@ -3,7 +3,7 @@
 // queries' own causal range), online softmax in fp32.
 //
 // A workgroup (4 waves) owns 128 query rows of one (sequence, q head); each wave 32 of them.
-// Keys are walked in tiles of 64 cache rows (aligned to multiples of 64), staged in a two-stage LDS ring
+// Keys are walked in tiles of 64 cache rows (aligned to multiples of 64), staged in two-stage LDS rings
 // by direct global->LDS loads (global_load_lds_dwordx4):
 //   K tile  [64 keys][dh]   - rows permuted (bits 2 and 3 of the key offset swapped), see below
 //   Vt tile [dh][64 keys]   - from a transposed copy of V kept in the model's workspace
@@ -53,8 +53,9 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
   constexpr int K_INST = BKV / K_RPI / 4; // per wave
   constexpr int V_INST = DH / 8 / 4;      // Vt rows are 64 keys = 8 slots -> 8 rows per instruction
   constexpr int NKS = DH / 16, NDT = DH / 32;
-  __shared__ __attribute__((aligned(16))) bf16_t sK[2][BKV * DH];
-  __shared__ __attribute__((aligned(16))) bf16_t sV[2][DH * BKV];
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  bf16_t* sK = (bf16_t*)smem_raw;        // [2][BKV * DH]  K ring
+  bf16_t* sV = sK + 2 * BKV * DH;        // [2][DH * BKV]  Vt ring
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -122,18 +123,39 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
   typedef __attribute__((address_space(3))) void lds_void;
   typedef const __attribute__((address_space(1))) void glb_void;
   auto tile_row0 = [&](int it) { return (it < nA ? ta0 + it : tb0 + (it - nA)) * BKV; };
-  auto issue_loads = [&](int stage, int it) {
-    const int r0 = tile_row0(it);
+  auto issue_k = [&](int it) {
+    const int r0 = tile_row0(it), stage = (it - it_begin) & 1;
 #pragma unroll
     for (int i = 0; i < K_INST; ++i) {
       const int row = min(r0 + k_u[i], p.k_row_max);
       __builtin_amdgcn_global_load_lds((glb_void*)(k_base + (int64_t)row * ldkv + k_coff[i]),
-                                       (lds_void*)(&sK[stage][K_RPI * (wave * K_INST + i) * DH]), 16, 0, 0);
+                                       (lds_void*)(sK + stage * BKV * DH + K_RPI * (wave * K_INST + i) * DH), 16, 0, 0);
     }
+  };
+  auto issue_v = [&](int it) {
+    const int r0 = tile_row0(it), stage = (it - it_begin) & 1;
 #pragma unroll
     for (int i = 0; i < V_INST; ++i)
       __builtin_amdgcn_global_load_lds((glb_void*)(v_src[i] + r0),
-                                       (lds_void*)(&sV[stage][8 * (wave * V_INST + i) * BKV]), 16, 0, 0);
+                                       (lds_void*)(sV + stage * DH * BKV + 8 * (wave * V_INST + i) * BKV), 16, 0, 0);
+  };
+  // a wave skips a tile that lies wholly beyond the causal limit of all its queries
+  auto tile_skipped = [&](int it) { return !wave_active || (it >= nA && tile_row0(it) > wave_lim_max); };
+  // S^T = K Q^T for the two 32-key halves of tile `it`
+  auto scores = [&](int it, f32x16* s) {
+    const bf16_t* kt_s = sK + ((it - it_begin) & 1) * BKV * DH;
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[kt][r] = 0.f;
+      const int row = 32 * kt + lq;
+      const bf16_t* kr = kt_s + row * DH;
+#pragma unroll
+      for (int ks = 0; ks < NKS; ++ks) {
+        bf16x8 kf = *(const bf16x8*)(kr + (((2 * ks + hh) ^ (row & 7)) * 8));
+        s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kt], 0, 0, 0);
+      }
+    }
   };
 
   f32x16 o[NDT];
@@ -143,35 +165,39 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
     for (int r = 0; r < 16; ++r) o[dt][r] = 0.f;
   float m = -INFINITY, l = 0.f;
 
+  // Software pipeline over key tiles, one barrier per tile:
+  //   [wait K(i+1), Vt(i); barrier]  issue loads K(i+2), Vt(i+1)  |  S(i+1) = K(i+1) Q^T (MFMA)
+  //   softmax of S(i) (VALU, runs while the MFMAs of S(i+1) drain)  |  O^T += Vt(i) P(i)^T (MFMA)
+  // so a wave always has matrix work in flight during its softmax.  Two-stage rings suffice: K(i+2) overwrites
+  // K(i), whose last reader S(i) ran one iteration earlier (before this iteration's barrier); Vt(i+1)
+  // overwrites Vt(i-1), last read by the previous iteration's O update.
+  f32x16 s_cur[2], s_nxt[2];
+#pragma unroll
+  for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s_cur[kt][r] = s_nxt[kt][r] = 0.f;
   if (it_begin < it_end) {
-    issue_loads(0, it_begin);
+    issue_k(it_begin);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
+    if (it_begin + 1 < it_end) issue_k(it_begin + 1);
+    issue_v(it_begin);
+    if (!tile_skipped(it_begin)) scores(it_begin, s_cur);
   }
   for (int it = it_begin; it < it_end; ++it) {
-    const int stage = (it - it_begin) & 1;
-    if (it + 1 < it_end) issue_loads(stage ^ 1, it + 1);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // K(it+1) and Vt(it): this wave's part
+    __syncthreads();
+    if (it + 2 < it_end) issue_k(it + 2);
+    if (it + 1 < it_end) issue_v(it + 1);
+    const bool skip_next = it + 1 >= it_end || tile_skipped(it + 1);
+    if (!skip_next) scores(it + 1, s_nxt);
     const int r0 = tile_row0(it);
     const bool segA = it < nA;
     // visible key rows for this lane in this segment: [lo, hi]
     const int lo = segA ? pre_begin : own_begin;
     const int hi = segA ? pre_end - 1 : lim;
-    const bool skip = !wave_active || (!segA && r0 > wave_lim_max);
-    if (!skip) {
-      // S^T = K Q^T for the two 32-key halves of the tile
-      f32x16 s[2];
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[kt][r] = 0.f;
-        const int row = 32 * kt + lq;
-        const bf16_t* kr = &sK[stage][row * DH];
-#pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) {
-          bf16x8 kf = *(const bf16x8*)(kr + (((2 * ks + hh) ^ (row & 7)) * 8));
-          s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kt], 0, 0, 0);
-        }
-      }
+    if (!tile_skipped(it)) {
+      f32x16* s = s_cur;
       // mask: register r of half kt is key r0 + 32*kt + 16*(r/8) + 8*(lane/32) + r%8
       const bool full = r0 >= lo && r0 + BKV - 1 <= (segA ? pre_end - 1 : wave_lim_min);
       if (!full) {
@@ -207,15 +233,20 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
         }
       l = l * alpha + psum;
       m = m_new;
+      // rescale the output accumulators only if some query of the wave saw a new maximum (after the first
+      // few tiles of a row that is rare)
+      if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
 #pragma unroll
-      for (int dt = 0; dt < NDT; ++dt)
+        for (int dt = 0; dt < NDT; ++dt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+          for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+      }
       // O^T += Vt P^T
+      const bf16_t* vt_s = sV + ((it - it_begin) & 1) * DH * BKV;
 #pragma unroll
       for (int dt = 0; dt < NDT; ++dt) {
         const int d = 32 * dt + lq;
-        const bf16_t* vr = &sV[stage][d * BKV];
+        const bf16_t* vr = vt_s + d * BKV;
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
@@ -225,8 +256,8 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
           }
       }
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
+    s_cur[0] = s_nxt[0];
+    s_cur[1] = s_nxt[1];
   }
 
   // ---- store: register 4g+e of d-tile dt is out[q][32dt + 8g + 4*(lane/32) + e] ----
@@ -343,6 +374,20 @@ hipError_t launch_transpose_v(const void* v_rows, void* vt, int64_t ldvt, int wi
   return hipGetLastError();
 }
 
+template <int DH, bool SPLIT>
+hipError_t launch_attn(const AttnParams& p, dim3 grid, hipStream_t s) {
+  auto kern = attn_bf16_kernel<DH, SPLIT>;
+  constexpr int lds = (2 * BKV * DH + 2 * DH * BKV) * 2;
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, p);
+  return hipGetLastError();
+}
+
 hipError_t launch_attn_mfma_bf16(const AttnArgs& a, hipStream_t s) {
   if (a.n_q <= 0) return hipSuccess;
   if ((a.dh != 128 && a.dh != 64) || !a.vt || (a.ldq & 7) || a.own_row0 + a.n_q >= ((int64_t)1 << 31))
@@ -381,9 +426,7 @@ hipError_t launch_attn_mfma_bf16(const AttnArgs& a, hipStream_t s) {
     p.part_o = (float*)a.ws;
     p.part_ml = p.part_o + (int64_t)a.n_q * a.Hq * splits * a.dh;
     dim3 grid(total, a.Hq, splits);
-    if (a.dh == 128) hipLaunchKernelGGL((attn_bf16_kernel<128, true>), grid, dim3(256), 0, s, p);
-    else hipLaunchKernelGGL((attn_bf16_kernel<64, true>), grid, dim3(256), 0, s, p);
-    hipError_t e = hipGetLastError();
+    hipError_t e = a.dh == 128 ? launch_attn<128, true>(p, grid, s) : launch_attn<64, true>(p, grid, s);
     if (e != hipSuccess) return e;
     dim3 cgrid(a.n_q, a.Hq);
     if (a.dh == 128)
@@ -393,7 +436,5 @@ hipError_t launch_attn_mfma_bf16(const AttnArgs& a, hipStream_t s) {
     return hipGetLastError();
   }
   dim3 grid(total, a.Hq);
-  if (a.dh == 128) hipLaunchKernelGGL((attn_bf16_kernel<128, false>), grid, dim3(256), 0, s, p);
-  else hipLaunchKernelGGL((attn_bf16_kernel<64, false>), grid, dim3(256), 0, s, p);
-  return hipGetLastError();
+  return a.dh == 128 ? launch_attn<128, false>(p, grid, s) : launch_attn<64, false>(p, grid, s);
 }
