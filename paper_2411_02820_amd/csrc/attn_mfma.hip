@@ -60,10 +60,25 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lq = lane & 31, hh = lane >> 5;
-  const int h = blockIdx.y, kvh = h / (p.Hq / p.Hkv);
-
-  // ---- which (sequence, query tile): heavy (late) tiles are launched first ----
-  int tile = p.total_tiles - 1 - (int)blockIdx.x;
+  // ---- which (head, sequence, query tile).  Workgroups are handed out in blockIdx.x order, round-robin over
+  //      the 8 XCDs (each with its own L2).  Late query tiles carry the most key tiles, so they come first for
+  //      every head (a heavy workgroup started late would run on alone at the end), and with a head count
+  //      that is a multiple of 8 each XCD serves a fixed eighth of the heads, so the q heads of one kv group
+  //      read their K and Vt through the same L2. ----
+  int h, rank;
+  {
+    const int L = blockIdx.x;
+    if ((p.Hq & 7) == 0) {
+      const int hpx = p.Hq >> 3, j = L >> 3;
+      h = (L & 7) * hpx + j % hpx;
+      rank = j / hpx;
+    } else {
+      h = L % p.Hq;
+      rank = L / p.Hq;
+    }
+  }
+  const int kvh = h / (p.Hq / p.Hkv);
+  int tile = p.total_tiles - 1 - rank;
   int b = 0, seq_begin = 0, seq_end = 0;
   for (;; ++b) {
     seq_begin = p.q_cu[b];
@@ -104,7 +119,13 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
   }
 
   // ---- tile loads, direct to LDS.  K: LDS row rho (MFMA row) holds key offset perm_key(rho); slot s of a
-  //      row holds chunk s ^ (rho & 7).  Vt: LDS row d, slot s holds key chunk s ^ (d & 7). ----
+  //      row holds chunk s ^ kswz(rho).  Vt: LDS row d, slot s holds key chunk s ^ vswz(d).  A 16-byte
+  //      fragment read is served 16 lanes (consecutive rows, one slot index) per cycle over 64 banks, so the
+  //      16 lanes must land in 16 different 16-byte bank groups: a 256-byte row covers all banks and needs 16
+  //      different slots (xor with row % 16); 128-byte rows come two per bank sweep and need 8 different
+  //      slots per row pair (xor with (row / 2) % 8). ----
+  auto kswz = [](int row) { return DH * 2 == 256 ? (row & 15) : ((row >> 1) & 7); };
+  auto vswz = [](int d) { return (d >> 1) & 7; };
   const int64_t ldkv = (int64_t)p.Hkv * DH;
   const bf16_t* k_base = p.k + kvh * DH;
   int k_u[K_INST], k_coff[K_INST];
@@ -113,12 +134,12 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
   for (int i = 0; i < K_INST; ++i) {
     const int rho = K_RPI * (wave * K_INST + i) + lane / KCH, s = lane % KCH;
     k_u[i] = perm_key(rho);
-    k_coff[i] = (s ^ (rho & 7)) * 8;
+    k_coff[i] = (s ^ kswz(rho)) * 8;
   }
 #pragma unroll
   for (int i = 0; i < V_INST; ++i) {
     const int d = 8 * (wave * V_INST + i) + (lane >> 3), s = lane & 7;
-    v_src[i] = p.vt + ((int64_t)kvh * DH + d) * p.ldvt + (s ^ (d & 7)) * 8;
+    v_src[i] = p.vt + ((int64_t)kvh * DH + d) * p.ldvt + (s ^ vswz(d)) * 8;
   }
   typedef __attribute__((address_space(3))) void lds_void;
   typedef const __attribute__((address_space(1))) void glb_void;
@@ -152,7 +173,7 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
       const bf16_t* kr = kt_s + row * DH;
 #pragma unroll
       for (int ks = 0; ks < NKS; ++ks) {
-        bf16x8 kf = *(const bf16x8*)(kr + (((2 * ks + hh) ^ (row & 7)) * 8));
+        bf16x8 kf = *(const bf16x8*)(kr + (((2 * ks + hh) ^ kswz(row)) * 8));
         s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kt], 0, 0, 0);
       }
     }
@@ -251,7 +272,7 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
           for (int t = 0; t < 2; ++t) {
-            bf16x8 vf = *(const bf16x8*)(vr + (((4 * kt + 2 * t + hh) ^ (d & 7)) * 8));
+            bf16x8 vf = *(const bf16x8*)(vr + (((4 * kt + 2 * t + hh) ^ vswz(d)) * 8));
             o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kt][t], o[dt], 0, 0, 0);
           }
       }
@@ -425,7 +446,7 @@ hipError_t launch_attn_mfma_bf16(const AttnArgs& a, hipStream_t s) {
   if (splits > 1) {
     p.part_o = (float*)a.ws;
     p.part_ml = p.part_o + (int64_t)a.n_q * a.Hq * splits * a.dh;
-    dim3 grid(total, a.Hq, splits);
+    dim3 grid((unsigned)total * a.Hq, 1, splits);
     hipError_t e = a.dh == 128 ? launch_attn<128, true>(p, grid, s) : launch_attn<64, true>(p, grid, s);
     if (e != hipSuccess) return e;
     dim3 cgrid(a.n_q, a.Hq);
@@ -435,6 +456,6 @@ hipError_t launch_attn_mfma_bf16(const AttnArgs& a, hipStream_t s) {
       hipLaunchKernelGGL(attn_combine_kernel<64>, cgrid, dim3(64), 0, s, p.part_o, p.part_ml, p.out, a.Hq, splits, p.c);
     return hipGetLastError();
   }
-  dim3 grid(total, a.Hq);
+  dim3 grid((unsigned)total * a.Hq);
   return a.dh == 128 ? launch_attn<128, false>(p, grid, s) : launch_attn<64, false>(p, grid, s);
 }
