@@ -21,6 +21,7 @@
 // workgroup can be split over blockIdx.z; each split writes its unnormalised fp32 output with its running
 // maximum and sum, and a second kernel merges the splits in a fixed order.
 #include "dsk_internal.h"
+#include <type_traits>
 
 namespace {
 
@@ -126,159 +127,236 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
   //      slots per row pair (xor with (row / 2) % 8). ----
   auto kswz = [](int row) { return DH * 2 == 256 ? (row & 15) : ((row >> 1) & 7); };
   auto vswz = [](int d) { return (d >> 1) & 7; };
-  const int64_t ldkv = (int64_t)p.Hkv * DH;
+  // A load instruction takes a scalar base (tile origin) plus a 32-bit per-lane byte offset that is the same
+  // for every tile; only a tile that reaches past the last readable cache row needs per-lane clamping.
+  const int ldkv = p.Hkv * DH;
   const bf16_t* k_base = p.k + kvh * DH;
-  int k_u[K_INST], k_coff[K_INST];
-  const bf16_t* v_src[V_INST];
+  const bf16_t* vt_base = p.vt + (int64_t)kvh * DH * p.ldvt;
+  const uint32_t sK_lds = (uint32_t)(uintptr_t)sK, sV_lds = (uint32_t)(uintptr_t)sV;
+  uint32_t k_off[K_INST], v_off[V_INST];
 #pragma unroll
   for (int i = 0; i < K_INST; ++i) {
     const int rho = K_RPI * (wave * K_INST + i) + lane / KCH, s = lane % KCH;
-    k_u[i] = perm_key(rho);
-    k_coff[i] = (s ^ kswz(rho)) * 8;
+    k_off[i] = (uint32_t)(perm_key(rho) * ldkv + (s ^ kswz(rho)) * 8) * 2u;
   }
 #pragma unroll
   for (int i = 0; i < V_INST; ++i) {
     const int d = 8 * (wave * V_INST + i) + (lane >> 3), s = lane & 7;
-    v_src[i] = p.vt + ((int64_t)kvh * DH + d) * p.ldvt + (s ^ vswz(d)) * 8;
+    v_off[i] = (uint32_t)(d * (int)p.ldvt + (s ^ vswz(d)) * 8) * 2u;
   }
-  typedef __attribute__((address_space(3))) void lds_void;
-  typedef const __attribute__((address_space(1))) void glb_void;
+  auto lds_load = [](uint32_t dst, uint32_t voff, const void* base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(dst), "v"(voff), "s"(base) : "memory", "m0");
+  };
   auto tile_row0 = [&](int it) { return (it < nA ? ta0 + it : tb0 + (it - nA)) * BKV; };
   auto issue_k = [&](int it) {
     const int r0 = tile_row0(it), stage = (it - it_begin) & 1;
+    const bf16_t* base = k_base + (int64_t)r0 * ldkv;
+    const bool inside = r0 + BKV - 1 <= p.k_row_max;
 #pragma unroll
     for (int i = 0; i < K_INST; ++i) {
-      const int row = min(r0 + k_u[i], p.k_row_max);
-      __builtin_amdgcn_global_load_lds((glb_void*)(k_base + (int64_t)row * ldkv + k_coff[i]),
-                                       (lds_void*)(sK + stage * BKV * DH + K_RPI * (wave * K_INST + i) * DH), 16, 0, 0);
+      uint32_t off = k_off[i];
+      if (!inside) {
+        const int rho = K_RPI * (wave * K_INST + i) + lane / KCH, s = lane % KCH;
+        off = (uint32_t)(min(perm_key(rho), p.k_row_max - r0) * ldkv + (s ^ kswz(rho)) * 8) * 2u;
+      }
+      lds_load(sK_lds + (uint32_t)(stage * BKV * DH + K_RPI * (wave * K_INST + i) * DH) * 2u, off, base);
     }
   };
   auto issue_v = [&](int it) {
     const int r0 = tile_row0(it), stage = (it - it_begin) & 1;
+    const bf16_t* base = vt_base + r0;
 #pragma unroll
     for (int i = 0; i < V_INST; ++i)
-      __builtin_amdgcn_global_load_lds((glb_void*)(v_src[i] + r0),
-                                       (lds_void*)(sV + stage * DH * BKV + 8 * (wave * V_INST + i) * BKV), 16, 0, 0);
+      lds_load(sV_lds + (uint32_t)(stage * DH * BKV + 8 * (wave * V_INST + i) * BKV) * 2u, v_off[i], base);
   };
-  // a wave skips a tile that lies wholly beyond the causal limit of all its queries
-  auto tile_skipped = [&](int it) { return !wave_active || (it >= nA && tile_row0(it) > wave_lim_max); };
-  // S^T = K Q^T for the two 32-key halves of tile `it`
-  auto scores = [&](int it, f32x16* s) {
-    const bf16_t* kt_s = sK + ((it - it_begin) & 1) * BKV * DH;
-#pragma unroll
-    for (int kt = 0; kt < 2; ++kt) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) s[kt][r] = 0.f;
-      const int row = 32 * kt + lq;
-      const bf16_t* kr = kt_s + row * DH;
-#pragma unroll
-      for (int ks = 0; ks < NKS; ++ks) {
-        bf16x8 kf = *(const bf16x8*)(kr + (((2 * ks + hh) ^ kswz(row)) * 8));
-        s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kt], 0, 0, 0);
-      }
-    }
-  };
+  // A wave has nothing to do in tiles that lie wholly beyond the causal limit of all its queries; those are
+  // the last tiles of the range, so the wave's active tiles are [it_begin, act_end).
+  int act_end = it_begin;
+  if (wave_active) act_end = max(it_begin, min(it_end, nA + wave_lim_max / BKV - tb0 + 1));
 
   f32x16 o[NDT];
 #pragma unroll
   for (int dt = 0; dt < NDT; ++dt)
 #pragma unroll
     for (int r = 0; r < 16; ++r) o[dt][r] = 0.f;
-  float m = -INFINITY, l = 0.f;
+  // running state: m = row maximum over the tiles scored so far, mc = m * c (0 while no key was visible),
+  // alpha = factor that brings sums and outputs accumulated under the previous maximum to m
+  float m = -INFINITY, mc = 0.f, alpha = 1.f, l = 0.f;
 
-  // Software pipeline over key tiles, one barrier per tile:
-  //   [wait K(i+1), Vt(i); barrier]  issue loads K(i+2), Vt(i+1)  |  S(i+1) = K(i+1) Q^T (MFMA)
-  //   softmax of S(i) (VALU, runs while the MFMAs of S(i+1) drain)  |  O^T += Vt(i) P(i)^T (MFMA)
-  // so a wave always has matrix work in flight during its softmax.  Two-stage rings suffice: K(i+2) overwrites
-  // K(i), whose last reader S(i) ran one iteration earlier (before this iteration's barrier); Vt(i+1)
-  // overwrites Vt(i-1), last read by the previous iteration's O update.
-  f32x16 s_cur[2], s_nxt[2];
+  constexpr int NQK = 2 * NKS;   // MFMAs of one score tile
+  constexpr int NPV = 4 * NDT;   // MFMAs of one output update
+  auto k_frag = [&](const bf16_t* kt_s, int j) {
+    const int kt = j / NKS, ks = j % NKS, row = 32 * kt + lq;
+    return *(const bf16x8*)(kt_s + row * DH + (((2 * ks + hh) ^ kswz(row)) * 8));
+  };
+  auto v_frag = [&](const bf16_t* vt_s, int j) {
+    const int dt = j / 4, kt = (j % 4) / 2, t = j % 2, d = 32 * dt + lq;
+    return *(const bf16x8*)(vt_s + d * BKV + (((4 * kt + 2 * t + hh) ^ vswz(d)) * 8));
+  };
+  // masks the scores of tile `it` where a key is outside this lane's visible range;
+  // register r of half kt is key r0 + 32*kt + 16*(r/8) + 8*(lane/32) + r%8
+  auto mask = [&](int it, f32x16* s) {
+    const int r0 = tile_row0(it);
+    const bool segA = it < nA;
+    const int lo = segA ? pre_begin : own_begin;
+    const int hi = segA ? pre_end - 1 : lim;
+    const bool full = r0 >= lo && r0 + BKV - 1 <= (segA ? pre_end - 1 : wave_lim_min);
+    if (!full) {
+      const int kb = r0 + 8 * hh;
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = kb + 32 * kt + 16 * (r >> 3) + (r & 7);
+          s[kt][r] = (key >= lo && key <= hi) ? s[kt][r] : -INFINITY;
+        }
+    }
+  };
+  // the lane's query has its 64 scores of a tile in this lane and in lane^32
+  auto new_max = [&](float mx) {
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m, mx);
+    const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+    alpha = __builtin_amdgcn_exp2f((m - m_safe) * p.c);
+    mc = m_safe * p.c;
+    m = m_new;
+  };
+
+  // One key tile.  The matrix pipe and the vector ALU of a SIMD run side by side only when their
+  // instructions alternate in the instruction stream, so the two matrix phases of a tile are interleaved,
+  // MFMA by MFMA, with the vector work of the neighbouring tile:
+  //   phase 1:  S(it+1) = K(it+1) Q^T      with   P(it) = exp2(S(it) c - m c), row sums, bf16 packing
+  //   phase 2:  O^T += Vt(it) P(it)^T       with   row maximum of S(it+1)
+  // s_i holds the masked scores of tile `it` (m, mc, alpha already include it), s_n receives tile it+1.
+  // Fragments are read from LDS two MFMAs ahead.
+  auto tile_step = [&](auto has_next_c, int it, f32x16* s_i, f32x16* s_n) {
+    constexpr bool HN = decltype(has_next_c)::value;
+    // outputs and sums accumulated so far move to the current maximum (rare after the first tiles of a row)
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+      for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+    }
+    float psum = 0.f;
+    bf16x8 pf[2][2];
+    {
+      const bf16_t* kt_s = sK + ((it + 1 - it_begin) & 1) * BKV * DH;
+      constexpr int EPM = 32 / NQK;
+      bf16x8 kf[NQK];
+      if (HN) {
+        kf[0] = k_frag(kt_s, 0);
+        kf[1] = k_frag(kt_s, 1);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int j = 0; j < NQK; ++j) {
+        if (HN) {
+          if (j + 2 < NQK) kf[j + 2] = k_frag(kt_s, j + 2);
+          const int kt = j / NKS, ks = j % NKS;
+          if (ks == 0) {
+            const f32x16 z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            s_n[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j], qf[ks], z, 0, 0, 0);
+          } else {
+            s_n[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j], qf[ks], s_n[kt], 0, 0, 0);
+          }
+        }
+#pragma unroll
+        for (int e = 0; e < EPM; ++e) {
+          const int idx = j * EPM + e, kt = idx / 16, r = idx % 16;
+          const float ex = __builtin_amdgcn_exp2f(s_i[kt][r] * p.c - mc);
+          psum += ex;
+          pf[kt][r >> 3][r & 7] = (bf16_t)ex;
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    l = l * alpha + psum;
+    if (HN) mask(it + 1, s_n);
+    {
+      const bf16_t* vt_s = sV + ((it - it_begin) & 1) * DH * BKV;
+      constexpr int EPM = 32 / NPV;
+      bf16x8 vf[NPV];
+      vf[0] = v_frag(vt_s, 0);
+      vf[1] = v_frag(vt_s, 1);
+      float mx = -INFINITY;
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int j = 0; j < NPV; ++j) {
+        if (j + 2 < NPV) vf[j + 2] = v_frag(vt_s, j + 2);
+        const int dt = j / 4, kt = (j % 4) / 2, t = j % 2;
+        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[j], pf[kt][t], o[dt], 0, 0, 0);
+        if (HN) {
+#pragma unroll
+          for (int e = 0; e < EPM; ++e) {
+            const int idx = j * EPM + e;
+            mx = fmaxf(mx, s_n[idx / 16][idx % 16]);
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if (HN) new_max(mx);
+    }
+  };
+
+  // Per tile and workgroup one barrier: after it K(it+1) and Vt(it) are complete in LDS and every wave is
+  // done with K(it) and Vt(it-1), whose ring stages the loads issued next overwrite.
+  auto sync_and_loads = [&](int it) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (it + 2 < it_end) issue_k(it + 2);
+    if (it + 1 < it_end) issue_v(it + 1);
+  };
+
+  f32x16 s_a[2], s_b[2];
 #pragma unroll
   for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) s_cur[kt][r] = s_nxt[kt][r] = 0.f;
+    for (int r = 0; r < 16; ++r) s_a[kt][r] = s_b[kt][r] = 0.f;
   if (it_begin < it_end) {
     issue_k(it_begin);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (it_begin + 1 < it_end) issue_k(it_begin + 1);
     issue_v(it_begin);
-    if (!tile_skipped(it_begin)) scores(it_begin, s_cur);
-  }
-  for (int it = it_begin; it < it_end; ++it) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // K(it+1) and Vt(it): this wave's part
-    __syncthreads();
-    if (it + 2 < it_end) issue_k(it + 2);
-    if (it + 1 < it_end) issue_v(it + 1);
-    const bool skip_next = it + 1 >= it_end || tile_skipped(it + 1);
-    if (!skip_next) scores(it + 1, s_nxt);
-    const int r0 = tile_row0(it);
-    const bool segA = it < nA;
-    // visible key rows for this lane in this segment: [lo, hi]
-    const int lo = segA ? pre_begin : own_begin;
-    const int hi = segA ? pre_end - 1 : lim;
-    if (!tile_skipped(it)) {
-      f32x16* s = s_cur;
-      // mask: register r of half kt is key r0 + 32*kt + 16*(r/8) + 8*(lane/32) + r%8
-      const bool full = r0 >= lo && r0 + BKV - 1 <= (segA ? pre_end - 1 : wave_lim_min);
-      if (!full) {
-        const int kb = r0 + 8 * hh;
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int key = kb + 32 * kt + 16 * (r >> 3) + (r & 7);
-            s[kt][r] = (key >= lo && key <= hi) ? s[kt][r] : -INFINITY;
-          }
-      }
-      // online softmax; the query's 64 scores sit in this lane and in lane^32
-      float mx = s[0][0];
+    if (it_begin < act_end) {
 #pragma unroll
       for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kt][r]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m, mx);
-      const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f((m - m_safe) * p.c);
-      const float mc = m_safe * p.c;
-      float psum = 0.f;
-      bf16x8 pf[2][2];
+        for (int ks = 0; ks < NKS; ++ks)
+          s_a[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_frag(sK, kt * NKS + ks), qf[ks], s_a[kt], 0, 0, 0);
+      mask(it_begin, s_a);
+      float mx = -INFINITY;
 #pragma unroll
       for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          float e = __builtin_amdgcn_exp2f(s[kt][r] * p.c - mc);
-          psum += e;
-          pf[kt][r >> 3][r & 7] = (bf16_t)e;
-        }
-      l = l * alpha + psum;
-      m = m_new;
-      // rescale the output accumulators only if some query of the wave saw a new maximum (after the first
-      // few tiles of a row that is rare)
-      if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
-#pragma unroll
-        for (int dt = 0; dt < NDT; ++dt)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
-      }
-      // O^T += Vt P^T
-      const bf16_t* vt_s = sV + ((it - it_begin) & 1) * DH * BKV;
-#pragma unroll
-      for (int dt = 0; dt < NDT; ++dt) {
-        const int d = 32 * dt + lq;
-        const bf16_t* vr = vt_s + d * BKV;
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-          for (int t = 0; t < 2; ++t) {
-            bf16x8 vf = *(const bf16x8*)(vr + (((4 * kt + 2 * t + hh) ^ vswz(d)) * 8));
-            o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kt][t], o[dt], 0, 0, 0);
-          }
-      }
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s_a[kt][r]);
+      new_max(mx);
+      alpha = 1.f;  // nothing accumulated yet
     }
-    s_cur[0] = s_nxt[0];
-    s_cur[1] = s_nxt[1];
+  }
+  {
+    // steady state in pairs so that the two score buffers swap roles without copies; then the wave's last
+    // active tile (no successor to score); then the tiles this wave only helps to load
+    int it = it_begin;
+    for (; it + 2 < act_end; it += 2) {
+      sync_and_loads(it);
+      tile_step(std::true_type{}, it, s_a, s_b);
+      sync_and_loads(it + 1);
+      tile_step(std::true_type{}, it + 1, s_b, s_a);
+    }
+    if (it + 1 < act_end) {
+      sync_and_loads(it);
+      tile_step(std::true_type{}, it, s_a, s_b);
+      sync_and_loads(it + 1);
+      tile_step(std::false_type{}, it + 1, s_b, s_a);
+      it += 2;
+    } else if (it < act_end) {
+      sync_and_loads(it);
+      tile_step(std::false_type{}, it, s_a, s_b);
+      it += 1;
+    }
+    for (; it < it_end; ++it) sync_and_loads(it);
   }
 
   // ---- store: register 4g+e of d-tile dt is out[q][32dt + 8g + 4*(lane/32) + e] ----
@@ -412,6 +490,9 @@ hipError_t launch_attn(const AttnParams& p, dim3 grid, hipStream_t s) {
 hipError_t launch_attn_mfma_bf16(const AttnArgs& a, hipStream_t s) {
   if (a.n_q <= 0) return hipSuccess;
   if ((a.dh != 128 && a.dh != 64) || !a.vt || (a.ldq & 7) || a.own_row0 + a.n_q >= ((int64_t)1 << 31))
+    return hipErrorNotSupported;
+  // per-lane tile offsets are 32-bit byte offsets
+  if ((int64_t)a.dh * a.ldvt * 2 >= ((int64_t)1 << 32) || (int64_t)BKV * a.Hkv * a.dh * 2 >= ((int64_t)1 << 32))
     return hipErrorNotSupported;
   AttnParams p;
   p.q = (const bf16_t*)a.q; p.ldq = a.ldq; p.k = (const bf16_t*)a.k_rows; p.vt = (const bf16_t*)a.vt; p.ldvt = a.ldvt;
