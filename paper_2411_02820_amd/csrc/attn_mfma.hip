@@ -27,6 +27,8 @@ namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
@@ -239,7 +241,7 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
         for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
     }
     float psum = 0.f;
-    bf16x8 pf[2][2];
+    u32x4 pf[2][2];
     {
       const bf16_t* kt_s = sK + ((it + 1 - it_begin) & 1) * BKV * DH;
       constexpr int EPM = 32 / NQK;
@@ -262,11 +264,18 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
           }
         }
 #pragma unroll
-        for (int e = 0; e < EPM; ++e) {
+        for (int e = 0; e < EPM; e += 2) {
           const int idx = j * EPM + e, kt = idx / 16, r = idx % 16;
-          const float ex = __builtin_amdgcn_exp2f(s_i[kt][r] * p.c - mc);
-          psum += ex;
-          pf[kt][r >> 3][r & 7] = (bf16_t)ex;
+          const float e0 = __builtin_amdgcn_exp2f(s_i[kt][r] * p.c - mc);
+          const float e1 = __builtin_amdgcn_exp2f(s_i[kt][r + 1] * p.c - mc);
+          psum += e0;
+          psum += e1;
+          bf16x2 pk = {(bf16_t)e0, (bf16_t)e1};
+          uint32_t pku = __builtin_bit_cast(uint32_t, pk);
+          // keeps this arithmetic between the neighbouring MFMAs (its results are first used in phase 2, and
+          // the optimiser would otherwise move it there)
+          asm volatile("" : "+v"(pku), "+v"(psum));
+          pf[kt][r >> 3][(r & 7) >> 1] = pku;
         }
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -285,7 +294,7 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
       for (int j = 0; j < NPV; ++j) {
         if (j + 2 < NPV) vf[j + 2] = v_frag(vt_s, j + 2);
         const int dt = j / 4, kt = (j % 4) / 2, t = j % 2;
-        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[j], pf[kt][t], o[dt], 0, 0, 0);
+        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[j], __builtin_bit_cast(bf16x8, pf[kt][t]), o[dt], 0, 0, 0);
         if (HN) {
 #pragma unroll
           for (int e = 0; e < EPM; ++e) {
@@ -302,7 +311,7 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
   // Per tile and workgroup one barrier: after it K(it+1) and Vt(it) are complete in LDS and every wave is
   // done with K(it) and Vt(it-1), whose ring stages the loads issued next overwrite.
   auto sync_and_loads = [&](int it) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): as a builtin the compiler accounts for it
     __syncthreads();
     if (it + 2 < it_end) issue_k(it + 2);
     if (it + 1 < it_end) issue_v(it + 1);
@@ -315,7 +324,7 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
     for (int r = 0; r < 16; ++r) s_a[kt][r] = s_b[kt][r] = 0.f;
   if (it_begin < it_end) {
     issue_k(it_begin);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): as a builtin the compiler accounts for it
     __syncthreads();
     if (it_begin + 1 < it_end) issue_k(it_begin + 1);
     issue_v(it_begin);
