@@ -139,37 +139,61 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
 #pragma unroll
   for (int i = 0; i < K_INST; ++i) {
     const int rho = K_RPI * (wave * K_INST + i) + lane / KCH, s = lane % KCH;
-    k_off[i] = (uint32_t)(perm_key(rho) * ldkv + (s ^ kswz(rho)) * 8) * 2u;
+    k_off[i] = (uint32_t)(perm_key(rho) * ldkv + (s ^ kswz(rho)) * 8) * 2u + 4096u - 1024u * i;
   }
 #pragma unroll
   for (int i = 0; i < V_INST; ++i) {
     const int d = 8 * (wave * V_INST + i) + (lane >> 3), s = lane & 7;
-    v_off[i] = (uint32_t)(d * (int)p.ldvt + (s ^ vswz(d)) * 8) * 2u;
+    v_off[i] = (uint32_t)(d * (int)p.ldvt + (s ^ vswz(d)) * 8) * 2u + 4096u - 1024u * i;
   }
-  auto lds_load = [](uint32_t dst, uint32_t voff, const void* base) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(dst), "v"(voff), "s"(base) : "memory", "m0");
-  };
-  auto tile_row0 = [&](int it) { return (it < nA ? ta0 + it : tb0 + (it - nA)) * BKV; };
-  auto issue_k = [&](int it) {
-    const int r0 = tile_row0(it), stage = (it - it_begin) & 1;
-    const bf16_t* base = k_base + (int64_t)r0 * ldkv;
-    const bool inside = r0 + BKV - 1 <= p.k_row_max;
-#pragma unroll
-    for (int i = 0; i < K_INST; ++i) {
-      uint32_t off = k_off[i];
-      if (!inside) {
-        const int rho = K_RPI * (wave * K_INST + i) + lane / KCH, s = lane % KCH;
-        off = (uint32_t)(min(perm_key(rho), p.k_row_max - r0) * ldkv + (s ^ kswz(rho)) * 8) * 2u;
-      }
-      lds_load(sK_lds + (uint32_t)(stage * BKV * DH + K_RPI * (wave * K_INST + i) * DH) * 2u, off, base);
+  // LDS destination of a direct load = M0 + instruction offset + 16 * lane, and the instruction offset also
+  // adds to the global address.  The load instructions of a tile write LDS pieces 1024 bytes apart, so they
+  // share one M0 value and differ in the instruction offset (the lane offsets k_off / v_off compensate it on
+  // the global side, biased by 4096 so that they stay non-negative).  M0 is written once per group of
+  // loads: a write to M0 has to wait until earlier direct loads have consumed the old value.
+  auto set_m0 = [](uint32_t dst) { asm volatile("s_mov_b32 m0, %0\n\ts_nop 0" : : "s"(dst) : "memory", "m0"); };
+  auto lds_load = [](uint32_t voff, const void* base, int i) {
+    switch (i) {
+      case 0: asm volatile("global_load_lds_dwordx4 %0, %1" : : "v"(voff), "s"(base) : "memory"); break;
+      case 1: asm volatile("global_load_lds_dwordx4 %0, %1 offset:1024" : : "v"(voff), "s"(base) : "memory"); break;
+      case 2: asm volatile("global_load_lds_dwordx4 %0, %1 offset:2048" : : "v"(voff), "s"(base) : "memory"); break;
+      default: asm volatile("global_load_lds_dwordx4 %0, %1 offset:3072" : : "v"(voff), "s"(base) : "memory"); break;
     }
   };
-  auto issue_v = [&](int it) {
+  auto tile_row0 = [&](int it) { return (it < nA ? ta0 + it : tb0 + (it - nA)) * BKV; };
+  // i-th load instruction of a K tile / a Vt tile; the first one of a tile sets M0
+  static_assert(K_INST <= 4 && V_INST <= 4 && K_RPI * DH * 2 == 1024, "instruction offsets assume 1024-byte pieces");
+  auto issue_k1 = [&](int it, int i) {
     const int r0 = tile_row0(it), stage = (it - it_begin) & 1;
-    const bf16_t* base = vt_base + r0;
+    const char* base = (const char*)(k_base + (int64_t)r0 * ldkv) - 4096;
+    uint32_t off = k_off[i];
+    if (r0 + BKV - 1 > p.k_row_max) {
+      const int rho = K_RPI * (wave * K_INST + i) + lane / KCH, s = lane % KCH;
+      off = (uint32_t)(min(perm_key(rho), p.k_row_max - r0) * ldkv + (s ^ kswz(rho)) * 8) * 2u + 4096u - 1024u * i;
+    }
+    if (i == 0) set_m0(sK_lds + (uint32_t)(stage * BKV * DH + K_RPI * wave * K_INST * DH) * 2u);
+    lds_load(off, base, i);
+  };
+  auto issue_v1 = [&](int it, int i) {
+    const int r0 = tile_row0(it), stage = (it - it_begin) & 1;
+    if (i == 0) set_m0(sV_lds + (uint32_t)(stage * DH * BKV + 8 * wave * V_INST * BKV) * 2u);
+    lds_load(v_off[i], (const char*)(vt_base + r0) - 4096, i);
+  };
+  auto issue_k = [&](int it) {
 #pragma unroll
-    for (int i = 0; i < V_INST; ++i)
-      lds_load(sV_lds + (uint32_t)(stage * DH * BKV + 8 * (wave * V_INST + i) * BKV) * 2u, v_off[i], base);
+    for (int i = 0; i < K_INST; ++i) issue_k1(it, i);
+  };
+  auto issue_v = [&](int it) {
+#pragma unroll
+    for (int i = 0; i < V_INST; ++i) issue_v1(it, i);
+  };
+  // n-th of the K_INST + V_INST loads that follow the barrier of tile `it`: K(it+2), then Vt(it+1)
+  auto issue_next = [&](int it, int n) {
+    if (n < K_INST) {
+      if (it + 2 < it_end) issue_k1(it + 2, n);
+    } else if (n < K_INST + V_INST) {
+      if (it + 1 < it_end) issue_v1(it + 1, n - K_INST);
+    }
   };
   // A wave has nothing to do in tiles that lie wholly beyond the causal limit of all its queries; those are
   // the last tiles of the range, so the wave's active tiles are [it_begin, act_end).
@@ -187,12 +211,14 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
 
   constexpr int NQK = 2 * NKS;   // MFMAs of one score tile
   constexpr int NPV = 4 * NDT;   // MFMAs of one output update
+  // MFMA j of a score tile works on key half j % 2 and head-dim step j / 2, MFMA j of an output update on
+  // d-tile j % NDT and key chunk j / NDT: consecutive MFMAs go to different accumulators
   auto k_frag = [&](const bf16_t* kt_s, int j) {
-    const int kt = j / NKS, ks = j % NKS, row = 32 * kt + lq;
+    const int kt = j % 2, ks = j / 2, row = 32 * kt + lq;
     return *(const bf16x8*)(kt_s + row * DH + (((2 * ks + hh) ^ kswz(row)) * 8));
   };
   auto v_frag = [&](const bf16_t* vt_s, int j) {
-    const int dt = j / 4, kt = (j % 4) / 2, t = j % 2, d = 32 * dt + lq;
+    const int dt = j % NDT, kt = j / NDT / 2, t = (j / NDT) % 2, d = 32 * dt + lq;
     return *(const bf16x8*)(vt_s + d * BKV + (((4 * kt + 2 * t + hh) ^ vswz(d)) * 8));
   };
   // masks the scores of tile `it` where a key is outside this lane's visible range;
@@ -215,11 +241,17 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
     }
   };
   // the lane's query has its 64 scores of a tile in this lane and in lane^32
+  // The exponentials are taken relative to a reference maximum m that follows the true running maximum
+  // lazily: it moves only when the true maximum exceeds it by more than 2^8 in the exponent, so that
+  // probabilities stay below 2^8 and the accumulated sums and outputs rarely need rescaling.  The
+  // normalised result does not depend on the reference.
   auto new_max = [&](float mx) {
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m, mx);
+    const float m_true = fmaxf(m, mx);
+    const bool keep = (m_true - m) * p.c <= 8.0f;  // false for m = -inf (first visible key)
+    const float m_new = keep ? m : m_true;
     const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-    alpha = __builtin_amdgcn_exp2f((m - m_safe) * p.c);
+    alpha = keep ? 1.0f : __builtin_amdgcn_exp2f((m - m_safe) * p.c);
     mc = m_safe * p.c;
     m = m_new;
   };
@@ -253,9 +285,12 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int j = 0; j < NQK; ++j) {
+        // the tile loads that this iteration's barrier released go out one per two MFMAs: a burst of
+        // them would stall the wave on the memory pipeline's issue rate
+        if ((j & 1) == 0) issue_next(it, j >> 1);
         if (HN) {
           if (j + 2 < NQK) kf[j + 2] = k_frag(kt_s, j + 2);
-          const int kt = j / NKS, ks = j % NKS;
+          const int kt = j % 2, ks = j / 2;
           if (ks == 0) {
             const f32x16 z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
             s_n[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j], qf[ks], z, 0, 0, 0);
@@ -293,7 +328,7 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
 #pragma unroll
       for (int j = 0; j < NPV; ++j) {
         if (j + 2 < NPV) vf[j + 2] = v_frag(vt_s, j + 2);
-        const int dt = j / 4, kt = (j % 4) / 2, t = j % 2;
+        const int dt = j % NDT, kt = j / NDT / 2, t = (j / NDT) % 2;
         o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[j], __builtin_bit_cast(bf16x8, pf[kt][t]), o[dt], 0, 0, 0);
         if (HN) {
 #pragma unroll
@@ -310,9 +345,11 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
 
   // Per tile and workgroup one barrier: after it K(it+1) and Vt(it) are complete in LDS and every wave is
   // done with K(it) and Vt(it-1), whose ring stages the loads issued next overwrite.
-  auto sync_and_loads = [&](int it) {
+  auto tile_sync = [&](int it) {
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): as a builtin the compiler accounts for it
     __syncthreads();
+  };
+  auto loads_only = [&](int it) {
     if (it + 2 < it_end) issue_k(it + 2);
     if (it + 1 < it_end) issue_v(it + 1);
   };
@@ -333,7 +370,7 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
       for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks)
-          s_a[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_frag(sK, kt * NKS + ks), qf[ks], s_a[kt], 0, 0, 0);
+          s_a[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_frag(sK, 2 * ks + kt), qf[ks], s_a[kt], 0, 0, 0);
       mask(it_begin, s_a);
       float mx = -INFINITY;
 #pragma unroll
@@ -349,23 +386,26 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
     // active tile (no successor to score); then the tiles this wave only helps to load
     int it = it_begin;
     for (; it + 2 < act_end; it += 2) {
-      sync_and_loads(it);
+      tile_sync(it);
       tile_step(std::true_type{}, it, s_a, s_b);
-      sync_and_loads(it + 1);
+      tile_sync(it + 1);
       tile_step(std::true_type{}, it + 1, s_b, s_a);
     }
     if (it + 1 < act_end) {
-      sync_and_loads(it);
+      tile_sync(it);
       tile_step(std::true_type{}, it, s_a, s_b);
-      sync_and_loads(it + 1);
+      tile_sync(it + 1);
       tile_step(std::false_type{}, it + 1, s_b, s_a);
       it += 2;
     } else if (it < act_end) {
-      sync_and_loads(it);
+      tile_sync(it);
       tile_step(std::false_type{}, it, s_a, s_b);
       it += 1;
     }
-    for (; it < it_end; ++it) sync_and_loads(it);
+    for (; it < it_end; ++it) {
+      tile_sync(it);
+      loads_only(it);
+    }
   }
 
   // ---- store: register 4g+e of d-tile dt is out[q][32dt + 8g + 4*(lane/32) + e] ----
