@@ -157,6 +157,30 @@ def partial_prefill(cfg, weights, hidden_in, lo, hi, kv_reused, positions, cu_se
     return kv_out, h
 
 
+def partial_prefill_groups(cfg, weights, groups, kv_reused, positions, cu_seqlens):
+    """Selective-layer prefill with several recomputed layer groups (Sec. 4.1, "critical
+    layer groups": the layers worth recomputing need not be one contiguous run).
+
+    groups: list of (lo, hi, hidden_in), ascending and disjoint; each group restarts from
+    the sender's E cache at its own transition layer lo, exactly as a single group does,
+    and what a group leaves in the residual stream is discarded.  Layers outside every
+    group keep the sender's KV.  Returns (kv_out, [hidden_out of each group])."""
+    prev_hi = 0
+    for lo, hi, _ in groups:
+        if not (prev_hi <= lo <= hi <= cfg.n_layers):
+            raise ValueError("groups must be ascending, disjoint and inside [0, n_layers]")
+        prev_hi = hi
+    kv_out = [kv_reused[l] for l in range(cfg.n_layers)]
+    hidden_outs = []
+    for lo, hi, hidden_in in groups:
+        h = hidden_in
+        for l in range(lo, hi):
+            h, K, V = prefix_layer(cfg, weights(l), h, positions, cu_seqlens)
+            kv_out[l] = (K, V)
+        hidden_outs.append(h)
+    return kv_out, hidden_outs
+
+
 def suffix_prefill(cfg, weights, suffix_hidden_in, kv, suffix_positions, cu_prefix, cu_suffix):
     """Prefill of the new tokens against the mixed cache, through all layers (Sec. 4.1:
     in a layer whose KV is reused only the new tokens' states flow).

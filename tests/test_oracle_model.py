@@ -142,6 +142,49 @@ def test_composition(setup):
         assert np.array_equal(kv_a[l][0], kv_2[l][0]) and np.array_equal(kv_a[l][1], kv_2[l][1])
 
 
+def test_two_groups_against_library_and_single_calls(setup):
+    # two recomputed groups, each restarted from the same model's own hidden state at its transition
+    # layer: the recomputed layers reproduce the independent implementation's KV, the layer between
+    # them keeps the sender's; and the call equals two single-group calls chained through the cache
+    w, x, T = setup
+    hs, kv_full = hf_prefill(w, x)
+    kv_r = kv_list(synth.kv_cache(SHAPE, T))
+    pos, cu = np.arange(T), np.array([0, T])
+    kv_g, h_g = O.partial_prefill_groups(CFG, w, [(0, 1, hs[0]), (2, 4, hs[2])], kv_r, pos, cu)
+    for l in (0, 2, 3):
+        assert np.allclose(kv_g[l][0], kv_full[l][0], atol=LIB_ATOL)
+        assert np.allclose(kv_g[l][1], kv_full[l][1], atol=LIB_ATOL)
+    assert kv_g[1][0] is kv_r[1][0] and kv_g[1][1] is kv_r[1][1]
+    assert np.allclose(h_g[0], hs[1], atol=LIB_ATOL)
+    kv_1, h_1 = O.partial_prefill(CFG, w, hs[0], 0, 1, kv_r, pos, cu)
+    kv_2, h_2 = O.partial_prefill(CFG, w, hs[2], 2, 4, kv_1, pos, cu)
+    assert np.array_equal(h_g[0], h_1) and np.array_equal(h_g[1], h_2)
+    for l in range(4):
+        assert np.array_equal(kv_g[l][0], kv_2[l][0]) and np.array_equal(kv_g[l][1], kv_2[l][1])
+
+
+def test_groups_do_not_feed_each_other(setup):
+    # a group starts from ITS E cache, not from what the previous group left: changing the first
+    # group's input must not change the second group's layers
+    w, x, T = setup
+    kv_r = kv_list(synth.kv_cache(SHAPE, T))
+    pos, cu = np.arange(T), np.array([0, T])
+    e2 = synth.hidden_states(SHAPE, T, seed=synth.SEED_SUFFIX).astype(np.float64)
+    kv_a, _ = O.partial_prefill_groups(CFG, w, [(0, 2, x), (2, 3, e2)], kv_r, pos, cu)
+    kv_b, _ = O.partial_prefill_groups(CFG, w, [(0, 2, 2.0 * x), (2, 3, e2)], kv_r, pos, cu)
+    assert np.array_equal(kv_a[2][0], kv_b[2][0]) and np.array_equal(kv_a[2][1], kv_b[2][1])
+    assert not np.allclose(kv_a[1][0], kv_b[1][0])
+
+
+def test_bad_groups_rejected(setup):
+    w, x, T = setup
+    kv_r = kv_list(synth.kv_cache(SHAPE, T))
+    pos, cu = np.arange(T), np.array([0, T])
+    for groups in ([(0, 2, x), (1, 3, x)], [(2, 3, x), (0, 1, x)], [(0, 5, x)], [(3, 2, x)]):
+        with pytest.raises(ValueError):
+            O.partial_prefill_groups(CFG, w, groups, kv_r, pos, cu)
+
+
 def test_causality_and_truncation(setup):
     w, x, T = setup
     t = 7
