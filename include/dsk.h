@@ -157,6 +157,26 @@ DSK_API int dsk_partial_prefill(dsk_model_t* model, const void* hidden_in, int h
                         const dsk_kv_t* kv_reused, const dsk_kv_t* kv_out, const dsk_batch_t* batch,
                         void* hidden_out, uint32_t flags, void* stream);
 
+/* One recomputed layer group of dsk_partial_prefill_groups. */
+typedef struct dsk_group_t {
+  int32_t lo, hi;         /* layers lo <= l < hi are recomputed */
+  const void* hidden_in;  /* [n_tokens, d] E cache at layer lo, device or pinned host */
+  int32_t hidden_in_mem;  /* dsk_mem */
+  void* hidden_out;       /* optional device [n_tokens, d]: state leaving layer hi-1 */
+} dsk_group_t;
+
+/* Selective-layer prefill with several recomputed groups (Sec. 4.1: the layers worth recomputing form
+ * "critical layer groups", not necessarily one run).  groups[0..n_groups) must be ascending and disjoint
+ * (groups[g].hi <= groups[g+1].lo), else DSK_EINVAL; every group restarts from its own E cache and what it
+ * leaves in the residual stream is only reported through its hidden_out.  Layers outside all groups are
+ * spliced from kv_reused as in dsk_partial_prefill, whose other rules (aliasing, streams, flags, lifetime
+ * of host buffers) apply unchanged; n_groups = 0 is a pure splice.  Host-resident E caches share one
+ * staging buffer: the first is transferred before any KV, a later one after the KV loads and after the
+ * preceding group's first layer has consumed the buffer.  dsk_partial_prefill is the one-group case. */
+DSK_API int dsk_partial_prefill_groups(dsk_model_t* model, const dsk_group_t* groups, int n_groups,
+                               const dsk_kv_t* kv_reused, const dsk_kv_t* kv_out, const dsk_batch_t* batch,
+                               uint32_t flags, void* stream);
+
 /* Prefill of the new tokens against the mixed cache through all L layers (Sec. 4.1: a layer whose
  * KV is reused only sees the new tokens).  Suffix token j of sequence b attends to prefix rows
  * prefix.cu[b] .. prefix.cu[b+1]-1 and to suffix tokens suffix.cu[b] .. j; its K/V is written to

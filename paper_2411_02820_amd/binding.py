@@ -30,10 +30,16 @@ DSK_LOAD_PIPELINED, DSK_LOAD_REUSED_FIRST, DSK_LOAD_ALL_FIRST = 0, 1, 2
 
 EXPORTS = (
     "dsk_model_create", "dsk_model_destroy", "dsk_model_set_tensor", "dsk_model_get_tensor",
-    "dsk_model_init_random", "dsk_fill_normal", "dsk_partial_prefill", "dsk_suffix_prefill",
+    "dsk_model_init_random", "dsk_fill_normal", "dsk_partial_prefill", "dsk_partial_prefill_groups",
+    "dsk_suffix_prefill",
     "dsk_join_loads", "dsk_set_load_mode", "dsk_model_weight_bytes", "dsk_model_workspace_bytes",
     "dsk_strerror", "dsk_last_hip_error", "dsk_linear", "dsk_attention", "dsk_set_option", "dsk_get_stat",
 )
+
+
+class dsk_group_t(C.Structure):
+    _fields_ = [("lo", C.c_int32), ("hi", C.c_int32), ("hidden_in", C.c_void_p), ("hidden_in_mem", C.c_int32),
+                ("hidden_out", C.c_void_p)]
 
 
 class dsk_config_t(C.Structure):
@@ -62,6 +68,8 @@ lib.dsk_model_init_random.argtypes = [_P, C.c_uint64, C.c_float, _P]
 lib.dsk_fill_normal.argtypes = [_P, C.c_int64, C.c_uint64, C.c_uint64, C.c_float, C.c_float, C.c_int64, C.c_int, _P]
 lib.dsk_partial_prefill.argtypes = [_P, _P, C.c_int, C.c_int, C.c_int, C.POINTER(dsk_kv_t), C.POINTER(dsk_kv_t),
                                     C.POINTER(dsk_batch_t), _P, C.c_uint32, _P]
+lib.dsk_partial_prefill_groups.argtypes = [_P, C.POINTER(dsk_group_t), C.c_int, C.POINTER(dsk_kv_t), C.POINTER(dsk_kv_t),
+                                           C.POINTER(dsk_batch_t), C.c_uint32, _P]
 lib.dsk_suffix_prefill.argtypes = [_P, _P, C.POINTER(dsk_kv_t), C.POINTER(dsk_batch_t), C.POINTER(dsk_batch_t),
                                    C.c_int64, _P, _P]
 lib.dsk_linear.argtypes = [C.c_int, _P, _P, _P, _P, C.c_int, C.c_int, C.c_int, _P]
@@ -152,6 +160,19 @@ def dsk_partial_prefill(model: int, hidden_in, lo: int, hi: int, kv_reused, kv_o
                                    None if kv_reused is None else C.byref(kv_reused), C.byref(kv_out),
                                    C.byref(batch), _ptr(hidden_out), flags, _stream(stream)),
            "dsk_partial_prefill")
+
+
+def dsk_partial_prefill_groups(model: int, groups, kv_reused, kv_out: dsk_kv_t, batch: dsk_batch_t, flags: int = 0,
+                               stream=None):
+    """groups: sequence of (lo, hi, hidden_in, hidden_out or None)."""
+    arr = (dsk_group_t * max(1, len(groups)))()
+    for i, (lo, hi, hidden_in, hidden_out) in enumerate(groups):
+        arr[i].lo, arr[i].hi = lo, hi
+        arr[i].hidden_in, arr[i].hidden_in_mem = _ptr(hidden_in), _mem_of(hidden_in)
+        arr[i].hidden_out = _ptr(hidden_out)
+    _check(lib.dsk_partial_prefill_groups(model, arr, len(groups), None if kv_reused is None else C.byref(kv_reused),
+                                          C.byref(kv_out), C.byref(batch), flags, _stream(stream)),
+           "dsk_partial_prefill_groups")
 
 
 def dsk_suffix_prefill(model: int, suffix_hidden_in, kv: dsk_kv_t, prefix: dsk_batch_t, suffix: dsk_batch_t,

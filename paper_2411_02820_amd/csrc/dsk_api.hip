@@ -53,6 +53,7 @@ void free_model(dsk_model* m) {
   }
   if (m->ev_entry) (void)hipEventDestroy(m->ev_entry);
   if (m->ev_e) (void)hipEventDestroy(m->ev_e);
+  if (m->ev_stage_free) (void)hipEventDestroy(m->ev_stage_free);
   if (m->ev_all) (void)hipEventDestroy(m->ev_all);
   if (m->load_stream) (void)hipStreamDestroy(m->load_stream);
   free(m->pending);
@@ -299,6 +300,7 @@ int dsk_model_create(const dsk_config_t* cfg, int64_t max_tokens, int64_t max_kv
     hip_ok(hipStreamCreateWithFlags(&m->load_stream, hipStreamNonBlocking));
     hip_ok(hipEventCreateWithFlags(&m->ev_entry, hipEventDisableTiming));
     hip_ok(hipEventCreateWithFlags(&m->ev_e, hipEventDisableTiming));
+    hip_ok(hipEventCreateWithFlags(&m->ev_stage_free, hipEventDisableTiming));
     hip_ok(hipEventCreateWithFlags(&m->ev_all, hipEventDisableTiming));
     for (int l = 0; l < L; ++l) hip_ok(hipEventCreateWithFlags(&m->ev_kv[l], hipEventDisableTiming));
   }
@@ -374,23 +376,30 @@ int dsk_fill_normal(void* dst_device, int64_t n, uint64_t seed, uint64_t stream_
   return DSK_OK;
 }
 
-int dsk_partial_prefill(dsk_model_t* model, const void* hidden_in, int hidden_in_mem, int lo, int hi,
-                        const dsk_kv_t* kv_reused, const dsk_kv_t* kv_out, const dsk_batch_t* batch,
-                        void* hidden_out, uint32_t flags, void* stream) {
-  if (!model || !hidden_in || !kv_out || !batch) return DSK_EINVAL;
+int dsk_partial_prefill_groups(dsk_model_t* model, const dsk_group_t* groups, int n_groups,
+                               const dsk_kv_t* kv_reused, const dsk_kv_t* kv_out, const dsk_batch_t* batch,
+                               uint32_t flags, void* stream) {
+  if (!model || !kv_out || !batch || n_groups < 0 || (n_groups > 0 && !groups)) return DSK_EINVAL;
   dsk_model* m = model;
   const dsk_config_t& c = m->cfg;
   const int L = c.n_layers;
-  if (!(0 <= lo && lo <= hi && hi <= L)) return DSK_EINVAL;
-  if (hidden_in_mem != DSK_MEM_DEVICE && hidden_in_mem != DSK_MEM_HOST_PINNED) return DSK_EINVAL;
-  if (!aligned16(hidden_in) || !aligned16(hidden_out)) return DSK_EINVAL;
+  int n_recomputed = 0;
+  for (int g = 0, prev_hi = 0; g < n_groups; ++g) {
+    const dsk_group_t& G = groups[g];
+    if (!(prev_hi <= G.lo && G.lo <= G.hi && G.hi <= L)) return DSK_EINVAL;  // ascending, disjoint
+    if (!G.hidden_in) return DSK_EINVAL;
+    if (G.hidden_in_mem != DSK_MEM_DEVICE && G.hidden_in_mem != DSK_MEM_HOST_PINNED) return DSK_EINVAL;
+    if (!aligned16(G.hidden_in) || !aligned16(G.hidden_out)) return DSK_EINVAL;
+    prev_hi = G.hi;
+    n_recomputed += G.hi - G.lo;
+  }
   if (flags & ~DSK_DEFER_JOIN) return DSK_EINVAL;
   int rc = check_batch(batch, true);
   if (rc) return rc;
   const int T = batch->n_tokens;
   if (T > m->max_tokens || T > m->max_kv_rows) return DSK_EINVAL;
   if ((rc = check_kv(m, kv_out, T, true))) return rc;
-  const bool need_reused = (hi - lo) < L;
+  const bool need_reused = n_recomputed < L;
   if (need_reused || kv_reused)
     if ((rc = check_kv(m, kv_reused, T, false))) return rc;
 
@@ -402,26 +411,31 @@ int dsk_partial_prefill(dsk_model_t* model, const void* hidden_in, int hidden_in
                      kv_reused->layer_stride == kv_out->layer_stride && kv_reused->v_offset == kv_out->v_offset;
   const hipMemcpyKind kv_kind = (kv_reused && kv_reused->mem == DSK_MEM_HOST_PINNED) ? hipMemcpyHostToDevice : hipMemcpyDeviceToDevice;
   const int mode = m->load_mode;
+  auto recomputed = [&](int l) {
+    for (int g = 0; g < n_groups; ++g)
+      if (l >= groups[g].lo && l < groups[g].hi) return true;
+    return false;
+  };
 
   // loads start after everything the caller already enqueued on `stream`
   HIP_TRY(hipEventRecord(m->ev_entry, s));
   HIP_TRY(hipStreamWaitEvent(ls, m->ev_entry, 0));
 
-  // the E cache goes first (Fig. 13(c)): recomputation can start as soon as it has arrived
-  const void* h_cur = hidden_in;
-  if (hidden_in_mem == DSK_MEM_HOST_PINNED) {
-    HIP_TRY(hipMemcpyAsync(m->e_stage, hidden_in, (size_t)hid_bytes, hipMemcpyHostToDevice, ls));
+  // The first group's E cache goes first (Fig. 13(c)): recomputation can start as soon as it has arrived.
+  // A host-resident E cache passes through the model's one staging buffer.
+  auto stage_e = [&](const dsk_group_t& G) -> int {
+    HIP_TRY(hipMemcpyAsync(m->e_stage, G.hidden_in, (size_t)hid_bytes, hipMemcpyHostToDevice, ls));
     HIP_TRY(hipEventRecord(m->ev_e, ls));
-    HIP_TRY(hipStreamWaitEvent(s, m->ev_e, 0));
-    h_cur = m->e_stage;
-  }
+    return DSK_OK;
+  };
+  if (n_groups > 0 && groups[0].hidden_in_mem == DSK_MEM_HOST_PINNED)
+    if ((rc = stage_e(groups[0]))) return rc;
 
   // reused layers, ascending (the order the suffix prefill consumes them), one event per layer
   memset(m->pending, 0, L);
   m->any_pending = 0;
   for (int l = 0; l < L; ++l) {
-    const bool recomputed = (l >= lo && l < hi);
-    if (recomputed && mode != DSK_LOAD_ALL_FIRST) continue;
+    if (recomputed(l) && mode != DSK_LOAD_ALL_FIRST) continue;
     if (!kv_reused || alias) continue;
     const int64_t bytes = (int64_t)T * row_bytes;
     const bool one_piece = kv_reused->v_offset == bytes && kv_out->v_offset == bytes;
@@ -438,19 +452,42 @@ int dsk_partial_prefill(dsk_model_t* model, const void* hidden_in, int hidden_in
   HIP_TRY(hipEventRecord(m->ev_all, ls));
   if (mode != DSK_LOAD_PIPELINED) HIP_TRY(hipStreamWaitEvent(s, m->ev_all, 0));  // strategies (a), (b): load, then compute
 
-  // recompute [lo, hi) on the compute stream
-  if (hi > lo) {
-    HIP_TRY(launch_rope_table(batch->positions_dev, m->theta, m->rope_cs, T, c.head_dim / 2, s));
-    for (int l = lo; l < hi; ++l) {
-      const bool last = l == hi - 1 && hidden_out;
-      void* h_next = last ? hidden_out : (void*)m->h;
-      rc = run_layer(m, l, h_cur, l > lo, h_next, !last, kv_k(kv_out, l), kv_v(kv_out, l), 0, batch->cu_seqlens_dev,
-                     batch->cu_seqlens_host, nullptr, nullptr, 0, batch->n_seqs, T, s);
-      if (rc) return rc;
-      h_cur = h_next;
+  // recompute the groups on the compute stream, each from its own E cache
+  bool table_done = false;
+  for (int g = 0; g < n_groups; ++g) {
+    const dsk_group_t& G = groups[g];
+    const void* h_cur = G.hidden_in;
+    if (G.hidden_in_mem == DSK_MEM_HOST_PINNED) {
+      HIP_TRY(hipStreamWaitEvent(s, m->ev_e, 0));  // this group's copy into the staging buffer (recorded above / below)
+      h_cur = m->e_stage;
     }
-  } else if (hidden_out && hidden_out != h_cur) {
-    HIP_TRY(hipMemcpyAsync(hidden_out, h_cur, (size_t)hid_bytes, hipMemcpyDeviceToDevice, s));
+    // the next host-resident E cache may enter the staging buffer once this group's first layer has read
+    // it; its copy queues behind the layer loads, which the suffix prefill needs first
+    const bool next_host = g + 1 < n_groups && groups[g + 1].hidden_in_mem == DSK_MEM_HOST_PINNED;
+    auto hand_over_stage = [&]() -> int {
+      HIP_TRY(hipEventRecord(m->ev_stage_free, s));
+      HIP_TRY(hipStreamWaitEvent(ls, m->ev_stage_free, 0));
+      return stage_e(groups[g + 1]);
+    };
+    if (G.hi > G.lo) {
+      if (!table_done) {
+        HIP_TRY(launch_rope_table(batch->positions_dev, m->theta, m->rope_cs, T, c.head_dim / 2, s));
+        table_done = true;
+      }
+      for (int l = G.lo; l < G.hi; ++l) {
+        const bool last = l == G.hi - 1 && G.hidden_out;
+        void* h_next = last ? G.hidden_out : (void*)m->h;
+        rc = run_layer(m, l, h_cur, l > G.lo, h_next, !last, kv_k(kv_out, l), kv_v(kv_out, l), 0, batch->cu_seqlens_dev,
+                       batch->cu_seqlens_host, nullptr, nullptr, 0, batch->n_seqs, T, s);
+        if (rc) return rc;
+        h_cur = h_next;
+        if (l == G.lo && next_host && (rc = hand_over_stage())) return rc;
+      }
+    } else {
+      if (G.hidden_out && G.hidden_out != h_cur)
+        HIP_TRY(hipMemcpyAsync(G.hidden_out, h_cur, (size_t)hid_bytes, hipMemcpyDeviceToDevice, s));
+      if (next_host && (rc = hand_over_stage())) return rc;
+    }
   }
 
   if (!(flags & DSK_DEFER_JOIN) || mode != DSK_LOAD_PIPELINED) {
@@ -459,6 +496,15 @@ int dsk_partial_prefill(dsk_model_t* model, const void* hidden_in, int hidden_in
     m->any_pending = 0;
   }
   return DSK_OK;
+}
+
+int dsk_partial_prefill(dsk_model_t* model, const void* hidden_in, int hidden_in_mem, int lo, int hi,
+                        const dsk_kv_t* kv_reused, const dsk_kv_t* kv_out, const dsk_batch_t* batch,
+                        void* hidden_out, uint32_t flags, void* stream) {
+  if (!hidden_in) return DSK_EINVAL;
+  dsk_group_t g;
+  g.lo = lo; g.hi = hi; g.hidden_in = hidden_in; g.hidden_in_mem = hidden_in_mem; g.hidden_out = hidden_out;
+  return dsk_partial_prefill_groups(model, &g, 1, kv_reused, kv_out, batch, flags, stream);
 }
 
 int dsk_suffix_prefill(dsk_model_t* model, const void* suffix_hidden_in, const dsk_kv_t* kv,

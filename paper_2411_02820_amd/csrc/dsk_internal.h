@@ -56,7 +56,7 @@ struct dsk_model {
   int64_t workspace_bytes;
   // load pipeline
   hipStream_t load_stream;
-  hipEvent_t ev_entry, ev_e, ev_all;
+  hipEvent_t ev_entry, ev_e, ev_all, ev_stage_free;
   hipEvent_t* ev_kv;        // [L]
   unsigned char* pending;   // [L] 1 if ev_kv[l] must be waited for by the suffix
   int any_pending;

@@ -85,6 +85,20 @@ class GpuModel:
         self._keep = (batch, hidden_in, kv_reused)
         return kv_out, hidden_out
 
+    def partial_groups(self, groups, kv_reused, lens, kv_out=None, flags=0, stream=None):
+        """groups: list of (lo, hi, hidden_in tensor).  Returns (kv_out, [hidden_out per group])."""
+        cu = synth.cu_seqlens(lens)
+        T = int(cu[-1])
+        batch = B.Batch(cu, synth.packed_positions(lens))
+        if kv_out is None:
+            kv_out = self.new_cache(T, fill=float("nan"))
+        outs = [torch.empty((T, self.shape.hidden), dtype=torch_dtype(self.shape), device="cuda") for _ in groups]
+        B.dsk_partial_prefill_groups(self.handle, [(lo, hi, h, o) for (lo, hi, h), o in zip(groups, outs)],
+                                     None if kv_reused is None else B.kv_desc(kv_reused), B.kv_desc(kv_out),
+                                     batch.desc, flags, stream)
+        self._keep = (batch, groups, kv_reused)
+        return kv_out, outs
+
     def suffix(self, suffix_hidden_in, kv, lens, slens, suffix_row0=None, stream=None):
         cu, cus = synth.cu_seqlens(lens), synth.cu_seqlens(slens)
         spos = synth.packed_positions(slens, start=lens)

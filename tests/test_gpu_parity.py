@@ -162,6 +162,69 @@ def test_composition_and_determinism_on_device(G):
                 assert O.max_rel_err(G.to_np(kv_2), G.to_np(kv_a)) <= tol
 
 
+def test_recompute_groups_against_oracle_and_single_calls(G):
+    # two recomputed groups, each from its own E cache (Sec. 4.1 "critical layer groups"): against the oracle,
+    # bit-identical to two single-group calls chained through the cache, with device and pinned-host sources
+    for shape, scale, lens in ((synth.TINY, 8.0, [70, 33]), (SMALL_BF16, 2.0, [150, 43])):
+        tol = TOL[shape.dtype]
+        cfg = oracle_config(shape)
+        cu = synth.cu_seqlens(lens)
+        T = int(cu[-1])
+        pos = synth.packed_positions(lens)
+        L = shape.n_layers
+        spans = [(0, 1), (2, L)] if L > 3 else [(0, 1), (2, 3)]
+        e_np = [synth.hidden_states(shape, T), synth.hidden_states(shape, T, seed=synth.SEED_SUFFIX)]
+        kv_r = synth.kv_cache(shape, T)
+        w = scaled_weights(shape, synth.SEED_RECEIVER, scale)
+        kv_ref, h_ref = O.partial_prefill_groups(
+            cfg, w, [(lo, hi, e.astype(np.float64)) for (lo, hi), e in zip(spans, e_np)], kv_list(kv_r), pos, cu)
+        with G.GpuModel(shape, T) as m:
+            m.load_from_generator(synth.SEED_RECEIVER, scale=scale)
+            results = []
+            for pinned in (False, True):
+                e_dev = [G.to_dev(e, shape, pinned=pinned) for e in e_np]
+                kv_out, outs = m.partial_groups([(lo, hi, e) for (lo, hi), e in zip(spans, e_dev)],
+                                                G.to_dev(kv_r, shape, pinned=pinned), lens)
+                torch.cuda.synchronize()
+                results.append((kv_out, outs))
+            kv_out, outs = results[0]
+            kv_gpu = G.to_np(kv_out)
+            recomputed = {l for lo, hi in spans for l in range(lo, hi)}
+            for l in range(L):
+                if l in recomputed:
+                    assert O.max_rel_err(kv_gpu[l, 0], kv_ref[l][0]) <= tol, f"K layer {l}"
+                    assert O.max_rel_err(kv_gpu[l, 1], kv_ref[l][1]) <= tol, f"V layer {l}"
+                else:
+                    assert np.array_equal(kv_gpu[l], kv_r[l]), f"splice layer {l}"
+            for g in range(2):
+                assert O.max_rel_err(G.to_np(outs[g]), h_ref[g]) <= tol, f"hidden_out of group {g}"
+            # host-resident sources (both E caches pass through the one staging buffer): same bits
+            assert torch.equal(results[1][0], kv_out)
+            assert all(torch.equal(a, b) for a, b in zip(results[1][1], outs))
+            # chained single-group calls: same bits
+            e_dev = [G.to_dev(e, shape) for e in e_np]
+            kv_1, h_1 = m.partial(e_dev[0], spans[0][0], spans[0][1], G.to_dev(kv_r, shape), lens)
+            kv_2, h_2 = m.partial(e_dev[1], spans[1][0], spans[1][1], kv_1, lens)
+            torch.cuda.synchronize()
+            assert torch.equal(kv_2, kv_out) and torch.equal(h_1, outs[0]) and torch.equal(h_2, outs[1])
+
+
+def test_recompute_groups_argument_errors(G):
+    from paper_2411_02820_amd import binding as B
+    shape = synth.TINY
+    T = 8
+    with G.GpuModel(shape, T) as m:
+        h = G.to_dev(synth.hidden_states(shape, T), shape)
+        kv = G.to_dev(synth.kv_cache(shape, T), shape)
+        for spans in ([(0, 2), (1, 3)], [(2, 3), (0, 1)], [(0, 5)], [(3, 2)]):
+            with pytest.raises(B.DskError) as e:
+                m.partial_groups([(lo, hi, h) for lo, hi in spans], kv, [T])
+            assert e.value.status == B.DSK_EINVAL
+        kv_out, _ = m.partial_groups([], kv, [T])      # no group: pure splice
+        torch.cuda.synchronize()
+        assert torch.equal(kv_out, kv)
+
+
 def test_load_strategies_give_identical_results(G):
     from paper_2411_02820_amd import binding as B
     shape = synth.TINY
