@@ -194,6 +194,12 @@ DSK_API int dsk_join_loads(dsk_model_t* model, void* stream);
 /* Selects the loading strategy used by later dsk_partial_prefill calls (default pipelined). */
 DSK_API int dsk_set_load_mode(dsk_model_t* model, int load_mode);
 
+/* Paces later loads (E caches and reused layers) to at most gb_per_s GB/s by idling the load stream after
+ * every 1 MiB chunk until that chunk would have arrived over such a link; 0 switches pacing off.  It
+ * emulates a slower link between the cache's home and the GPU for the loading-strategy and bandwidth
+ * experiments (Sec. 4.3 Fig. 13; Sec. 5.5 Fig. 20); results are unchanged. */
+DSK_API int dsk_set_load_throttle(dsk_model_t* model, double gb_per_s);
+
 /* ---- component entry points: single steps of the layer, for parity tests and micro-benchmarks ---- */
 
 /* y[M,N] = x[M,K] * w[N,K]^T (+ r[M,N] if r != NULL); all device, row-major, dense rows, dtype as given.

@@ -32,7 +32,7 @@ EXPORTS = (
     "dsk_model_create", "dsk_model_destroy", "dsk_model_set_tensor", "dsk_model_get_tensor",
     "dsk_model_init_random", "dsk_fill_normal", "dsk_partial_prefill", "dsk_partial_prefill_groups",
     "dsk_suffix_prefill",
-    "dsk_join_loads", "dsk_set_load_mode", "dsk_model_weight_bytes", "dsk_model_workspace_bytes",
+    "dsk_join_loads", "dsk_set_load_mode", "dsk_set_load_throttle", "dsk_model_weight_bytes", "dsk_model_workspace_bytes",
     "dsk_strerror", "dsk_last_hip_error", "dsk_linear", "dsk_attention", "dsk_set_option", "dsk_get_stat",
 )
 
@@ -79,6 +79,7 @@ lib.dsk_set_option.argtypes = [C.c_char_p, C.c_int]
 lib.dsk_get_stat.argtypes = [C.c_char_p, C.POINTER(C.c_double)]
 lib.dsk_join_loads.argtypes = [_P, _P]
 lib.dsk_set_load_mode.argtypes = [_P, C.c_int]
+lib.dsk_set_load_throttle.argtypes = [_P, C.c_double]
 lib.dsk_model_weight_bytes.argtypes = [_P]
 lib.dsk_model_weight_bytes.restype = C.c_int64
 lib.dsk_model_workspace_bytes.argtypes = [_P]
@@ -209,6 +210,10 @@ def dsk_join_loads(model: int, stream=None):
 
 def dsk_set_load_mode(model: int, mode: int):
     _check(lib.dsk_set_load_mode(model, mode), "dsk_set_load_mode")
+
+
+def dsk_set_load_throttle(model: int, gb_per_s: float):
+    _check(lib.dsk_set_load_throttle(model, gb_per_s), "dsk_set_load_throttle")
 
 
 def dsk_model_weight_bytes(model: int) -> int:

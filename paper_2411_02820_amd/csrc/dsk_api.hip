@@ -45,7 +45,7 @@ void free_model(dsk_model* m) {
     free(m->layers);
   }
   (void)hipFree(m->xn); (void)hipFree(m->qkv); (void)hipFree(m->attn); (void)hipFree(m->gu);
-  (void)hipFree(m->act); (void)hipFree(m->h); (void)hipFree(m->e_stage); (void)hipFree(m->rope_cs); (void)hipFree(m->theta); (void)hipFree(m->vt); (void)hipFree(m->gemm_ws); (void)hipFree(m->attn_ws);
+  (void)hipFree(m->act); (void)hipFree(m->h); (void)hipFree(m->e_stage); (void)hipFree(m->pace_t0); (void)hipFree(m->rope_cs); (void)hipFree(m->theta); (void)hipFree(m->vt); (void)hipFree(m->gemm_ws); (void)hipFree(m->attn_ws);
   if (m->ev_kv) {
     for (int l = 0; l < m->cfg.n_layers; ++l)
       if (m->ev_kv[l]) (void)hipEventDestroy(m->ev_kv[l]);
@@ -268,6 +268,7 @@ int dsk_model_create(const dsk_config_t* cfg, int64_t max_tokens, int64_t max_kv
   if (rc == DSK_OK) rc = alloc_dev(&m->act, T * F * elem, &m->workspace_bytes);
   if (rc == DSK_OK) rc = alloc_dev((void**)&m->h, T * d * 4, &m->workspace_bytes);
   if (rc == DSK_OK) rc = alloc_dev(&m->e_stage, T * d * elem, &m->workspace_bytes);
+  if (rc == DSK_OK) rc = alloc_dev((void**)&m->pace_t0, 8, &m->workspace_bytes);
   if (rc == DSK_OK) rc = alloc_dev((void**)&m->rope_cs, T * half * (int64_t)sizeof(float2), &m->workspace_bytes);
   if (rc == DSK_OK) rc = alloc_dev((void**)&m->theta, half * (int64_t)sizeof(double), &m->workspace_bytes);
   const int64_t kvw = (int64_t)cfg->n_kv_heads * cfg->head_dim;
@@ -376,6 +377,25 @@ int dsk_fill_normal(void* dst_device, int64_t n, uint64_t seed, uint64_t stream_
   return DSK_OK;
 }
 
+// One transfer on the load stream.  With a throttle set it goes in chunks, each followed by a wait until the
+// time the bytes sent so far would have needed on a link of that rate.
+static int load_copy(dsk_model* m, void* dst, const void* src, int64_t bytes, hipMemcpyKind kind) {
+  hipStream_t ls = m->load_stream;
+  if (m->throttle_gbps <= 0.0) {
+    HIP_TRY(hipMemcpyAsync(dst, src, (size_t)bytes, kind, ls));
+    return DSK_OK;
+  }
+  const int64_t chunk = (int64_t)1 << 20;
+  for (int64_t off = 0; off < bytes; off += chunk) {
+    const int64_t n = bytes - off < chunk ? bytes - off : chunk;
+    HIP_TRY(hipMemcpyAsync((char*)dst + off, (const char*)src + off, (size_t)n, kind, ls));
+    m->paced_bytes += n;
+    const double ticks = (double)m->paced_bytes / (m->throttle_gbps * 1e9) * 1e8;  // 100 MHz clock
+    HIP_TRY(launch_pace_wait(m->pace_t0, (unsigned long long)ticks, ls));
+  }
+  return DSK_OK;
+}
+
 int dsk_partial_prefill_groups(dsk_model_t* model, const dsk_group_t* groups, int n_groups,
                                const dsk_kv_t* kv_reused, const dsk_kv_t* kv_out, const dsk_batch_t* batch,
                                uint32_t flags, void* stream) {
@@ -420,11 +440,16 @@ int dsk_partial_prefill_groups(dsk_model_t* model, const dsk_group_t* groups, in
   // loads start after everything the caller already enqueued on `stream`
   HIP_TRY(hipEventRecord(m->ev_entry, s));
   HIP_TRY(hipStreamWaitEvent(ls, m->ev_entry, 0));
+  if (m->throttle_gbps > 0.0) {
+    m->paced_bytes = 0;
+    HIP_TRY(launch_pace_start(m->pace_t0, ls));
+  }
 
   // The first group's E cache goes first (Fig. 13(c)): recomputation can start as soon as it has arrived.
   // A host-resident E cache passes through the model's one staging buffer.
   auto stage_e = [&](const dsk_group_t& G) -> int {
-    HIP_TRY(hipMemcpyAsync(m->e_stage, G.hidden_in, (size_t)hid_bytes, hipMemcpyHostToDevice, ls));
+    int r = load_copy(m, m->e_stage, G.hidden_in, hid_bytes, hipMemcpyHostToDevice);
+    if (r) return r;
     HIP_TRY(hipEventRecord(m->ev_e, ls));
     return DSK_OK;
   };
@@ -440,10 +465,10 @@ int dsk_partial_prefill_groups(dsk_model_t* model, const dsk_group_t* groups, in
     const int64_t bytes = (int64_t)T * row_bytes;
     const bool one_piece = kv_reused->v_offset == bytes && kv_out->v_offset == bytes;
     if (one_piece) {
-      HIP_TRY(hipMemcpyAsync(kv_k(kv_out, l), kv_k(kv_reused, l), (size_t)(2 * bytes), kv_kind, ls));
+      if ((rc = load_copy(m, kv_k(kv_out, l), kv_k(kv_reused, l), 2 * bytes, kv_kind))) return rc;
     } else {
-      HIP_TRY(hipMemcpyAsync(kv_k(kv_out, l), kv_k(kv_reused, l), (size_t)bytes, kv_kind, ls));
-      HIP_TRY(hipMemcpyAsync(kv_v(kv_out, l), kv_v(kv_reused, l), (size_t)bytes, kv_kind, ls));
+      if ((rc = load_copy(m, kv_k(kv_out, l), kv_k(kv_reused, l), bytes, kv_kind))) return rc;
+      if ((rc = load_copy(m, kv_v(kv_out, l), kv_v(kv_reused, l), bytes, kv_kind))) return rc;
     }
     HIP_TRY(hipEventRecord(m->ev_kv[l], ls));
     m->pending[l] = 1;
@@ -550,6 +575,12 @@ int dsk_join_loads(dsk_model_t* model, void* stream) {
     memset(model->pending, 0, model->cfg.n_layers);
     model->any_pending = 0;
   }
+  return DSK_OK;
+}
+
+int dsk_set_load_throttle(dsk_model_t* model, double gb_per_s) {
+  if (!model || !(gb_per_s >= 0.0)) return DSK_EINVAL;
+  model->throttle_gbps = gb_per_s;
   return DSK_OK;
 }
 

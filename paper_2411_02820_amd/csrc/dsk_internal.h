@@ -61,6 +61,9 @@ struct dsk_model {
   unsigned char* pending;   // [L] 1 if ev_kv[l] must be waited for by the suffix
   int any_pending;
   int load_mode;
+  double throttle_gbps;        // > 0: loads are paced to this rate (emulates a slower link); 0 = off
+  unsigned long long* pace_t0; // device: start time of the current call's loads (constant-rate clock ticks)
+  int64_t paced_bytes;         // bytes handed to the load stream since pace_t0 was taken
 };
 
 // epilogues of the GEMM family
@@ -82,6 +85,9 @@ bool gemm_mfma_swiglu_supported(int M, int N, int K);
 
 // x is fp32 when x_f32 is set, else the model dtype; g and y are the model dtype
 hipError_t launch_rmsnorm(int dtype, const void* x, int x_f32, const void* g, void* y, int T, int d, float eps, hipStream_t s);
+// pacing of the load stream against the 100 MHz constant-rate clock
+hipError_t launch_pace_start(unsigned long long* t0, hipStream_t s);
+hipError_t launch_pace_wait(const unsigned long long* t0, unsigned long long ticks, hipStream_t s);
 hipError_t launch_rope_table(const int32_t* pos, const double* theta, float2* cs, int T, int half, hipStream_t s);
 // rotates q (in place) and k of qkv [T, n_qkv]; writes rotated k and v to the cache rows row0..row0+T-1
 hipError_t launch_rope_kv_write(int dtype, void* qkv, const float2* cs, void* k_rows, void* v_rows, int T, int Hq,

@@ -133,7 +133,29 @@ __global__ void swiglu_kernel(const T* __restrict__ gu, T* __restrict__ act, int
   }
 }
 
+// Link emulation for the loading-strategy experiments: the load stream notes when a call's loads begin and,
+// after each chunk, idles until the moment that chunk would have arrived over a link of the chosen rate.
+// Time is the constant-rate (100 MHz) counter; the wait ends at its deadline, or after kPaceCap ticks at
+// the latest, so the wave always retires.
+constexpr unsigned long long kPaceCap = 500000000ull;  // 5 s
+__global__ void pace_start_kernel(unsigned long long* t0) { *t0 = __builtin_amdgcn_s_memrealtime(); }
+__global__ void pace_wait_kernel(const unsigned long long* t0, unsigned long long ticks) {
+  const unsigned long long start = *t0;
+  if (ticks > kPaceCap) ticks = kPaceCap;
+  while (__builtin_amdgcn_s_memrealtime() - start < ticks) __builtin_amdgcn_s_sleep(32);
+}
+
 }  // namespace
+
+hipError_t launch_pace_start(unsigned long long* t0, hipStream_t s) {
+  hipLaunchKernelGGL(pace_start_kernel, dim3(1), dim3(1), 0, s, t0);
+  return hipGetLastError();
+}
+
+hipError_t launch_pace_wait(const unsigned long long* t0, unsigned long long ticks, hipStream_t s) {
+  hipLaunchKernelGGL(pace_wait_kernel, dim3(1), dim3(1), 0, s, t0, ticks);
+  return hipGetLastError();
+}
 
 hipError_t launch_rmsnorm(int dtype, const void* x, int x_f32, const void* g, void* y, int T, int d, float eps, hipStream_t s) {
   if (T <= 0) return hipSuccess;

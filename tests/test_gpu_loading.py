@@ -1,0 +1,71 @@
+"""The three KV-loading strategies (Sec. 4.3, Fig. 13) on the GPU, over an emulated slow link: results stay
+bit-identical, and the measured delay of each strategy follows the unit-cost schedule model that reproduces the
+figure's totals, fed with the per-layer transfer and recompute times measured on the same box."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import schedule_model as SM
+from paper_2411_02820_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+# E cache and one layer's KV have the same size (T*d = 2*T*Hkv*dh), as in the figure's unit-cost setting
+SHAPE = synth.ModelShape(8, 512, 4, 2, 128, 1536, 10000.0, 1e-5, "bf16")
+T = 2048
+LO, HI = 2, 6
+LINK_GBPS = 2.0
+
+
+def timed(fn, reps=3):
+    best = float("inf")
+    for _ in range(reps):
+        s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        s.record()
+        fn()
+        e.record()
+        torch.cuda.synchronize()
+        best = min(best, s.elapsed_time(e))
+    return best
+
+
+def test_strategies_over_a_slow_link_follow_the_schedule_model():
+    from paper_2411_02820_amd import binding as B
+    from tests import gpu_util as G
+    hidden_pinned = G.to_dev(synth.hidden_states(SHAPE, T), SHAPE, pinned=True)
+    hidden_dev = G.to_dev(synth.hidden_states(SHAPE, T), SHAPE)
+    kv_pinned = G.to_dev(synth.kv_cache(SHAPE, T), SHAPE, pinned=True)
+    kv_dev = G.to_dev(synth.kv_cache(SHAPE, T), SHAPE)
+    layer_bytes = 2 * T * SHAPE.kv_width * 2
+    assert layer_bytes == T * SHAPE.hidden * 2
+    with G.GpuModel(SHAPE, T) as m:
+        m.load_from_generator(0, scale=2.0)
+        kv_out = m.new_cache(T, fill=0.0)
+        # per-layer recompute time: everything device-resident and aliased, so nothing is loaded
+        for _ in range(2):
+            m.partial(hidden_dev, LO, HI, kv_dev, [T], kv_out=kv_dev)
+        t_compute = timed(lambda: m.partial(hidden_dev, LO, HI, kv_dev, [T], kv_out=kv_dev)) / (HI - LO)
+        # per-layer transfer time over the emulated link: a pure splice of all layers from host memory
+        B.dsk_set_load_throttle(m.handle, LINK_GBPS)
+        t_load = timed(lambda: m.partial(hidden_dev, 0, 0, kv_pinned, [T], kv_out=kv_out)) / SHAPE.n_layers
+        assert t_load == pytest.approx(layer_bytes / (LINK_GBPS * 1e9) * 1e3, rel=0.15), "pacing misses the chosen rate"
+
+        job = [SM.Job(0.0, SHAPE.n_layers, HI - LO, True)]
+        measured, outs = {}, {}
+        for name, mode in (("all_then_compute", B.DSK_LOAD_ALL_FIRST), ("reused_then_compute", B.DSK_LOAD_REUSED_FIRST),
+                           ("pipelined", B.DSK_LOAD_PIPELINED)):
+            B.dsk_set_load_mode(m.handle, mode)
+            res = []
+            measured[name] = timed(lambda: res.append(m.partial(hidden_pinned, LO, HI, kv_pinned, [T], kv_out=kv_out)))
+            outs[name] = (res[-1][0].clone(), res[-1][1].clone())
+            model = SM.total_ttft(job, name, unit_load=t_load, unit_compute=t_compute)
+            assert measured[name] == pytest.approx(model, rel=0.2), f"{name}: measured {measured[name]:.3f} ms, model {model:.3f} ms"
+        B.dsk_set_load_throttle(m.handle, 0.0)
+        B.dsk_set_load_mode(m.handle, B.DSK_LOAD_PIPELINED)
+        assert measured["pipelined"] < measured["reused_then_compute"] < measured["all_then_compute"]
+        # the link does not change a single bit, whatever the strategy
+        ref_kv, ref_h = m.partial(hidden_pinned, LO, HI, kv_pinned, [T])
+        torch.cuda.synchronize()
+        for name in outs:
+            assert torch.equal(outs[name][0], ref_kv) and torch.equal(outs[name][1], ref_h), name
