@@ -97,6 +97,8 @@ def main():
     ap.add_argument("--workload", default="8b-8k", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full-prefill", action="store_true")
+    ap.add_argument("--load-sweep", action="store_true",
+                    help="host-KV workloads: time the three loading strategies over emulated links of several rates")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy, the known-size kernel that scales FETCH_SIZE/WRITE_SIZE")
     args = ap.parse_args()
@@ -246,6 +248,31 @@ def main():
                             "overlap_efficiency": round(1.0 - (t_pipe - t_dev) / load_ms, 4),
                             "h2d_gb_per_s": round(reused_bytes / (load_ms * 1e-3) / 1e9, 1),
                             "loaded_bytes": int(reused_bytes)}
+        if args.load_sweep:
+            # Sec. 4.3 Fig. 13 / Sec. 5.5 Fig. 20 on this machine: prefill delay (selective prefill of the prefix, joined)
+            # of the three strategies against the link rate; 0 = the native host link.  "model" is the unit-cost
+            # schedule of Fig. 13 fed with this run's per-layer recompute time and the layer/E-cache bytes at that rate.
+            layer_bytes = 2 * T * shape.kv_width * shape.elem_bytes
+            e_bytes = T * shape.hidden * shape.elem_bytes
+            t_layer = t_dev / (hi - lo)
+            native = reused_bytes / (load_ms * 1e-3) / 1e9
+            sweep = []
+            for gbps in (2.0, 5.0, 10.0, 20.0, 0.0):
+                B.dsk_set_load_throttle(model, gbps)
+                rate = (gbps if gbps > 0 else native) * 1e9
+                tl, te = layer_bytes / rate * 1e3, e_bytes / rate * 1e3
+                n_reused = L - (hi - lo)
+                row = {"link_gb_per_s": gbps if gbps > 0 else round(native, 1)}
+                for name, mode, model_ms in (
+                        ("all_then_compute", B.DSK_LOAD_ALL_FIRST, te + L * tl + (hi - lo) * t_layer),
+                        ("reused_then_compute", B.DSK_LOAD_REUSED_FIRST, te + n_reused * tl + (hi - lo) * t_layer),
+                        ("pipelined", B.DSK_LOAD_PIPELINED, max(te + n_reused * tl, te + (hi - lo) * t_layer))):
+                    row[name + "_ms"] = round(run_mode(mode, kv_r, hidden_in), 2)
+                    row[name + "_model_ms"] = round(model_ms, 2)
+                sweep.append(row)
+            B.dsk_set_load_throttle(model, 0.0)
+            B.dsk_set_load_mode(model, B.DSK_LOAD_PIPELINED)
+            extra["load_sweep"] = sweep
     flops = recompute_flops(shape, lens, hi - lo)
     extra.update({
         "partial_prefill_ms": round(t_partial, 3), "suffix_prefill_ms": round(t_suffix, 3),
