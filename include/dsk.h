@@ -200,6 +200,32 @@ DSK_API int dsk_set_load_mode(dsk_model_t* model, int load_mode);
  * experiments (Sec. 4.3 Fig. 13; Sec. 5.5 Fig. 20); results are unchanged. */
 DSK_API int dsk_set_load_throttle(dsk_model_t* model, double gb_per_s);
 
+/* ---- run-time choice of the re-computation configuration (App. B); host code, no device work ---- */
+
+/* One point of the offline profile's Pareto frontier (Sec. 4.2): recomputing layers [lo, hi) gave `quality`. */
+typedef struct dsk_frontier_point_t {
+  int32_t lo, hi;
+  double quality;
+} dsk_frontier_point_t;
+
+/* Profiled prefill-delay model in ms: c0 + R*(c_layer_token*T + c_layer_token2*T^2) + (L-R)*c_reused_token*T
+ * for R recomputed of L layers and T tokens (projections and MLP are linear in T, causal attention quadratic,
+ * a reused layer costs its KV transfer). */
+typedef struct dsk_latency_model_t {
+  double c0, c_layer_token, c_layer_token2, c_reused_token;
+} dsk_latency_model_t;
+
+DSK_API double dsk_estimate_prefill_ms(const dsk_latency_model_t* lat, int n_layers, int n_recomputed, int64_t n_tokens);
+
+/* App. B: with requests waiting (n_waiting > 0) the point with the fewest recomputed layers whose quality
+ * reaches quality_target; otherwise the point with the most recomputed layers whose estimated delay for
+ * n_tokens meets slo_ms.  If no point qualifies the one with the fewest layers is taken; equal layer counts go
+ * to the better quality, then to the lower index.  *chosen receives the index into frontier.  DSK_EINVAL for
+ * null or empty input or a point outside [0, n_layers]. */
+DSK_API int dsk_select_recompute(const dsk_frontier_point_t* frontier, int n_points, int n_layers, int64_t n_tokens,
+                         const dsk_latency_model_t* lat, double slo_ms, double quality_target, int n_waiting,
+                         int* chosen);
+
 /* ---- component entry points: single steps of the layer, for parity tests and micro-benchmarks ---- */
 
 /* y[M,N] = x[M,K] * w[N,K]^T (+ r[M,N] if r != NULL); all device, row-major, dense rows, dtype as given.

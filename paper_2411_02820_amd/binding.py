@@ -33,13 +33,22 @@ EXPORTS = (
     "dsk_model_init_random", "dsk_fill_normal", "dsk_partial_prefill", "dsk_partial_prefill_groups",
     "dsk_suffix_prefill",
     "dsk_join_loads", "dsk_set_load_mode", "dsk_set_load_throttle", "dsk_model_weight_bytes", "dsk_model_workspace_bytes",
-    "dsk_strerror", "dsk_last_hip_error", "dsk_linear", "dsk_attention", "dsk_set_option", "dsk_get_stat",
+    "dsk_strerror", "dsk_last_hip_error", "dsk_estimate_prefill_ms", "dsk_select_recompute", "dsk_linear", "dsk_attention", "dsk_set_option", "dsk_get_stat",
 )
 
 
 class dsk_group_t(C.Structure):
     _fields_ = [("lo", C.c_int32), ("hi", C.c_int32), ("hidden_in", C.c_void_p), ("hidden_in_mem", C.c_int32),
                 ("hidden_out", C.c_void_p)]
+
+
+class dsk_frontier_point_t(C.Structure):
+    _fields_ = [("lo", C.c_int32), ("hi", C.c_int32), ("quality", C.c_double)]
+
+
+class dsk_latency_model_t(C.Structure):
+    _fields_ = [("c0", C.c_double), ("c_layer_token", C.c_double), ("c_layer_token2", C.c_double),
+                ("c_reused_token", C.c_double)]
 
 
 class dsk_config_t(C.Structure):
@@ -79,6 +88,10 @@ lib.dsk_set_option.argtypes = [C.c_char_p, C.c_int]
 lib.dsk_get_stat.argtypes = [C.c_char_p, C.POINTER(C.c_double)]
 lib.dsk_join_loads.argtypes = [_P, _P]
 lib.dsk_set_load_mode.argtypes = [_P, C.c_int]
+lib.dsk_estimate_prefill_ms.argtypes = [C.POINTER(dsk_latency_model_t), C.c_int, C.c_int, C.c_int64]
+lib.dsk_estimate_prefill_ms.restype = C.c_double
+lib.dsk_select_recompute.argtypes = [C.POINTER(dsk_frontier_point_t), C.c_int, C.c_int, C.c_int64, C.POINTER(dsk_latency_model_t),
+                                     C.c_double, C.c_double, C.c_int, C.POINTER(C.c_int)]
 lib.dsk_set_load_throttle.argtypes = [_P, C.c_double]
 lib.dsk_model_weight_bytes.argtypes = [_P]
 lib.dsk_model_weight_bytes.restype = C.c_int64
@@ -88,7 +101,7 @@ lib.dsk_strerror.argtypes = [C.c_int]
 lib.dsk_strerror.restype = C.c_char_p
 lib.dsk_last_hip_error.argtypes = []
 for _n in EXPORTS:
-    if _n not in ("dsk_model_weight_bytes", "dsk_model_workspace_bytes", "dsk_strerror"):
+    if _n not in ("dsk_model_weight_bytes", "dsk_model_workspace_bytes", "dsk_strerror", "dsk_estimate_prefill_ms"):
         getattr(lib, _n).restype = C.c_int
 
 
@@ -214,6 +227,21 @@ def dsk_set_load_mode(model: int, mode: int):
 
 def dsk_set_load_throttle(model: int, gb_per_s: float):
     _check(lib.dsk_set_load_throttle(model, gb_per_s), "dsk_set_load_throttle")
+
+
+def dsk_estimate_prefill_ms(lat, n_layers: int, n_recomputed: int, n_tokens: int) -> float:
+    """lat: (c0, c_layer_token, c_layer_token2, c_reused_token)."""
+    return lib.dsk_estimate_prefill_ms(C.byref(dsk_latency_model_t(*lat)), n_layers, n_recomputed, n_tokens)
+
+
+def dsk_select_recompute(frontier, n_layers: int, n_tokens: int, lat, slo_ms: float, quality_target: float,
+                         n_waiting: int) -> int:
+    """frontier: sequence of (lo, hi, quality); returns the index of the chosen point."""
+    arr = (dsk_frontier_point_t * max(1, len(frontier)))(*[dsk_frontier_point_t(*p) for p in frontier])
+    chosen = C.c_int(-1)
+    _check(lib.dsk_select_recompute(arr, len(frontier), n_layers, n_tokens, C.byref(dsk_latency_model_t(*lat)), slo_ms,
+                                    quality_target, n_waiting, C.byref(chosen)), "dsk_select_recompute")
+    return chosen.value
 
 
 def dsk_model_weight_bytes(model: int) -> int:
