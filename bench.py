@@ -99,6 +99,9 @@ def main():
     ap.add_argument("--no-full-prefill", action="store_true")
     ap.add_argument("--load-sweep", action="store_true",
                     help="host-KV workloads: time the three loading strategies over emulated links of several rates")
+    ap.add_argument("--fit-latency", action="store_true",
+                    help="profile partial-prefill delay over token counts and recompute depths, fit the App. B latency model "
+                         "and show the configuration the policy picks for a synthetic frontier at several SLOs")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy, the known-size kernel that scales FETCH_SIZE/WRITE_SIZE")
     args = ap.parse_args()
@@ -273,6 +276,43 @@ def main():
             B.dsk_set_load_throttle(model, 0.0)
             B.dsk_set_load_mode(model, B.DSK_LOAD_PIPELINED)
             extra["load_sweep"] = sweep
+    if args.fit_latency and len(lens) == 1:
+        # App. B: "the parameters for estimation can be obtained through the profiling phase".  Profile the joined
+        # selective prefill at three token counts x three depths, least-squares fit of
+        # t = c0 + R (c1 T + c2 T^2) + (L - R) c3 T, then ask the library's policy for a synthetic frontier.
+        import numpy as np
+        rows_fit, t_fit = [], []
+        for Tn in (T // 4, T // 2, T):
+            pb = B.Batch(synth.cu_seqlens([Tn]), synth.packed_positions([Tn]))
+            for R in (2, 4, 8):
+                a = min(lo, L - R)
+                def f():
+                    B.dsk_partial_prefill(model, hidden_in, a, a + R, kv_r, kv_o, pb.desc, None, 0)
+                f()
+                ms = time_region(torch, f, 2)
+                rows_fit.append([1.0, R * Tn, R * Tn * Tn, (L - R) * Tn])
+                t_fit.append(ms)
+        A = np.array(rows_fit)
+        y = np.array(t_fit)
+        # scale the columns so that the least-squares problem is well conditioned
+        scale = A.max(axis=0)
+        from scipy.optimize import nnls   # costs cannot be negative
+        coef = nnls(A / scale, y)[0] / scale
+        lat = tuple(float(c) for c in coef)
+        resid = float(np.max(np.abs(A @ coef - y) / y))
+        frontier = [(lo, lo, 0.30), (lo, lo + 2, 0.55), (lo, lo + 4, 0.70), (lo, lo + 8, 0.78), (0, L, 0.82)]
+        full_ms = B.dsk_estimate_prefill_ms(lat, L, L, T)
+        picks = []
+        for frac in (0.05, 0.15, 0.3, 0.6, 1.1):
+            i = B.dsk_select_recompute(frontier, L, T, lat, frac * full_ms, 0.7, 0)
+            picks.append({"slo_ms": round(frac * full_ms, 2), "recompute": list(frontier[i][:2]),
+                          "estimate_ms": round(B.dsk_estimate_prefill_ms(lat, L, frontier[i][1] - frontier[i][0], T), 2)})
+        i_busy = B.dsk_select_recompute(frontier, L, T, lat, full_ms, 0.7, 4)
+        extra["latency_model"] = {"c0_ms": lat[0], "c_layer_token_ms": lat[1], "c_layer_token2_ms": lat[2],
+                                  "c_reused_token_ms": lat[3], "max_rel_residual": round(resid, 4),
+                                  "points": len(t_fit), "policy_idle": picks,
+                                  "policy_4_waiting_target_0.7": list(frontier[i_busy][:2]),
+                                  "frontier": "synthetic (quality values are placeholders)"}
     flops = recompute_flops(shape, lens, hi - lo)
     extra.update({
         "partial_prefill_ms": round(t_partial, 3), "suffix_prefill_ms": round(t_suffix, 3),
