@@ -48,7 +48,8 @@ typedef enum {
   DSK_ESHAPE = -2, /* model shape not supported (Hq % Hkv, odd head_dim, head_dim > 256, ...) */
   DSK_EDTYPE = -3, /* dtype not DSK_F32 / DSK_BF16 */
   DSK_ENOMEM = -4, /* device or host allocation failed */
-  DSK_EHIP = -5    /* a HIP call failed; see dsk_last_hip_error() */
+  DSK_EHIP = -5,   /* a HIP call failed; see dsk_last_hip_error() */
+  DSK_ENOENT = -6  /* the cache store holds no such entry */
 } dsk_status;
 
 typedef enum { DSK_F32 = 0, DSK_BF16 = 1 } dsk_dtype;
@@ -199,6 +200,46 @@ DSK_API int dsk_set_load_mode(dsk_model_t* model, int load_mode);
  * emulates a slower link between the cache's home and the GPU for the loading-strategy and bandwidth
  * experiments (Sec. 4.3 Fig. 13; Sec. 5.5 Fig. 20); results are unchanged. */
 DSK_API int dsk_set_load_throttle(dsk_model_t* model, double gb_per_s);
+
+/* ---- cache store: the store / fetch interfaces of Sec. 4.4 ----
+ * A key-value store of KV and E caches, split by layer, keyed by the hash of the context text and the model that
+ * produced them, kept in GPU memory (the paper's choice) with pinned host memory as a second tier.  The store
+ * owns the memory; pointers and descriptors it hands out stay valid until the entry is erased or the store
+ * destroyed, and what they point to is complete once the stream given to the put call has drained.  Calls are
+ * serialised by an internal lock.  partial_prefill (Sec. 4.4) is dsk_partial_prefill[_groups] fed with these
+ * descriptors. */
+typedef struct dsk_store dsk_store_t;
+typedef enum { DSK_TIER_AUTO = 0, DSK_TIER_DEVICE = 1, DSK_TIER_HOST = 2 } dsk_tier; /* AUTO: device while it fits */
+
+/* "We calculate the hash of the context text" (Sec. 4.4): 64-bit FNV-1a of the bytes. */
+DSK_API uint64_t dsk_hash_context(const void* bytes, int64_t n);
+
+/* Capacities bound what each tier may hold; a put that fits nowhere returns DSK_ENOMEM. */
+DSK_API int dsk_store_create(int64_t device_capacity_bytes, int64_t host_capacity_bytes, dsk_store_t** out);
+/* Frees every entry (waits for device work on them) and the store. */
+DSK_API int dsk_store_destroy(dsk_store_t* store);
+
+/* store(Cache, context, LLM) for a KV cache: copies rows 0..n_rows-1 of all n_layers layers of `kv` (device or
+ * pinned host; row_bytes = Hkv*dh*element size) into a compact slab of the chosen tier, on `stream`.  If the
+ * (context, model) pair is already present nothing happens (Sec. 4.4) and *inserted (optional) is 0. */
+DSK_API int dsk_store_put_kv(dsk_store_t* store, uint64_t context, uint64_t model_id, const dsk_kv_t* kv, int n_layers,
+                     int64_t n_rows, int64_t row_bytes, int tier, void* stream, int* inserted);
+/* The same for the E cache at transition layer `layer` ([n_tokens, d], `bytes` in all). */
+DSK_API int dsk_store_put_e(dsk_store_t* store, uint64_t context, uint64_t model_id, int layer, const void* e_cache,
+                    int e_mem, int64_t bytes, int tier, void* stream, int* inserted);
+
+/* fetch(context, LLM, layer_id) -> Cache.  Per layer: K and V row blocks of that layer; or the whole cache as a
+ * descriptor that dsk_partial_prefill accepts as kv_reused; or the E cache stored for a transition layer.
+ * DSK_ENOENT if nothing was stored under the key. */
+DSK_API int dsk_store_fetch_kv_layer(dsk_store_t* store, uint64_t context, uint64_t model_id, int layer,
+                             const void** k_rows, const void** v_rows, int* mem, int64_t* bytes_each);
+DSK_API int dsk_store_fetch_kv(dsk_store_t* store, uint64_t context, uint64_t model_id, dsk_kv_t* out, int* n_layers);
+DSK_API int dsk_store_fetch_e(dsk_store_t* store, uint64_t context, uint64_t model_id, int layer, const void** e_cache,
+                      int* mem, int64_t* bytes);
+
+/* Drops everything stored for (context, model); waits for device work that may still use it. */
+DSK_API int dsk_store_erase(dsk_store_t* store, uint64_t context, uint64_t model_id);
+DSK_API int dsk_store_usage(dsk_store_t* store, int64_t* device_bytes, int64_t* host_bytes, int64_t* n_entries);
 
 /* ---- run-time choice of the re-computation configuration (App. B); host code, no device work ---- */
 

@@ -33,7 +33,9 @@ EXPORTS = (
     "dsk_model_init_random", "dsk_fill_normal", "dsk_partial_prefill", "dsk_partial_prefill_groups",
     "dsk_suffix_prefill",
     "dsk_join_loads", "dsk_set_load_mode", "dsk_set_load_throttle", "dsk_model_weight_bytes", "dsk_model_workspace_bytes",
-    "dsk_strerror", "dsk_last_hip_error", "dsk_estimate_prefill_ms", "dsk_select_recompute", "dsk_linear", "dsk_attention", "dsk_set_option", "dsk_get_stat",
+    "dsk_strerror", "dsk_last_hip_error", "dsk_hash_context", "dsk_store_create", "dsk_store_destroy",
+    "dsk_store_put_kv", "dsk_store_put_e", "dsk_store_fetch_kv_layer", "dsk_store_fetch_kv", "dsk_store_fetch_e",
+    "dsk_store_erase", "dsk_store_usage", "dsk_estimate_prefill_ms", "dsk_select_recompute", "dsk_linear", "dsk_attention", "dsk_set_option", "dsk_get_stat",
 )
 
 
@@ -88,6 +90,19 @@ lib.dsk_set_option.argtypes = [C.c_char_p, C.c_int]
 lib.dsk_get_stat.argtypes = [C.c_char_p, C.POINTER(C.c_double)]
 lib.dsk_join_loads.argtypes = [_P, _P]
 lib.dsk_set_load_mode.argtypes = [_P, C.c_int]
+lib.dsk_hash_context.argtypes = [C.c_char_p, C.c_int64]
+lib.dsk_hash_context.restype = C.c_uint64
+lib.dsk_store_create.argtypes = [C.c_int64, C.c_int64, C.POINTER(_P)]
+lib.dsk_store_destroy.argtypes = [_P]
+lib.dsk_store_put_kv.argtypes = [_P, C.c_uint64, C.c_uint64, C.POINTER(dsk_kv_t), C.c_int, C.c_int64, C.c_int64, C.c_int, _P,
+                                 C.POINTER(C.c_int)]
+lib.dsk_store_put_e.argtypes = [_P, C.c_uint64, C.c_uint64, C.c_int, _P, C.c_int, C.c_int64, C.c_int, _P, C.POINTER(C.c_int)]
+lib.dsk_store_fetch_kv_layer.argtypes = [_P, C.c_uint64, C.c_uint64, C.c_int, C.POINTER(_P), C.POINTER(_P), C.POINTER(C.c_int),
+                                         C.POINTER(C.c_int64)]
+lib.dsk_store_fetch_kv.argtypes = [_P, C.c_uint64, C.c_uint64, C.POINTER(dsk_kv_t), C.POINTER(C.c_int)]
+lib.dsk_store_fetch_e.argtypes = [_P, C.c_uint64, C.c_uint64, C.c_int, C.POINTER(_P), C.POINTER(C.c_int), C.POINTER(C.c_int64)]
+lib.dsk_store_erase.argtypes = [_P, C.c_uint64, C.c_uint64]
+lib.dsk_store_usage.argtypes = [_P, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
 lib.dsk_estimate_prefill_ms.argtypes = [C.POINTER(dsk_latency_model_t), C.c_int, C.c_int, C.c_int64]
 lib.dsk_estimate_prefill_ms.restype = C.c_double
 lib.dsk_select_recompute.argtypes = [C.POINTER(dsk_frontier_point_t), C.c_int, C.c_int, C.c_int64, C.POINTER(dsk_latency_model_t),
@@ -101,7 +116,8 @@ lib.dsk_strerror.argtypes = [C.c_int]
 lib.dsk_strerror.restype = C.c_char_p
 lib.dsk_last_hip_error.argtypes = []
 for _n in EXPORTS:
-    if _n not in ("dsk_model_weight_bytes", "dsk_model_workspace_bytes", "dsk_strerror", "dsk_estimate_prefill_ms"):
+    if _n not in ("dsk_model_weight_bytes", "dsk_model_workspace_bytes", "dsk_strerror", "dsk_estimate_prefill_ms",
+                  "dsk_hash_context"):
         getattr(lib, _n).restype = C.c_int
 
 
@@ -120,11 +136,13 @@ def _check(status: int, where: str):
 
 
 def _ptr(x):
-    """Raw address of a torch tensor / int / None."""
+    """Raw address of a torch tensor / int / (address, dsk_mem) pair / None."""
     if x is None:
         return None
     if isinstance(x, int):
         return x
+    if isinstance(x, tuple):
+        return x[0]
     return x.data_ptr()
 
 
@@ -135,6 +153,8 @@ def _stream(stream):
 
 
 def _mem_of(t) -> int:
+    if isinstance(t, tuple):   # (address, dsk_mem), e.g. what the cache store hands out
+        return t[1]
     return DSK_MEM_DEVICE if t.is_cuda else DSK_MEM_HOST_PINNED
 
 
@@ -227,6 +247,74 @@ def dsk_set_load_mode(model: int, mode: int):
 
 def dsk_set_load_throttle(model: int, gb_per_s: float):
     _check(lib.dsk_set_load_throttle(model, gb_per_s), "dsk_set_load_throttle")
+
+
+DSK_ENOENT = -6
+DSK_TIER_AUTO, DSK_TIER_DEVICE, DSK_TIER_HOST = 0, 1, 2
+
+
+def dsk_hash_context(data: bytes) -> int:
+    return lib.dsk_hash_context(data, len(data))
+
+
+def dsk_store_create(device_capacity_bytes: int, host_capacity_bytes: int) -> int:
+    out = _P()
+    _check(lib.dsk_store_create(device_capacity_bytes, host_capacity_bytes, C.byref(out)), "dsk_store_create")
+    return out.value
+
+
+def dsk_store_destroy(store: int):
+    _check(lib.dsk_store_destroy(store), "dsk_store_destroy")
+
+
+def dsk_store_put_kv(store: int, context: int, model_id: int, kv: dsk_kv_t, n_layers: int, n_rows: int, row_bytes: int,
+                     tier: int = DSK_TIER_AUTO, stream=None) -> bool:
+    ins = C.c_int(0)
+    _check(lib.dsk_store_put_kv(store, context, model_id, C.byref(kv), n_layers, n_rows, row_bytes, tier, _stream(stream),
+                                C.byref(ins)), "dsk_store_put_kv")
+    return bool(ins.value)
+
+
+def dsk_store_put_e(store: int, context: int, model_id: int, layer: int, e_cache, tier: int = DSK_TIER_AUTO,
+                    stream=None) -> bool:
+    ins = C.c_int(0)
+    nbytes = e_cache.numel() * e_cache.element_size()
+    _check(lib.dsk_store_put_e(store, context, model_id, layer, _ptr(e_cache), _mem_of(e_cache), nbytes, tier,
+                               _stream(stream), C.byref(ins)), "dsk_store_put_e")
+    return bool(ins.value)
+
+
+def dsk_store_fetch_kv_layer(store: int, context: int, model_id: int, layer: int):
+    """-> (k_ptr, v_ptr, mem, bytes_each)"""
+    k, v, mem, n = _P(), _P(), C.c_int(), C.c_int64()
+    _check(lib.dsk_store_fetch_kv_layer(store, context, model_id, layer, C.byref(k), C.byref(v), C.byref(mem), C.byref(n)),
+           "dsk_store_fetch_kv_layer")
+    return k.value, v.value, mem.value, n.value
+
+
+def dsk_store_fetch_kv(store: int, context: int, model_id: int):
+    """-> (dsk_kv_t, n_layers)"""
+    d, n = dsk_kv_t(), C.c_int()
+    _check(lib.dsk_store_fetch_kv(store, context, model_id, C.byref(d), C.byref(n)), "dsk_store_fetch_kv")
+    return d, n.value
+
+
+def dsk_store_fetch_e(store: int, context: int, model_id: int, layer: int):
+    """-> (ptr, mem, bytes)"""
+    p, mem, n = _P(), C.c_int(), C.c_int64()
+    _check(lib.dsk_store_fetch_e(store, context, model_id, layer, C.byref(p), C.byref(mem), C.byref(n)), "dsk_store_fetch_e")
+    return p.value, mem.value, n.value
+
+
+def dsk_store_erase(store: int, context: int, model_id: int):
+    _check(lib.dsk_store_erase(store, context, model_id), "dsk_store_erase")
+
+
+def dsk_store_usage(store: int):
+    """-> (device_bytes, host_bytes, n_entries)"""
+    a, b, c = C.c_int64(), C.c_int64(), C.c_int64()
+    _check(lib.dsk_store_usage(store, C.byref(a), C.byref(b), C.byref(c)), "dsk_store_usage")
+    return a.value, b.value, c.value
 
 
 def dsk_estimate_prefill_ms(lat, n_layers: int, n_recomputed: int, n_tokens: int) -> float:

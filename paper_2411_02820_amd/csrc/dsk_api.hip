@@ -7,9 +7,9 @@
 
 #include "dsk_internal.h"
 
-namespace {
+thread_local int g_last_hip_error = 0;  // shared with the cache store
 
-thread_local int g_last_hip_error = 0;
+namespace {
 
 #define HIP_TRY(expr)                          \
   do {                                         \
@@ -680,6 +680,7 @@ const char* dsk_strerror(int status) {
     case DSK_EDTYPE: return "unsupported dtype";
     case DSK_ENOMEM: return "out of memory";
     case DSK_EHIP: return "HIP call failed";
+    case DSK_ENOENT: return "no such entry in the cache store";
     default: return "unknown status";
   }
 }

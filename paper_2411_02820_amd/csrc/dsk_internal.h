@@ -85,6 +85,8 @@ bool gemm_mfma_swiglu_supported(int M, int N, int K);
 
 // x is fp32 when x_f32 is set, else the model dtype; g and y are the model dtype
 hipError_t launch_rmsnorm(int dtype, const void* x, int x_f32, const void* g, void* y, int T, int d, float eps, hipStream_t s);
+extern thread_local int g_last_hip_error;  // hipError_t of the last failed HIP call on this thread
+
 // pacing of the load stream against the 100 MHz constant-rate clock
 hipError_t launch_pace_start(unsigned long long* t0, hipStream_t s);
 hipError_t launch_pace_wait(const unsigned long long* t0, unsigned long long ticks, hipStream_t s);
