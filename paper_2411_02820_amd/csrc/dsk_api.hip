@@ -595,7 +595,18 @@ int dsk_linear(int dtype, const void* x, const void* w, void* y, const void* r, 
   if (dtype != DSK_F32 && dtype != DSK_BF16) return DSK_EDTYPE;
   if (!aligned16(x) || !aligned16(w) || !aligned16(y) || !aligned16(r)) return DSK_EINVAL;
   const int epi = r ? EPI_RESIDUAL : EPI_STORE;
-  HIP_TRY(gemm_any(dtype, x, K + g_linear_ld_pad, w, K + g_linear_ld_pad, y, N, r, N, M, N, K, epi, nullptr, 0, (hipStream_t)stream));
+  // split-K partials of the small-M path: one buffer per process, allocated at the first small-M call and kept
+  // (calls that overlap on different streams would share it: this entry point is for tests and micro-benchmarks)
+  static void* ws = nullptr;
+  static int64_t ws_bytes = 0;
+  if (dtype == DSK_BF16 && M <= 64 && gemm_mfma_workspace_bytes(N) > ws_bytes) {
+    if (ws) HIP_TRY(hipFree(ws));
+    ws = nullptr; ws_bytes = 0;
+    HIP_TRY(hipMalloc(&ws, (size_t)gemm_mfma_workspace_bytes(N)));
+    ws_bytes = gemm_mfma_workspace_bytes(N);
+  }
+  HIP_TRY(gemm_any(dtype, x, K + g_linear_ld_pad, w, K + g_linear_ld_pad, y, N, r, N, M, N, K, epi, M <= 64 ? ws : nullptr,
+                   M <= 64 ? ws_bytes : 0, (hipStream_t)stream));
   return DSK_OK;
 }
 
