@@ -284,7 +284,7 @@ def main():
         rows_fit, t_fit = [], []
         for Tn in (T // 4, T // 2, T):
             pb = B.Batch(synth.cu_seqlens([Tn]), synth.packed_positions([Tn]))
-            for R in (2, 4, 8):
+            for R in sorted({min(2, L), min(4, L), min(8, L)}):
                 a = min(lo, L - R)
                 def f():
                     B.dsk_partial_prefill(model, hidden_in, a, a + R, kv_r, kv_o, pb.desc, None, 0)
@@ -300,7 +300,7 @@ def main():
         coef = nnls(A / scale, y)[0] / scale
         lat = tuple(float(c) for c in coef)
         resid = float(np.max(np.abs(A @ coef - y) / y))
-        frontier = [(lo, lo, 0.30), (lo, lo + 2, 0.55), (lo, lo + 4, 0.70), (lo, lo + 8, 0.78), (0, L, 0.82)]
+        frontier = [(lo, min(lo + r, L), q) for r, q in ((0, 0.30), (2, 0.55), (4, 0.70), (8, 0.78))] + [(0, L, 0.82)]
         full_ms = B.dsk_estimate_prefill_ms(lat, L, L, T)
         picks = []
         for frac in (0.05, 0.15, 0.3, 0.6, 1.1):

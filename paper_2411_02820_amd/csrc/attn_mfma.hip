@@ -571,7 +571,9 @@ hipError_t launch_attn_mfma_bf16(const AttnArgs& a, hipStream_t s) {
   const int64_t blocks = (int64_t)total * a.Hq;
   const int key_tiles = (int)((max_keys + BKV - 1) / BKV) + 1;
   if (a.ws && blocks < 512 && key_tiles >= 8) {
-    splits = (int)((1024 + blocks - 1) / blocks);
+    // about two workgroups per CU; measured on 64 queries against 8k and 16k keys: 16 splits beat 8 and 32
+    // (more splits pay more for partial outputs and the per-workgroup start-up than they gain in parallelism)
+    splits = (int)((512 + blocks - 1) / blocks);
     if (splits > key_tiles / 4) splits = key_tiles / 4;
     while (splits > 1 && ((int64_t)a.n_q * splits > kMaxSplitRows ||
                           (int64_t)a.n_q * splits * a.Hq * (a.dh + 2) * 4 > a.ws_bytes))
