@@ -314,11 +314,15 @@ def main():
                                   "policy_4_waiting_target_0.7": list(frontier[i_busy][:2]),
                                   "frontier": "synthetic (quality values are placeholders)"}
     flops = recompute_flops(shape, lens, hi - lo)
+    # what the matrix cores of this machine sustain in a register-only loop (bf16), right after the measurements
+    peak_measured = B.dsk_measure_mfma_peak()
     extra.update({
         "partial_prefill_ms": round(t_partial, 3), "suffix_prefill_ms": round(t_suffix, 3),
         "ttft_ms": round(t_partial + t_suffix, 3),
         "recompute_tflops_algorithmic": round(flops / 1e12, 2),
         "mfma_util_recompute_phase": round(flops / (t_partial * 1e-3) / (PEAK_BF16_TFLOPS * 1e12), 4),
+        "mfma_peak_measured_tflops": round(peak_measured, 1),
+        "mfma_util_recompute_phase_vs_measured_peak": round(flops / (t_partial * 1e-3) / (peak_measured * 1e12), 4),
         "reused_kv_bytes": int((L - (hi - lo)) * 2 * T * shape.kv_width * shape.elem_bytes),
         "weights_gb": round(weights_gb, 2),
         "kernel_launch_mix": {k: int(B.dsk_get_stat(k)) for k in

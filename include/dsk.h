@@ -282,11 +282,17 @@ DSK_API int dsk_attention(int dtype, const void* q, const void* k_rows, const vo
                           const dsk_batch_t* queries, const dsk_batch_t* prefix, int64_t own_row0, int n_q_heads,
                           int n_kv_heads, int head_dim, void* scratch, int64_t scratch_bytes, void* stream);
 
+/* Matrix-core throughput this device sustains, in TFLOP/s: a register-only bf16 MFMA loop on every CU, timed with
+ * events on `stream` (blocks until done; allocates and frees a small buffer).  For utilisation figures next to
+ * those against the spec-sheet peak. */
+DSK_API int dsk_measure_mfma_peak(double* tflops, void* stream);
+
 /* Integer knobs for benchmarks and tests; unknown names return DSK_EINVAL.
  *   "gemm_variant", "attn_variant": pick a kernel tiling (default 0 = what the library picks by itself)
  *   "force_generic": 1 = use the plain-ALU kernels even for bf16
  *   "time_gemm": 1 = bracket every tensor-core GEMM launch with M >= 1024 by a pair of HIP events on its
  *                stream (read back through dsk_get_stat)
+ *   "linear_ld_pad": dsk_linear reads x and w with row stride K + value elements (stride experiments)
  *   "reset_stats": any value; clears all counters and recorded timings */
 DSK_API int dsk_set_option(const char* name, int value);
 
