@@ -321,7 +321,9 @@ void gemm_mfma_set_variant(int v) { g_variant = v; }
 // the fused gate/up epilogue needs whole 64-row gate/up blocks and is not offered on the split-K path
 bool gemm_mfma_swiglu_supported(int M, int N, int K) { return M > 64 && N % 64 == 0 && K >= BK && K % BK == 0; }
 
-int64_t gemm_mfma_workspace_bytes(int max_n) { return (int64_t)64 * 4 * ((int64_t)768 * 64 + max_n); }
+// 64 token rows x (splits x N) floats: about 768 tiles of 64 columns (+ one more split's worth) for the 64x64
+// tiling, up to 4 splits of a wide N for the 64x128 tiling
+int64_t gemm_mfma_workspace_bytes(int max_n) { return (int64_t)64 * 4 * ((int64_t)768 * 64 + (int64_t)4 * max_n); }
 
 hipError_t launch_gemm_mfma_bf16(const void* A, int64_t lda, const void* W, int64_t ldw, void* C, int64_t ldc,
                                  const void* R, int64_t ldr, int M, int N, int K, int epi, void* ws, int64_t ws_bytes,
@@ -345,14 +347,19 @@ hipError_t launch_gemm_mfma_bf16(const void* A, int64_t lda, const void* W, int6
     else variant = 2;
   }
   switch (variant) {
-    case 3: {  // weight streaming: 64x64 tiles, K split so that about 768 workgroups stream W
-      const int tiles = ((M + 63) / 64) * ((N + 63) / 64);
-      int splits = (768 + tiles - 1) / tiles;
+    case 3: {  // weight streaming: K split over workgroups, fp32 partial planes, fixed-order reduce
+      // 64x64 tiles and about 768 workgroups; a very wide N (the gate/up projection) has enough 64x128 tiles to
+      // fill the chip with few splits, which halves the share of the token rows in the tile loads (measured on
+      // M = 64, N = 28672, K = 4096: 54 us against 64 us; narrower shapes are best left as they are)
+      const bool wide = (N + 127) / 128 >= 192;
+      const int tiles = ((M + 63) / 64) * (wide ? (N + 127) / 128 : (N + 63) / 64);
+      int splits = ((wide ? 512 : 768) + tiles - 1) / tiles;
       splits = max(1, min(splits, KT / 2));
       int per = (KT + splits - 1) / splits;
       splits = (KT + per - 1) / per;
       if (splits > 1 && ws && (int64_t)splits * M * N * 4 <= ws_bytes) {
-        hipError_t e = launch<64, 64, 1, 2, true>(A, lda, W, ldw, C, ldc, R, ldr, (float*)ws, M, N, K, epi, splits, per, s);
+        hipError_t e = wide ? launch<64, 128, 1, 4, true>(A, lda, W, ldw, C, ldc, R, ldr, (float*)ws, M, N, K, epi, splits, per, s)
+                            : launch<64, 64, 1, 2, true>(A, lda, W, ldw, C, ldc, R, ldr, (float*)ws, M, N, K, epi, splits, per, s);
         if (e != hipSuccess) return e;
         const int64_t quads = (int64_t)M * (N / 4);
         hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s, (const float*)ws,
