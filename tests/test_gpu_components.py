@@ -61,7 +61,7 @@ def test_linear_in_place_residual(B):
     assert O.max_rel_err(y.float().cpu().numpy(), ref) <= 2 ** -8
 
 
-def _attention_case(B, lens, plens, Hq, Hkv, dh, dtype, use_scratch):
+def _attention_case(B, lens, plens, Hq, Hkv, dh, dtype, use_scratch, key_gain=None, q_gain=1.0):
     from paper_2411_02820_amd import binding
     cu = synth.cu_seqlens(lens)
     n_q = int(cu[-1])
@@ -70,8 +70,11 @@ def _attention_case(B, lens, plens, Hq, Hkv, dh, dtype, use_scratch):
     own_row0 = n_pre + 3 if plens else 0          # a gap between the two ranges
     rows = own_row0 + n_q
     rnd = (lambda a: _bf16(a)) if dtype == "bf16" else (lambda a: a)
-    q = rnd(synth.normal(n_q * Hq * dh, 21, 0, 1.0).reshape(n_q, Hq, dh))
-    k = rnd(synth.normal(rows * Hkv * dh, 21, 1, 1.0).reshape(rows, Hkv, dh))
+    q = rnd(synth.normal(n_q * Hq * dh, 21, 0, 1.0).reshape(n_q, Hq, dh) * np.float32(q_gain))
+    k = synth.normal(rows * Hkv * dh, 21, 1, 1.0).reshape(rows, Hkv, dh)
+    if key_gain is not None:   # per-row gain on the keys: shapes how the running maximum moves along the keys
+        k = k * key_gain(np.arange(rows)).astype(np.float32)[:, None, None]
+    k = rnd(k)
     v = rnd(synth.normal(rows * Hkv * dh, 21, 2, 1.0).reshape(rows, Hkv, dh))
     seq = np.repeat(np.arange(len(lens)), lens)
     ref = np.empty((n_q, Hq, dh))
@@ -98,6 +101,19 @@ def _attention_case(B, lens, plens, Hq, Hkv, dh, dtype, use_scratch):
 def test_attention_bf16_tensor_core_kernel(B, lens, plens):
     err = _attention_case(B, lens, plens, 8, 2, 128, "bf16", True)
     assert B.dsk_get_stat("attn_mfma_launches") == 1, "the MFMA kernel must be the one that ran"
+    assert err <= 1e-2
+
+
+@pytest.mark.parametrize("ramp", ["up", "down", "spikes"])
+def test_attention_bf16_peaked_scores(B, ramp):
+    # Scores with a standard deviation of tens instead of one, so the softmax is sharply peaked and the running
+    # maximum matters: growing along the keys (the maximum keeps jumping by far more than the kernel's lazy
+    # threshold, every jump rescales the accumulated output), shrinking (the first tile holds the maximum, later
+    # probabilities underflow), and isolated large keys (long stretches where the reference maximum stays put).
+    gain = {"up": lambda r: 1.0 + r / 24.0, "down": lambda r: 1.0 + (r.max() - r) / 24.0,
+            "spikes": lambda r: np.where(r % 97 == 5, 12.0, 1.0)}[ramp]
+    err = _attention_case(B, [333, 90], [70, 150], 8, 2, 128, "bf16", True, key_gain=gain, q_gain=3.0)
+    assert B.dsk_get_stat("attn_mfma_launches") == 1
     assert err <= 1e-2
 
 
