@@ -187,14 +187,6 @@ __global__ void __launch_bounds__(64 * NW, 8 / NW) attn_bf16_kernel(AttnParams p
 #pragma unroll
     for (int i = 0; i < V_INST; ++i) issue_v1(it, i);
   };
-  // n-th of the K_INST + V_INST loads that follow the barrier of tile `it`: K(it+2), then Vt(it+1)
-  auto issue_next = [&](int it, int n) {
-    if (n < K_INST) {
-      if (it + 2 < it_end) issue_k1(it + 2, n);
-    } else if (n < K_INST + V_INST) {
-      if (it + 1 < it_end) issue_v1(it + 1, n - K_INST);
-    }
-  };
   // A wave has nothing to do in tiles that lie wholly beyond the causal limit of all its queries; those are
   // the last tiles of the range, so the wave's active tiles are [it_begin, act_end).
   int act_end = it_begin;
@@ -285,9 +277,6 @@ __global__ void __launch_bounds__(64 * NW, 8 / NW) attn_bf16_kernel(AttnParams p
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int j = 0; j < NQK; ++j) {
-        // the tile loads that this iteration's barrier released go out one per two MFMAs: a burst of
-        // them would stall the wave on the memory pipeline's issue rate
-        if ((j & 1) == 0) issue_next(it, j >> 1);
         if (HN) {
           if (j + 2 < NQK) kf[j + 2] = k_frag(kt_s, j + 2);
           const int kt = j % 2, ks = j / 2;
@@ -345,11 +334,11 @@ __global__ void __launch_bounds__(64 * NW, 8 / NW) attn_bf16_kernel(AttnParams p
 
   // Per tile and workgroup one barrier: after it K(it+1) and Vt(it) are complete in LDS and every wave is
   // done with K(it) and Vt(it-1), whose ring stages the loads issued next overwrite.
+  // The loads the barrier released go out right behind it, in one burst (about 55 cycles each): spread between
+  // the MFMAs of phase 1 they cost the wave more than that (measured with per-phase timestamps).
   auto tile_sync = [&](int it) {
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): as a builtin the compiler accounts for it
     __syncthreads();
-  };
-  auto loads_only = [&](int it) {
     if (it + 2 < it_end) issue_k(it + 2);
     if (it + 1 < it_end) issue_v(it + 1);
   };
@@ -402,10 +391,7 @@ __global__ void __launch_bounds__(64 * NW, 8 / NW) attn_bf16_kernel(AttnParams p
       tile_step(std::false_type{}, it, s_a, s_b);
       it += 1;
     }
-    for (; it < it_end; ++it) {
-      tile_sync(it);
-      loads_only(it);
-    }
+    for (; it < it_end; ++it) tile_sync(it);
   }
 
   // ---- store: register 4g+e of d-tile dt is out[q][32dt + 8g + 4*(lane/32) + e] ----
