@@ -10,6 +10,10 @@ import ctypes as C
 import os
 
 import numpy as np
+# PyTorch first: it brings its own copy of the HIP runtime, and the process must end up with ONE runtime.  Loaded
+# after torch, libdsk.so binds to that copy; loaded before, it would pull in the system's runtime, and torch would
+# then find no GPU.
+import torch  # noqa: F401
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdsk.so")
