@@ -182,7 +182,7 @@ int run_layer(dsk_model* m, int l, const void* h_in, int h_in_f32, void* h_out, 
   HIP_TRY(gemm(m, m->attn, nq, w.wo, nq, m->h, d, h_in, d, n, d, nq,
                EPI_RESIDUAL | EPI_C_F32 | ((h_in_f32 || all_f32) ? EPI_R_F32 : 0), s));
   HIP_TRY(launch_rmsnorm(c.dtype, m->h, 1, w.g2, m->xn, n, d, (float)c.rms_eps, s));
-  if (c.dtype == DSK_BF16 && !g_force_generic && m->gu_block == 32 && gemm_mfma_swiglu_supported(n, 2 * F, d)) {
+  if (c.dtype == DSK_BF16 && !g_force_generic && m->gu_block == 32 && gemm_mfma_swiglu_supported(n, 2 * F, d, m->gemm_ws ? m->gemm_ws_bytes : 0)) {
     HIP_TRY(gemm(m, m->xn, d, w.wgu, d, m->act, F, nullptr, 0, n, 2 * F, d, EPI_SWIGLU, s));  // SwiGLU in the epilogue
   } else {
     HIP_TRY(gemm(m, m->xn, d, w.wgu, d, m->gu, 2 * (int64_t)F, nullptr, 0, n, 2 * F, d, EPI_STORE, s));

@@ -81,7 +81,7 @@ hipError_t launch_gemm_mfma_bf16(const void* A, int64_t lda, const void* W, int6
                                  const void* R, int64_t ldr, int M, int N, int K, int epi, void* ws, int64_t ws_bytes,
                                  hipStream_t s);
 int64_t gemm_mfma_workspace_bytes(int max_n);
-bool gemm_mfma_swiglu_supported(int M, int N, int K);
+bool gemm_mfma_swiglu_supported(int M, int N, int K, int64_t ws_bytes);
 
 // x is fp32 when x_f32 is set, else the model dtype; g and y are the model dtype
 hipError_t launch_rmsnorm(int dtype, const void* x, int x_f32, const void* g, void* y, int T, int d, float eps, hipStream_t s);

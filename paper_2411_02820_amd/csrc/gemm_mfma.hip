@@ -295,6 +295,34 @@ __global__ void __launch_bounds__(256) splitk_reduce_kernel(const float* __restr
   store_quad(C, ldc, R, ldr, m, n, s, epi);
 }
 
+// The same for the gate/up projection, with SwiGLU applied to the sums: act[m][f] = silu(gate) * up, where gate
+// column f sits at packed column (f/32)*64 + f%32 of P and its up column 32 further (rows of W interleaved in
+// blocks of 32).  N = 2F columns in P, F columns in act.
+__global__ void __launch_bounds__(256) splitk_reduce_swiglu_kernel(const float* __restrict__ P, bf16_t* __restrict__ act,
+                                                                   int64_t ldc, int M, int N, int splits) {
+  const int F = N / 2;
+  const int64_t quads = (int64_t)M * (F / 4);
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= quads) return;
+  const int m = (int)(i / (F / 4)), f = (int)(i - (int64_t)m * (F / 4)) * 4;
+  const int pg = (f / 32) * 64 + f % 32;
+  f32x4 g = *(const f32x4*)(P + (int64_t)m * N + pg);
+  f32x4 u = *(const f32x4*)(P + (int64_t)m * N + pg + 32);
+  for (int k = 1; k < splits; ++k) {
+    const float* row = P + ((int64_t)k * M + m) * N + pg;
+    const f32x4 g2 = *(const f32x4*)row, u2 = *(const f32x4*)(row + 32);
+    g[0] += g2[0]; g[1] += g2[1]; g[2] += g2[2]; g[3] += g2[3];
+    u[0] += u2[0]; u[1] += u2[1]; u[2] += u2[2]; u[3] += u2[3];
+  }
+  bf16x4 o;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const float sig = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * g[e]));
+    o[e] = (bf16_t)(g[e] * sig * u[e]);
+  }
+  *(bf16x4*)(act + (int64_t)m * ldc + f) = o;
+}
+
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool PARTIAL>
 hipError_t launch(const void* A, int64_t lda, const void* W, int64_t ldw, void* C, int64_t ldc, const void* R, int64_t ldr,
                   float* P, int M, int N, int K, int epi, int splits, int kt_per_split, hipStream_t s) {
@@ -318,8 +346,30 @@ int g_variant = 0;
 
 void gemm_mfma_set_variant(int v) { g_variant = v; }
 
-// the fused gate/up epilogue needs whole 64-row gate/up blocks and is not offered on the split-K path
-bool gemm_mfma_swiglu_supported(int M, int N, int K) { return M > 64 && N % 64 == 0 && K >= BK && K % BK == 0; }
+// How a projection over few token rows (M <= 64) is split: 64x64 tiles and about 768 workgroups; a very wide N
+// (the gate/up projection) has enough 64x128 tiles to fill the chip with few splits, which halves the share of the
+// token rows in the tile loads (measured on M = 64, N = 28672, K = 4096: 54 us against 64 us; narrower shapes are
+// best left as they are).  Returns whether the K-split path can run (more than one split, partials fit in ws).
+static bool small_m_plan(int M, int N, int K, int64_t ws_bytes, bool* wide, int* splits, int* per) {
+  const int KT = K / BK;
+  *wide = (N + 127) / 128 >= 192;
+  const int tiles = ((M + 63) / 64) * (*wide ? (N + 127) / 128 : (N + 63) / 64);
+  int sp = ((*wide ? 512 : 768) + tiles - 1) / tiles;
+  sp = max(1, min(sp, KT / 2));
+  *per = (KT + sp - 1) / sp;
+  *splits = (KT + *per - 1) / *per;
+  return *splits > 1 && (int64_t)*splits * M * N * 4 <= ws_bytes;
+}
+
+// The fused gate/up epilogue needs whole 64-column gate/up blocks; over few token rows it is applied by the
+// split-K reduction, so there it needs the K-split path.
+bool gemm_mfma_swiglu_supported(int M, int N, int K, int64_t ws_bytes) {
+  if (N % 64 != 0 || K < BK || K % BK != 0) return false;
+  if (M > 64) return true;
+  bool wide;
+  int splits, per;
+  return small_m_plan(M, N, K, ws_bytes, &wide, &splits, &per);
+}
 
 // 64 token rows x (splits x N) floats: about 768 tiles of 64 columns (+ one more split's worth) for the 64x64
 // tiling, up to 4 splits of a wide N for the 64x128 tiling
@@ -336,7 +386,19 @@ hipError_t launch_gemm_mfma_bf16(const void* A, int64_t lda, const void* W, int6
   const int KT = K / BK;
   int variant = g_variant;
   if (epi & EPI_SWIGLU) {
-    if (!gemm_mfma_swiglu_supported(M, N, K)) return hipErrorNotSupported;
+    if (!gemm_mfma_swiglu_supported(M, N, K, ws ? ws_bytes : 0)) return hipErrorNotSupported;
+    if (M <= 64) {
+      bool wide;
+      int splits, per;
+      small_m_plan(M, N, K, ws_bytes, &wide, &splits, &per);
+      hipError_t e = wide ? launch<64, 128, 1, 4, true>(A, lda, W, ldw, C, ldc, R, ldr, (float*)ws, M, N, K, 0, splits, per, s)
+                          : launch<64, 64, 1, 2, true>(A, lda, W, ldw, C, ldc, R, ldr, (float*)ws, M, N, K, 0, splits, per, s);
+      if (e != hipSuccess) return e;
+      const int64_t quads = (int64_t)M * (N / 8);
+      hipLaunchKernelGGL(splitk_reduce_swiglu_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s,
+                         (const float*)ws, (bf16_t*)C, ldc, M, N, splits);
+      return hipGetLastError();
+    }
     if ((int64_t)((M + 255) / 256) * ((N + 255) / 256) >= 192 || variant == 1)
       return launch<256, 256, 2, 4, false>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
     return launch<128, 128, 2, 2, false>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
@@ -348,16 +410,9 @@ hipError_t launch_gemm_mfma_bf16(const void* A, int64_t lda, const void* W, int6
   }
   switch (variant) {
     case 3: {  // weight streaming: K split over workgroups, fp32 partial planes, fixed-order reduce
-      // 64x64 tiles and about 768 workgroups; a very wide N (the gate/up projection) has enough 64x128 tiles to
-      // fill the chip with few splits, which halves the share of the token rows in the tile loads (measured on
-      // M = 64, N = 28672, K = 4096: 54 us against 64 us; narrower shapes are best left as they are)
-      const bool wide = (N + 127) / 128 >= 192;
-      const int tiles = ((M + 63) / 64) * (wide ? (N + 127) / 128 : (N + 63) / 64);
-      int splits = ((wide ? 512 : 768) + tiles - 1) / tiles;
-      splits = max(1, min(splits, KT / 2));
-      int per = (KT + splits - 1) / splits;
-      splits = (KT + per - 1) / per;
-      if (splits > 1 && ws && (int64_t)splits * M * N * 4 <= ws_bytes) {
+      bool wide;
+      int splits, per;
+      if (ws && small_m_plan(M, N, K, ws_bytes, &wide, &splits, &per)) {
         hipError_t e = wide ? launch<64, 128, 1, 4, true>(A, lda, W, ldw, C, ldc, R, ldr, (float*)ws, M, N, K, epi, splits, per, s)
                             : launch<64, 64, 1, 2, true>(A, lda, W, ldw, C, ldc, R, ldr, (float*)ws, M, N, K, epi, splits, per, s);
         if (e != hipSuccess) return e;
