@@ -166,8 +166,17 @@ int run_layer(dsk_model* m, int l, const void* h_in, int h_in_f32, void* h_out, 
   char* v_own = v_layer + own_row0 * row_bytes;
   const int all_f32 = c.dtype == DSK_F32;  // an fp32 model: every buffer is fp32 anyway
   HIP_TRY(launch_rmsnorm(c.dtype, h_in, h_in_f32 || all_f32, w.g1, m->xn, n, d, (float)c.rms_eps, s));
-  HIP_TRY(gemm(m, m->xn, d, w.wqkv, d, m->qkv, m->n_qkv, nullptr, 0, n, m->n_qkv, d, EPI_STORE, s));
-  HIP_TRY(launch_rope_kv_write(c.dtype, m->qkv, m->rope_cs, k_own, v_own, n, c.n_q_heads, c.n_kv_heads, c.head_dim, s));
+  // few token rows (the suffix pass) on the tensor-core path: RoPE + KV write, and below the post-attention
+  // RMSNorm, are done by the split-K reduction of the projection in front of them
+  const bool few_rows = c.dtype == DSK_BF16 && !g_force_generic && n <= 64 && m->gemm_ws;
+  if (few_rows && gemm_small_m_fused_supported(n, m->n_qkv, d, d, d, m->gemm_ws_bytes)) {
+    HIP_TRY(launch_gemm_small_m_rope(m->xn, d, w.wqkv, d, m->qkv, m->n_qkv, m->rope_cs, k_own, v_own, n, d, c.n_q_heads,
+                                     c.n_kv_heads, c.head_dim, m->gemm_ws, m->gemm_ws_bytes, s));
+    ++g_stats.gemm_mfma;
+  } else {
+    HIP_TRY(gemm(m, m->xn, d, w.wqkv, d, m->qkv, m->n_qkv, nullptr, 0, n, m->n_qkv, d, EPI_STORE, s));
+    HIP_TRY(launch_rope_kv_write(c.dtype, m->qkv, m->rope_cs, k_own, v_own, n, c.n_q_heads, c.n_kv_heads, c.head_dim, s));
+  }
   AttnArgs a;
   a.q = m->qkv; a.ldq = m->n_qkv; a.k_rows = k_layer; a.v_rows = v_layer; a.out = m->attn;
   a.q_cu = q_cu; a.p_cu = p_cu; a.q_cu_host = q_cu_host; a.p_cu_host = p_cu_host; a.n_seqs = n_seqs;
@@ -179,9 +188,15 @@ int run_layer(dsk_model* m, int l, const void* h_in, int h_in_f32, void* h_out, 
     a.vt = m->vt; a.ldvt = m->ldvt;
   }
   HIP_TRY(attention(m, a, s));
-  HIP_TRY(gemm(m, m->attn, nq, w.wo, nq, m->h, d, h_in, d, n, d, nq,
-               EPI_RESIDUAL | EPI_C_F32 | ((h_in_f32 || all_f32) ? EPI_R_F32 : 0), s));
-  HIP_TRY(launch_rmsnorm(c.dtype, m->h, 1, w.g2, m->xn, n, d, (float)c.rms_eps, s));
+  if (few_rows && gemm_small_m_fused_supported(n, d, nq, nq, nq, m->gemm_ws_bytes)) {
+    HIP_TRY(launch_gemm_small_m_rmsnorm(m->attn, nq, w.wo, nq, m->h, h_in, h_in_f32 ? 1 : 0, w.g2, m->xn, (float)c.rms_eps, n,
+                                        d, nq, m->gemm_ws, m->gemm_ws_bytes, s));
+    ++g_stats.gemm_mfma;
+  } else {
+    HIP_TRY(gemm(m, m->attn, nq, w.wo, nq, m->h, d, h_in, d, n, d, nq,
+                 EPI_RESIDUAL | EPI_C_F32 | ((h_in_f32 || all_f32) ? EPI_R_F32 : 0), s));
+    HIP_TRY(launch_rmsnorm(c.dtype, m->h, 1, w.g2, m->xn, n, d, (float)c.rms_eps, s));
+  }
   if (c.dtype == DSK_BF16 && !g_force_generic && m->gu_block == 32 && gemm_mfma_swiglu_supported(n, 2 * F, d, m->gemm_ws ? m->gemm_ws_bytes : 0)) {
     HIP_TRY(gemm(m, m->xn, d, w.wgu, d, m->act, F, nullptr, 0, n, 2 * F, d, EPI_SWIGLU, s));  // SwiGLU in the epilogue
   } else {

@@ -82,6 +82,14 @@ hipError_t launch_gemm_mfma_bf16(const void* A, int64_t lda, const void* W, int6
                                  hipStream_t s);
 int64_t gemm_mfma_workspace_bytes(int max_n);
 bool gemm_mfma_swiglu_supported(int M, int N, int K, int64_t ws_bytes);
+// Few token rows (M <= 64, bf16): the projection and the step that follows it in one pass of the split-K reduction.
+bool gemm_small_m_fused_supported(int M, int N, int K, int64_t lda, int64_t ldw, int64_t ws_bytes);
+hipError_t launch_gemm_small_m_rope(const void* A, int64_t lda, const void* W, int64_t ldw, void* qkv, int64_t ldq,
+                                    const float2* cs, void* k_rows, void* v_rows, int M, int K, int Hq, int Hkv, int dh,
+                                    void* ws, int64_t ws_bytes, hipStream_t s);
+hipError_t launch_gemm_small_m_rmsnorm(const void* A, int64_t lda, const void* W, int64_t ldw, float* h, const void* R,
+                                       int r_f32, const void* g, void* xn, float eps, int M, int d, int K, void* ws,
+                                       int64_t ws_bytes, hipStream_t s);
 
 // x is fp32 when x_f32 is set, else the model dtype; g and y are the model dtype
 hipError_t launch_rmsnorm(int dtype, const void* x, int x_f32, const void* g, void* y, int T, int d, float eps, hipStream_t s);

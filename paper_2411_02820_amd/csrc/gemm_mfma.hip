@@ -323,6 +323,101 @@ __global__ void __launch_bounds__(256) splitk_reduce_swiglu_kernel(const float* 
   *(bf16x4*)(act + (int64_t)m * ldc + f) = o;
 }
 
+// The same for the fused QKV projection of few token rows, followed by what rope_kv_write_kernel does: q and k
+// heads rotated with the (cos, sin) table of the tokens (pairs (i, i + dh/2)), q written to the qkv buffer, rotated
+// k and v written to the rows of the cache.  One thread per 4 rotary pairs, or per 4 values of v.
+__global__ void __launch_bounds__(256) splitk_reduce_rope_kernel(const float* __restrict__ P, bf16_t* __restrict__ qkv,
+                                                                 int64_t ldq, const float2* __restrict__ cs,
+                                                                 bf16_t* __restrict__ k_rows, bf16_t* __restrict__ v_rows,
+                                                                 int M, int N, int splits, int Hq, int Hkv, int dh) {
+  const int half = dh / 2;
+  const int rot_units = (Hq + Hkv) * (half / 4), v_units = Hkv * dh / 4;
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (int64_t)M * (rot_units + v_units)) return;
+  const int m = (int)(i / (rot_units + v_units)), u = (int)(i - (int64_t)m * (rot_units + v_units));
+  const int kvw = Hkv * dh;
+  auto sum4 = [&](int col) {
+    f32x4 a = *(const f32x4*)(P + (int64_t)m * N + col);
+    for (int k = 1; k < splits; ++k) {
+      const f32x4 b = *(const f32x4*)(P + ((int64_t)k * M + m) * N + col);
+      a[0] += b[0]; a[1] += b[1]; a[2] += b[2]; a[3] += b[3];
+    }
+    return a;
+  };
+  auto to_bf16 = [](f32x4 v) {
+    bf16x4 o;
+    o[0] = (bf16_t)v[0]; o[1] = (bf16_t)v[1]; o[2] = (bf16_t)v[2]; o[3] = (bf16_t)v[3];
+    return o;
+  };
+  if (u < rot_units) {
+    const int head = u / (half / 4), i0 = (u % (half / 4)) * 4;
+    const f32x4 x1 = sum4(head * dh + i0), x2 = sum4(head * dh + i0 + half);
+    f32x4 y1, y2;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float2 c = cs[(int64_t)m * half + i0 + e];
+      y1[e] = x1[e] * c.x - x2[e] * c.y;
+      y2[e] = x2[e] * c.x + x1[e] * c.y;
+    }
+    bf16_t* dst = head < Hq ? qkv + (int64_t)m * ldq + head * dh + i0 : k_rows + (int64_t)m * kvw + (head - Hq) * dh + i0;
+    *(bf16x4*)dst = to_bf16(y1);
+    *(bf16x4*)(dst + half) = to_bf16(y2);
+  } else {
+    const int j = (u - rot_units) * 4;
+    *(bf16x4*)(v_rows + (int64_t)m * kvw + j) = to_bf16(sum4((Hq + Hkv) * dh + j));
+  }
+}
+
+// The same for a projection with residual whose result feeds an RMSNorm (the O projection before the MLP): one
+// workgroup per token row adds the partial sums and the residual, writes the fp32 residual stream h and the
+// normalised row xn = h * rsqrt(mean(h^2) + eps) * g in bf16.  d <= 1024 * NCH.
+template <int NCH>
+__global__ void __launch_bounds__(256) splitk_reduce_rmsnorm_kernel(const float* __restrict__ P, float* __restrict__ h,
+                                                                    const void* __restrict__ R, int r_f32,
+                                                                    const bf16_t* __restrict__ g, bf16_t* __restrict__ xn,
+                                                                    int M, int d, int splits, float eps) {
+  __shared__ float part[4];
+  const int m = blockIdx.x;
+  f32x4 v[NCH];
+  float ss = 0.f;
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int n = (threadIdx.x + c * 256) * 4;
+    if (n < d) {
+      f32x4 a = *(const f32x4*)(P + (int64_t)m * d + n);
+      for (int k = 1; k < splits; ++k) {
+        const f32x4 b = *(const f32x4*)(P + ((int64_t)k * M + m) * d + n);
+        a[0] += b[0]; a[1] += b[1]; a[2] += b[2]; a[3] += b[3];
+      }
+      if (r_f32) {
+        a += *(const f32x4*)((const float*)R + (int64_t)m * d + n);
+      } else {
+        const bf16x4 r = *(const bf16x4*)((const bf16_t*)R + (int64_t)m * d + n);
+        a[0] += (float)r[0]; a[1] += (float)r[1]; a[2] += (float)r[2]; a[3] += (float)r[3];
+      }
+      *(f32x4*)(h + (int64_t)m * d + n) = a;
+      v[c] = a;
+      ss += a[0] * a[0] + a[1] * a[1] + a[2] * a[2] + a[3] * a[3];
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  const float r = 1.0f / sqrtf((part[0] + part[1] + part[2] + part[3]) / (float)d + eps);
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int n = (threadIdx.x + c * 256) * 4;
+    if (n < d) {
+      const bf16x4 gg = *(const bf16x4*)(g + n);
+      bf16x4 o;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[e] = (bf16_t)(v[c][e] * r * (float)gg[e]);
+      *(bf16x4*)(xn + (int64_t)m * d + n) = o;
+    }
+  }
+}
+
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool PARTIAL>
 hipError_t launch(const void* A, int64_t lda, const void* W, int64_t ldw, void* C, int64_t ldc, const void* R, int64_t ldr,
                   float* P, int M, int N, int K, int epi, int splits, int kt_per_split, hipStream_t s) {
@@ -426,4 +521,56 @@ hipError_t launch_gemm_mfma_bf16(const void* A, int64_t lda, const void* W, int6
     case 2: return launch<128, 128, 2, 2, false>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
     default: return launch<256, 256, 2, 4, false>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
   }
+}
+
+// ---- few token rows (M <= 64): projection + the step that follows it, in the split-K reduction ----
+
+bool gemm_small_m_fused_supported(int M, int N, int K, int64_t lda, int64_t ldw, int64_t ws_bytes) {
+  if (M < 1 || M > 64 || K < BK || K % BK || N % 4 || (lda & 7) || (ldw & 7)) return false;
+  if ((int64_t)M * lda * 2 >= ((int64_t)1 << 32) || (int64_t)N * ldw * 2 >= ((int64_t)1 << 32)) return false;
+  bool wide;
+  int splits, per;
+  return small_m_plan(M, N, K, ws_bytes, &wide, &splits, &per);
+}
+
+static hipError_t small_m_partials(const void* A, int64_t lda, const void* W, int64_t ldw, int M, int N, int K, void* ws,
+                                   int64_t ws_bytes, int* splits, hipStream_t s) {
+  if (!ws || !gemm_small_m_fused_supported(M, N, K, lda, ldw, ws_bytes)) return hipErrorNotSupported;
+  bool wide;
+  int per;
+  small_m_plan(M, N, K, ws_bytes, &wide, splits, &per);
+  return wide ? launch<64, 128, 1, 4, true>(A, lda, W, ldw, nullptr, N, nullptr, 0, (float*)ws, M, N, K, 0, *splits, per, s)
+              : launch<64, 64, 1, 2, true>(A, lda, W, ldw, nullptr, N, nullptr, 0, (float*)ws, M, N, K, 0, *splits, per, s);
+}
+
+// qkv projection + RoPE + KV-cache write: N = (Hq + 2 Hkv) dh
+hipError_t launch_gemm_small_m_rope(const void* A, int64_t lda, const void* W, int64_t ldw, void* qkv, int64_t ldq,
+                                    const float2* cs, void* k_rows, void* v_rows, int M, int K, int Hq, int Hkv, int dh,
+                                    void* ws, int64_t ws_bytes, hipStream_t s) {
+  const int N = (Hq + 2 * Hkv) * dh;
+  if (dh % 8 || (ldq & 3)) return hipErrorNotSupported;
+  int splits = 0;
+  hipError_t e = small_m_partials(A, lda, W, ldw, M, N, K, ws, ws_bytes, &splits, s);
+  if (e != hipSuccess) return e;
+  const int64_t units = (int64_t)M * ((Hq + Hkv) * (dh / 8) + Hkv * dh / 4);
+  hipLaunchKernelGGL(splitk_reduce_rope_kernel, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, s, (const float*)ws,
+                     (bf16_t*)qkv, ldq, cs, (bf16_t*)k_rows, (bf16_t*)v_rows, M, N, splits, Hq, Hkv, dh);
+  return hipGetLastError();
+}
+
+// projection + residual + RMSNorm: h[M, d] (fp32) = x W^T + R, xn[M, d] (bf16) = rmsnorm(h) * g; dense rows
+hipError_t launch_gemm_small_m_rmsnorm(const void* A, int64_t lda, const void* W, int64_t ldw, float* h, const void* R,
+                                       int r_f32, const void* g, void* xn, float eps, int M, int d, int K, void* ws,
+                                       int64_t ws_bytes, hipStream_t s) {
+  if (d % 4 || d > 8192) return hipErrorNotSupported;
+  int splits = 0;
+  hipError_t e = small_m_partials(A, lda, W, ldw, M, d, K, ws, ws_bytes, &splits, s);
+  if (e != hipSuccess) return e;
+  if (d <= 4096)
+    hipLaunchKernelGGL(splitk_reduce_rmsnorm_kernel<4>, dim3(M), dim3(256), 0, s, (const float*)ws, h, R, r_f32,
+                       (const bf16_t*)g, (bf16_t*)xn, M, d, splits, eps);
+  else
+    hipLaunchKernelGGL(splitk_reduce_rmsnorm_kernel<8>, dim3(M), dim3(256), 0, s, (const float*)ws, h, R, r_f32,
+                       (const bf16_t*)g, (bf16_t*)xn, M, d, splits, eps);
+  return hipGetLastError();
 }

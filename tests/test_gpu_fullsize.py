@@ -189,6 +189,7 @@ def test_8b_shape_suffix_ragged_against_oracle(G, B):
     with G.GpuModel(shape, T, T + S) as m:
         m.init_random(synth.SEED_RECEIVER)
         kv_r = device_kv_cache(B, shape, T, T)
+        B.dsk_set_option("reset_stats", 0)   # the launch counters checked below are process-wide
         kv_out, h_out = m.partial(G.to_dev(hidden_host, shape), 1, 2, kv_r, lens, n_rows=T + S)
         hs = m.suffix(G.to_dev(xs_host, shape), kv_out, lens, slens)
         torch.cuda.synchronize()
