@@ -3,9 +3,11 @@
 // Both operands are K-contiguous, so both feed v_mfma_f32_32x32x16_bf16 with 16-byte vectors and no
 // transposition.  A workgroup owns a BM x BN tile of C and walks K in steps of 64 through a two-stage
 // LDS ring filled by direct global->LDS loads (global_load_lds_dwordx4: no staging registers, no
-// ds_write).  The loads of k-tile kt+1 are issued right after the barrier that ends k-tile kt-1 and land
-// while the MFMAs of k-tile kt run; fragments of k-step ks+1 are read from LDS before the MFMAs of
-// k-step ks are issued.
+// ds_write).  The loads of k-tile kt+2 go out, between MFMAs, as soon as a barrier shows that every wave
+// has read k-tile kt out of the stage they overwrite; fragments are read from LDS one or two k-steps ahead
+// of the MFMAs that use them.  Two schedules (SCHED): 0 frees the stage before the last k-step (one
+// barrier per k-tile; any tile shape), 1 frees it before k-step 2 of 4 and spreads the loads over two
+// k-steps (two barriers; the 256 x 256 prefill tile, where it is 5-8 % faster).
 //
 // LDS rows hold 64 bf16 = eight 16-byte slots.  A wave load instruction fills 64 consecutive slots
 // (8 rows); the swizzle is applied on the global side: the lane that fills slot p of row r fetches chunk
@@ -64,7 +66,8 @@ __device__ __forceinline__ void store_quad(void* C, int64_t ldc, const void* R, 
 // rows interleaved in blocks of 32 (packed rows 64b..64b+31 = gate rows 32b.., the next 32 = the same up
 // rows), so MFMA tiles j (even) and j+1 of a wave are gate and up of the same 32 FFN indices at the same
 // lane/register; the epilogue writes silu(gate)*up to C[M, N/2].
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool PARTIAL>
+// SCHED: software-pipeline schedule of the k loop, see the top of the file.
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool PARTIAL, int SCHED = 0>
 __global__ void __launch_bounds__(WAVES_M* WAVES_N * 64)
     gemm_bf16_kernel(const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ W, int64_t ldw,
                      void* __restrict__ C, int64_t ldc, const void* __restrict__ R, int64_t ldr,
@@ -176,59 +179,119 @@ __global__ void __launch_bounds__(WAVES_M* WAVES_N * 64)
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   }
   __syncthreads();
-  bf16x8 xf[2][TM], wf[2][TN];
-  load_frags(sA, sW, 0, xf[0], wf[0]);
-  // one k-tile; the two flags are compile-time so that the steady-state loop body is a single basic block
-  // (precise s_waitcnt counts) and the tail tiles are peeled
-  auto tile_step = [&](int t, auto has_next, auto has_next2) {
-    const int stage = t & 1;
-    const bf16_t* a_s = sA + stage * BM * BK;
-    const bf16_t* w_s = sW + stage * BN * BK;
+  if constexpr (SCHED == 1) {
+    // Early-freed stage, for k-tiles of four k-steps.  Fragments are read two k-steps ahead (sets 1 and 2 during
+    // k-step 0, set 3 during k-step 1), so every LDS read of the tile has returned before k-step 2: the barrier
+    // there frees the stage, and the loads of tile t+2 go out one per two MFMAs over k-steps 2 and 3 instead of
+    // all in the last one.  A second barrier before k-step 3 publishes tile t+1: its loads were issued a whole
+    // tile earlier, and only the LD loads issued since the first barrier may still be in flight.
+    static_assert(NKS == 4 && PER_TILE % 2 == 0, "schedule written for four k-steps");
+    constexpr int NM = TN * TM;
+    constexpr int LD = PER_TILE / 2;  // loads per wave in each of the last two k-steps
+    bf16x8 xs[NKS][TM], ws[NKS][TN];
+    load_frags(sA, sW, 0, xs[0], ws[0]);
+    auto tile_step = [&](int t, auto has_next, auto has_next2) {
+      const int stage = t & 1;
+      const bf16_t* a_s = sA + stage * BM * BK;
+      const bf16_t* w_s = sW + stage * BN * BK;
 #pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) {
-      const int cur = ks & 1;
-      constexpr int NM = TN * TM;
-      constexpr int LEAD = NM >= 8 ? 2 : 1;  // MFMAs issued before the next fragment reads
-      if (ks + 1 == NKS) {
-        // all reads of this tile are done; tile t+1 has landed (only its loads are outstanding)
-        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-        __syncthreads();
-        if (has_next)
-          load_frags(sA + (stage ^ 1) * BM * BK, sW + (stage ^ 1) * BN * BK, 0, xf[cur ^ 1], wf[cur ^ 1]);
-      }
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-          const int m = j * TM + i;
-          if (ks + 1 < NKS && m == LEAD) {
-            // Fragment reads of the next k-step go out after the first MFMAs of this one: the s_waitcnt the
-            // compiler puts in front of this k-step then only covers reads issued a whole k-step earlier, and
-            // the new reads have the remaining MFMAs to land.
-            __builtin_amdgcn_sched_barrier(0);
-            load_frags(a_s, w_s, ks + 1, xf[cur ^ 1], wf[cur ^ 1]);
-            __builtin_amdgcn_sched_barrier(0);
-          }
-          acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[cur][j], xf[cur][i], acc[j][i], 0, 0, 0);
-          if (ks + 1 == NKS && has_next2) {
-            // the loads of tile t+2 (its stage was freed by the barrier) go out one by one between the MFMAs of
-            // the last k-step: a wave that queues several vector-memory instructions back to back cannot issue
-            // its MFMAs until the address unit has taken them
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int q = m * PER_TILE / NM; q < (m + 1) * PER_TILE / NM; ++q)
-              issue_load(stage, (kt_begin + t + 2) * BK, q);
-            __builtin_amdgcn_sched_barrier(0);
-          }
+      for (int ks = 0; ks < NKS; ++ks) {
+        if (ks == 2) {
+          asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+          __builtin_amdgcn_s_barrier();
+          asm volatile("" ::: "memory");
         }
-      __builtin_amdgcn_sched_barrier(0);
-    }
-  };
-  int t = 0;
-  for (; t + 2 < n_kt; ++t) tile_step(t, std::true_type{}, std::true_type{});
-  if (t + 1 < n_kt) { tile_step(t, std::true_type{}, std::false_type{}); ++t; }
-  if (t < n_kt) tile_step(t, std::false_type{}, std::false_type{});
+        if (ks == 3) {
+          if (has_next2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LD) : "memory");
+          else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+          __builtin_amdgcn_s_barrier();
+          asm volatile("" ::: "memory");
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int i = 0; i < TM; ++i) {
+            const int m = j * TM + i;
+            if (m == (NM >= 8 ? 2 : 1)) {
+              __builtin_amdgcn_sched_barrier(0);
+              if (ks == 0) { load_frags(a_s, w_s, 1, xs[1], ws[1]); load_frags(a_s, w_s, 2, xs[2], ws[2]); }
+              if (ks == 1) load_frags(a_s, w_s, 3, xs[3], ws[3]);
+              if (ks == 3 && has_next) load_frags(sA + (stage ^ 1) * BM * BK, sW + (stage ^ 1) * BN * BK, 0, xs[0], ws[0]);
+              __builtin_amdgcn_sched_barrier(0);
+            }
+            acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ws[ks][j], xs[ks][i], acc[j][i], 0, 0, 0);
+            if (ks >= 2 && has_next2) {
+              __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+              for (int q = m * LD / NM; q < (m + 1) * LD / NM; ++q)
+                issue_load(stage, (kt_begin + t + 2) * BK, (ks - 2) * LD + q);
+              __builtin_amdgcn_sched_barrier(0);
+            }
+          }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    };
+    int t = 0;
+    for (; t + 2 < n_kt; ++t) tile_step(t, std::true_type{}, std::true_type{});
+    if (t + 1 < n_kt) { tile_step(t, std::true_type{}, std::false_type{}); ++t; }
+    if (t < n_kt) tile_step(t, std::false_type{}, std::false_type{});
+  } else {
+    bf16x8 xf[2][TM], wf[2][TN];
+    load_frags(sA, sW, 0, xf[0], wf[0]);
+    // one k-tile; the two flags are compile-time so that the steady-state loop body is a single basic block
+    // (precise s_waitcnt counts) and the tail tiles are peeled
+    auto tile_step = [&](int t, auto has_next, auto has_next2) {
+      const int stage = t & 1;
+      const bf16_t* a_s = sA + stage * BM * BK;
+      const bf16_t* w_s = sW + stage * BN * BK;
+  #pragma unroll
+      for (int ks = 0; ks < NKS; ++ks) {
+        const int cur = ks & 1;
+        constexpr int NM = TN * TM;
+        constexpr int LEAD = NM >= 8 ? 2 : 1;  // MFMAs issued before the next fragment reads
+        if (ks + 1 == NKS) {
+          // all reads of this tile are done; tile t+1 has landed (only its loads are outstanding)
+          asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+          __syncthreads();
+          if (has_next)
+            load_frags(sA + (stage ^ 1) * BM * BK, sW + (stage ^ 1) * BN * BK, 0, xf[cur ^ 1], wf[cur ^ 1]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+  #pragma unroll
+        for (int j = 0; j < TN; ++j)
+  #pragma unroll
+          for (int i = 0; i < TM; ++i) {
+            const int m = j * TM + i;
+            if (ks + 1 < NKS && m == LEAD) {
+              // Fragment reads of the next k-step go out after the first MFMAs of this one: the s_waitcnt the
+              // compiler puts in front of this k-step then only covers reads issued a whole k-step earlier, and
+              // the new reads have the remaining MFMAs to land.
+              __builtin_amdgcn_sched_barrier(0);
+              load_frags(a_s, w_s, ks + 1, xf[cur ^ 1], wf[cur ^ 1]);
+              __builtin_amdgcn_sched_barrier(0);
+            }
+            acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[cur][j], xf[cur][i], acc[j][i], 0, 0, 0);
+            if (ks + 1 == NKS && has_next2) {
+              // the loads of tile t+2 (its stage was freed by the barrier) go out one by one between the MFMAs of
+              // the last k-step: a wave that queues several vector-memory instructions back to back cannot issue
+              // its MFMAs until the address unit has taken them
+              __builtin_amdgcn_sched_barrier(0);
+  #pragma unroll
+              for (int q = m * PER_TILE / NM; q < (m + 1) * PER_TILE / NM; ++q)
+                issue_load(stage, (kt_begin + t + 2) * BK, q);
+              __builtin_amdgcn_sched_barrier(0);
+            }
+          }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    };
+    int t = 0;
+    for (; t + 2 < n_kt; ++t) tile_step(t, std::true_type{}, std::true_type{});
+    if (t + 1 < n_kt) { tile_step(t, std::true_type{}, std::false_type{}); ++t; }
+    if (t < n_kt) tile_step(t, std::false_type{}, std::false_type{});
+
+  }
 
   // ---- epilogue: accumulator register 4q+e of tile (j,i) is C[m][n + e],
   //      m = tile row base + lane%32, n = tile col base + 8q + 4*(lane/32) ----
@@ -418,10 +481,10 @@ __global__ void __launch_bounds__(256) splitk_reduce_rmsnorm_kernel(const float*
   }
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool PARTIAL>
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool PARTIAL, int SCHED = 0>
 hipError_t launch(const void* A, int64_t lda, const void* W, int64_t ldw, void* C, int64_t ldc, const void* R, int64_t ldr,
                   float* P, int M, int N, int K, int epi, int splits, int kt_per_split, hipStream_t s) {
-  auto kern = gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, PARTIAL>;
+  auto kern = gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, PARTIAL, SCHED>;
   constexpr int lds = NSTAGE * (BM + BN) * BK * 2;
   static bool configured = false;
   if (!configured) {
@@ -495,7 +558,7 @@ hipError_t launch_gemm_mfma_bf16(const void* A, int64_t lda, const void* W, int6
       return hipGetLastError();
     }
     if ((int64_t)((M + 255) / 256) * ((N + 255) / 256) >= 192 || variant == 1)
-      return launch<256, 256, 2, 4, false>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
+      return launch<256, 256, 2, 4, false, 1>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
     return launch<128, 128, 2, 2, false>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
   }
   if (variant == 0) {
@@ -519,7 +582,8 @@ hipError_t launch_gemm_mfma_bf16(const void* A, int64_t lda, const void* W, int6
       return launch<64, 64, 1, 2, false>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
     }
     case 2: return launch<128, 128, 2, 2, false>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
-    default: return launch<256, 256, 2, 4, false>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
+    case 4: return launch<256, 256, 2, 4, false, 0>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
+    default: return launch<256, 256, 2, 4, false, 1>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
   }
 }
 
