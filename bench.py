@@ -52,15 +52,23 @@ def measured_traffic(workload):
     return None
 
 
-def time_region(torch, fn, reps):
-    s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+PHASE_TIMES = {}
+
+
+def time_region(torch, fn, reps, name=None):
+    """Mean duration of fn in ms over reps back-to-back calls (HIP events on the current stream); with a name,
+    the per-call median and minimum are kept for the output line as well."""
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
     torch.cuda.synchronize()
-    s.record()
-    for _ in range(reps):
+    ev[0].record()
+    for i in range(reps):
         fn()
-    e.record()
+        ev[i + 1].record()
     torch.cuda.synchronize()
-    return s.elapsed_time(e) / reps
+    if name:
+        each = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(reps))
+        PHASE_TIMES[name] = {"median_ms": round(each[len(each) // 2], 3), "min_ms": round(each[0], 3), "reps": reps}
+    return ev[0].elapsed_time(ev[reps]) / reps
 
 
 def cpu_baseline(shape, lo, hi):
@@ -178,6 +186,7 @@ def main():
     else:
         kv_r = kv_dev_desc
     kv_o = B.kv_desc(kv_out)
+    kv_out.fill_(float("nan"))
     torch.cuda.synchronize()
 
     def partial(a=lo, b=hi):
@@ -221,14 +230,19 @@ def main():
     def partial_joined():
         partial()
         B.dsk_join_loads(model)
-    t_partial = time_region(torch, partial_joined, max(2, args.steps // 2))
-    t_suffix = time_region(torch, suffix_pass, max(2, args.steps // 2))
+    t_partial = time_region(torch, partial_joined, max(2, args.steps // 2), "partial_prefill")
+    t_suffix = time_region(torch, suffix_pass, max(2, args.steps // 2), "suffix_prefill")
+    # the timed steps really wrote the cache: a reused layer is the sender's, bit for bit, in a cache that was
+    # filled with NaN before the first step
+    chk = lo - 1 if lo > 0 else (hi if hi < L else None)
+    splice_ok = None if chk is None else bool(torch.equal(kv_out[chk, :, :T].view(torch.int16 if tdt == torch.bfloat16 else torch.int32),
+                                                            kv_sender[chk, :, :T].view(torch.int16 if tdt == torch.bfloat16 else torch.int32)))
     extra = {}
     if not args.no_full_prefill:
         def full():
             B.dsk_partial_prefill(model, hidden_in, 0, L, None, kv_o, prefix.desc, None, 0)
         full()
-        t_full = time_region(torch, full, 2)
+        t_full = time_region(torch, full, 2, "full_prefill")
         extra["full_prefill_ms"] = round(t_full, 3)
         extra["speedup_vs_full_prefill"] = round((t_full + t_suffix) / (t_partial + t_suffix), 3)
         extra["full_prefill_tokens_per_s"] = round(T / (t_full / 1e3), 1)
@@ -318,7 +332,8 @@ def main():
     peak_measured = B.dsk_measure_mfma_peak()
     extra.update({
         "partial_prefill_ms": round(t_partial, 3), "suffix_prefill_ms": round(t_suffix, 3),
-        "ttft_ms": round(t_partial + t_suffix, 3),
+        "ttft_ms": round(t_partial + t_suffix, 3), "phase_timing": PHASE_TIMES,
+        "reused_layer_bit_exact_after_timed_steps": splice_ok,
         "recompute_tflops_algorithmic": round(flops / 1e12, 2),
         "mfma_util_recompute_phase": round(flops / (t_partial * 1e-3) / (PEAK_BF16_TFLOPS * 1e12), 4),
         "mfma_peak_measured_tflops": round(peak_measured, 1),
@@ -344,7 +359,7 @@ def main():
         out["roofline"] = {"bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                            "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": measured_traffic(args.workload),
                            "traffic_unit": "bytes per launch (L2<->fabric reads + writes, rocprofv3 --pmc, see profiles/)",
-                           "kernel": "gemm_bf16_kernel<256,256,2,4> (prefill GEMMs: QKV, O, gate/up, down)",
+                           "kernel": "gemm_bf16_kernel<256,256,2,4,false,1> (prefill GEMMs: QKV, O, gate/up, down)",
                            "launches": int(gemm_n), "avg_launch_ms": round(gemm_ms / gemm_n, 4),
                            "flops_per_launch": round(gemm_flops / gemm_n / 1e9, 1), "flops_unit": "GFLOP"}
     else:
