@@ -37,6 +37,42 @@ def test_linear_bf16(B, M, N, K, residual):
     assert O.max_rel_err(y.float().cpu().numpy(), ref) <= 2 ** -8
 
 
+# every tiling of the prefill GEMM (1: 256x256 with the early-freed stage, 4: 256x256 with one barrier per k-tile,
+# 2: 128x128) forced on shapes with 1, 2, 3 and 7 k-tiles (the peeled head and tail of the software pipeline),
+# ragged M and N, with and without residual
+@pytest.mark.parametrize("variant", [1, 4, 2])
+@pytest.mark.parametrize("M,N,K,residual", [(300, 516, 64, False), (257, 512, 128, True), (513, 260, 192, False),
+                                            (700, 1028, 448, True)])
+def test_linear_bf16_forced_tiling(B, variant, M, N, K, residual):
+    x = _bf16(synth.normal(M * K, 14, 0, 1.0).reshape(M, K))
+    w = _bf16(synth.normal(N * K, 14, 1, 0.05).reshape(N, K))
+    r = _bf16(synth.normal(M * N, 14, 2, 1.0).reshape(M, N)) if residual else None
+    ref = x.astype(np.float64) @ w.astype(np.float64).T + (0 if r is None else r.astype(np.float64))
+    dev = lambda a: torch.from_numpy(a).to(torch.bfloat16).cuda()
+    y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    B.dsk_set_option("gemm_variant", variant)
+    try:
+        B.dsk_linear(B.DSK_BF16, dev(x), dev(w), y, None if r is None else dev(r), M, N, K)
+        torch.cuda.synchronize()
+    finally:
+        B.dsk_set_option("gemm_variant", 0)
+    assert O.max_rel_err(y.float().cpu().numpy(), ref) <= 2 ** -8
+
+
+# the tiling the library picks by itself for a prefill-sized problem (>= 192 tiles of 256x256), short K
+@pytest.mark.parametrize("K", [64, 320])
+def test_linear_bf16_large_grid_short_k(B, K):
+    M, N = 3585, 3332
+    x = _bf16(synth.normal(M * K, 15, 0, 1.0).reshape(M, K))
+    w = _bf16(synth.normal(N * K, 15, 1, 0.05).reshape(N, K))
+    ref = x.astype(np.float64) @ w.astype(np.float64).T
+    dev = lambda a: torch.from_numpy(a).to(torch.bfloat16).cuda()
+    y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    B.dsk_linear(B.DSK_BF16, dev(x), dev(w), y, None, M, N, K)
+    torch.cuda.synchronize()
+    assert O.max_rel_err(y.float().cpu().numpy(), ref) <= 2 ** -8
+
+
 @pytest.mark.parametrize("M,N,K", [(70, 96, 40), (128, 64, 256)])
 def test_linear_fp32(B, M, N, K):
     x = synth.normal(M * K, 12, 0, 1.0).reshape(M, K)
