@@ -295,6 +295,68 @@ __global__ void __launch_bounds__(WAVES_M* WAVES_N * 64)
 
   // ---- epilogue: accumulator register 4q+e of tile (j,i) is C[m][n + e],
   //      m = tile row base + lane%32, n = tile col base + 8q + 4*(lane/32) ----
+  // Wave tiles of 64 columns go through LDS (free by now: every wave has read its last fragments before the last
+  // barrier, and no load is in flight): stored straight from the accumulators, a store instruction would touch
+  // 32 rows with 8 or 16 bytes each; staged, a wave writes 32 x 64 fp32 values to a padded region of its own and
+  // reads them back row by row, so that 16 lanes cover one output row (128 contiguous bytes of bf16, 256 of fp32)
+  // and the residual is read the same way.  Only the wave itself touches its region: no barrier.
+  if constexpr (!PARTIAL && TN == 2) {
+    constexpr int ROW_F = 64 + 4;  // floats per staged row: 16-byte pad, conflict-free for 16 lanes at a time
+    float* stage = (float*)smem_raw + wave * (32 * ROW_F);
+    static_assert(NW * 32 * ROW_F * 4 <= NSTAGE * (BM + BN) * BK * 2, "staging region fits the tile ring");
+    const bool swiglu = (epi & EPI_SWIGLU) != 0;
+    const int rr = lane >> 4, c4 = (lane & 15) * 4;  // read-back: 4 rows per instruction, 4 columns per lane
+    const int rr_s = lane >> 3, c4_s = (lane & 7) * 4;  // SwiGLU: 32 result columns per row, 8 rows per instruction
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      if (swiglu) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          f32x4 o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float g = acc[0][i][4 * q + e], u = acc[1][i][4 * q + e];
+            const float sig = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * g));
+            o[e] = g * sig * u;
+          }
+          *(f32x4*)(stage + frag_row * ROW_F + 8 * q + 4 * frag_hi) = o;
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            f32x4 o = {acc[j][i][4 * q], acc[j][i][4 * q + 1], acc[j][i][4 * q + 2], acc[j][i][4 * q + 3]};
+            *(f32x4*)(stage + frag_row * ROW_F + j * 32 + 8 * q + 4 * frag_hi) = o;
+          }
+      }
+      __builtin_amdgcn_wave_barrier();
+      const int mb = m0 + wm * WTM + i * 32;
+      if (swiglu) {
+        const int fb = (n0 + wn * WTN) / 2;
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+          const int r = it * 8 + rr_s, m = mb + r, f = fb + c4_s;
+          const f32x4 v = *(const f32x4*)(stage + r * ROW_F + c4_s);
+          if (m < M && f < N / 2) {
+            bf16x4 o;
+            o[0] = (bf16_t)v[0]; o[1] = (bf16_t)v[1]; o[2] = (bf16_t)v[2]; o[3] = (bf16_t)v[3];
+            *(bf16x4*)((bf16_t*)C + (int64_t)m * ldc + f) = o;
+          }
+        }
+      } else {
+        const int n = n0 + wn * WTN + c4;
+#pragma unroll
+        for (int it = 0; it < 8; ++it) {
+          const int r = it * 4 + rr, m = mb + r;
+          const f32x4 v = *(const f32x4*)(stage + r * ROW_F + c4);
+          if (m < M && n < N) store_quad(C, ldc, R, ldr, m, n, v, epi);  // N is a multiple of 4
+        }
+      }
+      __builtin_amdgcn_wave_barrier();
+    }
+    return;
+  }
   if constexpr (TN % 2 == 0 && !PARTIAL) if (epi & EPI_SWIGLU) {
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
