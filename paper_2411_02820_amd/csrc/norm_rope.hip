@@ -119,6 +119,43 @@ __global__ void __launch_bounds__(256) rope_kv_write_kernel(T* __restrict__ qkv,
   for (int e = threadIdx.x; e < Hkv * dh; e += 256) vr[e] = vsrc[e];
 }
 
+// bf16, head_dim a multiple of 16: a lane handles eight neighbouring pairs (i, i + dh/2) of one head (two
+// 16-byte loads, two 16-byte stores, 64 bytes of the cos/sin row) or copies 16 bytes of v; the work items of all
+// tokens form one flat index space so that every lane of every workgroup has one.
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+__global__ void __launch_bounds__(256) rope_kv_write_vec_kernel(bf16_t* __restrict__ qkv, const float2* __restrict__ cs,
+                                                                bf16_t* __restrict__ k_rows, bf16_t* __restrict__ v_rows,
+                                                                int T, int Hq, int Hkv, int dh) {
+  const int half = dh >> 1, cph = half >> 3;  // 8-pair chunks per head
+  const int n_rope = (Hq + Hkv) * cph, n_v = Hkv * dh / 8, per_tok = n_rope + n_v;
+  const int64_t w = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (w >= (int64_t)T * per_tok) return;
+  const int t = (int)(w / per_tok), c = (int)(w - (int64_t)t * per_tok);
+  bf16_t* row = qkv + (int64_t)t * (Hq + 2 * Hkv) * dh;
+  if (c >= n_rope) {
+    const int e = (c - n_rope) * 8;
+    *(bf16x8_t*)(v_rows + (int64_t)t * Hkv * dh + e) = *(const bf16x8_t*)(row + (Hq + Hkv) * dh + e);
+    return;
+  }
+  const int head = c / cph, i0 = (c - head * cph) * 8;
+  const float2* csr = cs + (int64_t)t * half + i0;
+  bf16_t* hp = row + head * dh + i0;
+  const bf16x8_t x1 = *(const bf16x8_t*)hp, x2 = *(const bf16x8_t*)(hp + half);
+  bf16x8_t y1, y2;
+#pragma unroll
+  for (int e = 0; e < 8; e += 2) {
+    const f32x4_t c2 = *(const f32x4_t*)(csr + e);  // (cos, sin) of pairs e and e+1
+    const float a0 = (float)x1[e], b0 = (float)x2[e], a1 = (float)x1[e + 1], b1 = (float)x2[e + 1];
+    y1[e] = (bf16_t)(a0 * c2[0] - b0 * c2[1]);
+    y2[e] = (bf16_t)(b0 * c2[0] + a0 * c2[1]);
+    y1[e + 1] = (bf16_t)(a1 * c2[2] - b1 * c2[3]);
+    y2[e + 1] = (bf16_t)(b1 * c2[2] + a1 * c2[3]);
+  }
+  bf16_t* dst = head < Hq ? hp : k_rows + (int64_t)t * Hkv * dh + (head - Hq) * dh + i0;
+  *(bf16x8_t*)dst = y1;
+  *(bf16x8_t*)(dst + half) = y2;
+}
+
 template <typename T>
 __global__ void swiglu_kernel(const T* __restrict__ gu, T* __restrict__ act, int64_t n, int F, int gu_block) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -190,7 +227,11 @@ hipError_t launch_rope_kv_write(int dtype, void* qkv, const float2* cs, void* k_
   if (T <= 0) return hipSuccess;
   if (dtype == DSK_F32)
     hipLaunchKernelGGL(rope_kv_write_kernel<float>, dim3(T), dim3(256), 0, s, (float*)qkv, cs, (float*)k_rows, (float*)v_rows, Hq, Hkv, dh);
-  else
+  else if (dh % 16 == 0 && ((uintptr_t)qkv & 15) == 0 && ((uintptr_t)k_rows & 15) == 0 && ((uintptr_t)v_rows & 15) == 0) {
+    const int64_t items = (int64_t)T * ((Hq + Hkv) * (dh / 16) + Hkv * dh / 8);
+    hipLaunchKernelGGL(rope_kv_write_vec_kernel, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, s, (bf16_t*)qkv, cs,
+                       (bf16_t*)k_rows, (bf16_t*)v_rows, T, Hq, Hkv, dh);
+  } else
     hipLaunchKernelGGL(rope_kv_write_kernel<bf16_t>, dim3(T), dim3(256), 0, s, (bf16_t*)qkv, cs, (bf16_t*)k_rows, (bf16_t*)v_rows, Hq, Hkv, dh);
   return hipGetLastError();
 }
