@@ -505,15 +505,43 @@ __global__ void __launch_bounds__(256) splitk_reduce_rmsnorm_kernel(const float*
   const int m = blockIdx.x;
   f32x4 v[NCH];
   float ss = 0.f;
+  // partial sums in split order; the loads of four splits are issued together (one workgroup per row: it is
+  // the loads in flight per lane that decide how fast the row arrives)
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int n = (threadIdx.x + c * 256) * 4;
+    if (n < d) v[c] = *(const f32x4*)(P + (int64_t)m * d + n);
+  }
+  int k = 1;
+  for (; k + 3 < splits; k += 4) {
+    f32x4 b[4][NCH];
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int c = 0; c < NCH; ++c) {
+        const int n = (threadIdx.x + c * 256) * 4;
+        if (n < d) b[u][c] = *(const f32x4*)(P + ((int64_t)(k + u) * M + m) * d + n);
+      }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int c = 0; c < NCH; ++c) {
+        const int n = (threadIdx.x + c * 256) * 4;
+        if (n < d) v[c] += b[u][c];
+      }
+  }
+  for (; k < splits; ++k) {
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      const int n = (threadIdx.x + c * 256) * 4;
+      if (n < d) v[c] += *(const f32x4*)(P + ((int64_t)k * M + m) * d + n);
+    }
+  }
 #pragma unroll
   for (int c = 0; c < NCH; ++c) {
     const int n = (threadIdx.x + c * 256) * 4;
     if (n < d) {
-      f32x4 a = *(const f32x4*)(P + (int64_t)m * d + n);
-      for (int k = 1; k < splits; ++k) {
-        const f32x4 b = *(const f32x4*)(P + ((int64_t)k * M + m) * d + n);
-        a[0] += b[0]; a[1] += b[1]; a[2] += b[2]; a[3] += b[3];
-      }
+      f32x4 a = v[c];
       if (r_f32) {
         a += *(const f32x4*)((const float*)R + (int64_t)m * d + n);
       } else {
