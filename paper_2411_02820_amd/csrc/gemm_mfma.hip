@@ -305,8 +305,14 @@ __global__ void __launch_bounds__(WAVES_M* WAVES_N * 64)
     float* stage = (float*)smem_raw + wave * (32 * ROW_F);
     static_assert(NW * 32 * ROW_F * 4 <= NSTAGE * (BM + BN) * BK * 2, "staging region fits the tile ring");
     const bool swiglu = (epi & EPI_SWIGLU) != 0;
-    const int rr = lane >> 4, c4 = (lane & 15) * 4;  // read-back: 4 rows per instruction, 4 columns per lane
-    const int rr_s = lane >> 3, c4_s = (lane & 7) * 4;  // SwiGLU: 32 result columns per row, 8 rows per instruction
+    // the lane's indices are derived here from an opaque copy of the lane id: computed before the k loop (where the
+    // compiler would otherwise hoist them) they would take the kernel from 248 to 252 registers, i.e. to all 512
+    // of a SIMD for its two waves, and no other kernel's wave (a copy, a pacing kernel) could share the CU
+    int lane_e = lane;
+    asm volatile("" : "+v"(lane_e));
+    const int frag_row = lane_e & 31, frag_hi = lane_e >> 5;
+    const int rr = lane_e >> 4, c4 = (lane_e & 15) * 4;  // read-back: 4 rows per instruction, 4 columns per lane
+    const int rr_s = lane_e >> 3, c4_s = (lane_e & 7) * 4;  // SwiGLU: 32 result columns per row, 8 rows per instruction
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
       if (swiglu) {
