@@ -290,8 +290,8 @@ DSK_API int dsk_measure_mfma_peak(double* tflops, void* stream);
 /* Integer knobs for benchmarks and tests; unknown names return DSK_EINVAL.
  *   "gemm_variant", "attn_variant": pick a kernel tiling (default 0 = what the library picks by itself)
  *   "force_generic": 1 = use the plain-ALU kernels even for bf16
- *   "time_gemm": 1 = bracket every tensor-core GEMM launch with M >= 1024 by a pair of HIP events on its
- *                stream (read back through dsk_get_stat)
+ *   "time_gemm": 1 = bracket every tensor-core GEMM launch that runs on the 256 x 256 prefill tiling (at least
+ *                192 such tiles) by a pair of HIP events on its stream (read back through dsk_get_stat)
  *   "linear_ld_pad": dsk_linear reads x and w with row stride K + value elements (stride experiments)
  *   "reset_stats": any value; clears all counters and recorded timings */
 DSK_API int dsk_set_option(const char* name, int value);

@@ -101,7 +101,7 @@ struct Stats {
 hipError_t gemm_any(int dtype, const void* A, int64_t lda, const void* W, int64_t ldw, void* C, int64_t ldc,
                     const void* R, int64_t ldr, int M, int N, int K, int epi, void* ws, int64_t ws_bytes, hipStream_t s) {
   if (dtype == DSK_BF16 && !g_force_generic) {
-    const bool timed = g_time_gemm && M >= 1024 && g_stats.n_timed < Stats::kMaxTimed;
+    const bool timed = g_time_gemm && gemm_mfma_uses_prefill_tile(M, N) && g_stats.n_timed < Stats::kMaxTimed;
     if (timed) {
       if (!g_stats.ev) {
         g_stats.ev = (hipEvent_t*)calloc(2 * Stats::kMaxTimed, sizeof(hipEvent_t));

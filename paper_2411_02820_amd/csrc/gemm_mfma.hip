@@ -629,6 +629,11 @@ bool gemm_mfma_swiglu_supported(int M, int N, int K, int64_t ws_bytes) {
 // tiling, up to 4 splits of a wide N for the 64x128 tiling
 int64_t gemm_mfma_workspace_bytes(int max_n) { return (int64_t)64 * 4 * ((int64_t)768 * 64 + (int64_t)4 * max_n); }
 
+// Whether a projection of this size runs on the 256 x 256 prefill tiling (the kernel the roofline figure is about).
+bool gemm_mfma_uses_prefill_tile(int M, int N) {
+  return M > 64 && (int64_t)((M + 255) / 256) * ((N + 255) / 256) >= 192;
+}
+
 hipError_t launch_gemm_mfma_bf16(const void* A, int64_t lda, const void* W, int64_t ldw, void* C, int64_t ldc,
                                  const void* R, int64_t ldr, int M, int N, int K, int epi, void* ws, int64_t ws_bytes,
                                  hipStream_t s) {
