@@ -7,7 +7,7 @@
 // has read k-tile kt out of the stage they overwrite; fragments are read from LDS one or two k-steps ahead
 // of the MFMAs that use them.  Two schedules (SCHED): 0 frees the stage before the last k-step (one
 // barrier per k-tile; any tile shape), 1 frees it before k-step 2 of 4 and spreads the loads over two
-// k-steps (two barriers; the 256 x 256 prefill tile, where it is 5-8 % faster).
+// k-steps (two barriers; the 256 x 256 and 128 x 128 tiles, where it is 5-8 % and up to 25 % faster).
 //
 // LDS rows hold 64 bf16 = eight 16-byte slots.  A wave load instruction fills 64 consecutive slots
 // (8 rows); the swizzle is applied on the global side: the lane that fills slot p of row r fetches chunk
@@ -660,7 +660,7 @@ hipError_t launch_gemm_mfma_bf16(const void* A, int64_t lda, const void* W, int6
     }
     if ((int64_t)((M + 255) / 256) * ((N + 255) / 256) >= 192 || variant == 1)
       return launch<256, 256, 2, 4, false, 1>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
-    return launch<128, 128, 2, 2, false>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
+    return launch<128, 128, 2, 2, false, 1>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
   }
   if (variant == 0) {
     if (M <= 64) variant = 3;
@@ -682,7 +682,7 @@ hipError_t launch_gemm_mfma_bf16(const void* A, int64_t lda, const void* W, int6
       }
       return launch<64, 64, 1, 2, false>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
     }
-    case 2: return launch<128, 128, 2, 2, false>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
+    case 2: return launch<128, 128, 2, 2, false, 1>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
     case 4: return launch<256, 256, 2, 4, false, 0>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
     default: return launch<256, 256, 2, 4, false, 1>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
   }
