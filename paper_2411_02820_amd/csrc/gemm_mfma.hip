@@ -352,11 +352,27 @@ __global__ void __launch_bounds__(WAVES_M* WAVES_N * 64)
         }
       } else {
         const int n = n0 + wn * WTN + c4;
+        // the eight residual quads of this 32-row block are requested together, then added and stored: one
+        // memory round trip per block instead of one per store
+        f32x4 res[8];
+        if (epi & EPI_RESIDUAL) {
+#pragma unroll
+          for (int it = 0; it < 8; ++it) {
+            const int m = min(mb + it * 4 + rr, M - 1), nn = min(n, N - 4);  // clamped: masked below
+            if (epi & EPI_R_F32) {
+              res[it] = *(const f32x4*)((const float*)R + (int64_t)m * ldr + nn);
+            } else {
+              const bf16x4 rb = *(const bf16x4*)((const bf16_t*)R + (int64_t)m * ldr + nn);
+              res[it][0] = (float)rb[0]; res[it][1] = (float)rb[1]; res[it][2] = (float)rb[2]; res[it][3] = (float)rb[3];
+            }
+          }
+        }
 #pragma unroll
         for (int it = 0; it < 8; ++it) {
           const int r = it * 4 + rr, m = mb + r;
-          const f32x4 v = *(const f32x4*)(stage + r * ROW_F + c4);
-          if (m < M && n < N) store_quad(C, ldc, R, ldr, m, n, v, epi);  // N is a multiple of 4
+          f32x4 v = *(const f32x4*)(stage + r * ROW_F + c4);
+          if (epi & EPI_RESIDUAL) v += res[it];
+          if (m < M && n < N) store_quad(C, ldc, nullptr, 0, m, n, v, epi & ~(EPI_RESIDUAL | EPI_R_F32));  // N % 4 == 0
         }
       }
       __builtin_amdgcn_wave_barrier();
