@@ -614,14 +614,15 @@ int dsk_linear(int dtype, const void* x, const void* w, void* y, const void* r, 
   // (calls that overlap on different streams would share it: this entry point is for tests and micro-benchmarks)
   static void* ws = nullptr;
   static int64_t ws_bytes = 0;
-  if (dtype == DSK_BF16 && M <= 64 && gemm_mfma_workspace_bytes(N) > ws_bytes) {
+  const bool may_split = M <= 4096;  // the K-split paths are for few and for a few hundred token rows
+  if (dtype == DSK_BF16 && may_split && gemm_mfma_workspace_bytes(N) > ws_bytes) {
     if (ws) HIP_TRY(hipFree(ws));
     ws = nullptr; ws_bytes = 0;
     HIP_TRY(hipMalloc(&ws, (size_t)gemm_mfma_workspace_bytes(N)));
     ws_bytes = gemm_mfma_workspace_bytes(N);
   }
-  HIP_TRY(gemm_any(dtype, x, K + g_linear_ld_pad, w, K + g_linear_ld_pad, y, N, r, N, M, N, K, epi, M <= 64 ? ws : nullptr,
-                   M <= 64 ? ws_bytes : 0, (hipStream_t)stream));
+  HIP_TRY(gemm_any(dtype, x, K + g_linear_ld_pad, w, K + g_linear_ld_pad, y, N, r, N, M, N, K, epi, may_split ? ws : nullptr,
+                   may_split ? ws_bytes : 0, (hipStream_t)stream));
   return DSK_OK;
 }
 

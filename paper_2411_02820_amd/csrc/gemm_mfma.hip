@@ -678,6 +678,26 @@ hipError_t launch_gemm_mfma_bf16(const void* A, int64_t lda, const void* W, int6
       return launch<256, 256, 2, 4, false, 1>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
     return launch<128, 128, 2, 2, false, 1>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
   }
+  // A few hundred token rows: too few 128 x 128 tiles to fill the chip, so K is split over workgroups as on the
+  // few-row path (fp32 partial planes, fixed-order reduce); every split gets at least two k-tiles.
+  if (variant == 0 && M > 64 && ws) {
+    const int64_t tiles = (int64_t)((M + 127) / 128) * ((N + 127) / 128);
+    if (tiles <= 256) {
+      int sp = (int)((512 + tiles - 1) / tiles);
+      sp = max(1, min(sp, KT / 2));
+      while (sp > 1 && (int64_t)sp * M * N * 4 > ws_bytes) --sp;
+      const int per = (KT + sp - 1) / sp;
+      const int splits = (KT + per - 1) / per;
+      if (splits > 1) {
+        hipError_t e = launch<128, 128, 2, 2, true, 1>(A, lda, W, ldw, C, ldc, R, ldr, (float*)ws, M, N, K, epi, splits, per, s);
+        if (e != hipSuccess) return e;
+        const int64_t quads = (int64_t)M * (N / 4);
+        hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s, (const float*)ws,
+                           C, ldc, R, ldr, M, N, splits, epi);
+        return hipGetLastError();
+      }
+    }
+  }
   if (variant == 0) {
     if (M <= 64) variant = 3;
     else if ((int64_t)((M + 255) / 256) * ((N + 255) / 256) >= 192) variant = 1;
