@@ -359,7 +359,7 @@ def main():
         out["roofline"] = {"bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                            "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": measured_traffic(args.workload),
                            "traffic_unit": "bytes per launch (L2<->fabric reads + writes, rocprofv3 --pmc, see profiles/)",
-                           "kernel": "gemm_bf16_kernel<256,256,2,4,false,1> (prefill GEMMs: QKV, O, gate/up, down)",
+                           "kernel": "gemm16_bf16_kernel<256,256,2,4> (prefill GEMMs: QKV, O, gate/up, down)",
                            "launches": int(gemm_n), "avg_launch_ms": round(gemm_ms / gemm_n, 4),
                            "flops_per_launch": round(gemm_flops / gemm_n / 1e9, 1), "flops_unit": "GFLOP"}
     else:

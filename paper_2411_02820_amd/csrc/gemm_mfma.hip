@@ -426,6 +426,240 @@ __global__ void __launch_bounds__(WAVES_M* WAVES_N * 64)
   }
 }
 
+// The same GEMM on v_mfma_f32_16x16x32_bf16 (wave tiles of 64 columns, no K split).  Under a bf16 GEMM on random
+// data the chip sits at its power limit, and a register-only loop of this instruction sustains about 10 % more
+// flops there than the 32x32x16 one (the 16x16 accumulator tile is read and written half as often per flop).
+// W rows are the MFMA "A" operand again: lane l holds row l%16 and the eight k values 8*(l/16)..+7 of a 32-wide
+// k-step; accumulator register r of tile (j,i) is C[m][n + r], m = 16i + l%16, n = 16j + 4*(l/16).
+// Schedule per k-tile (two k-steps of 32 MFMAs): the fragments of k-step 1 are read during k-step 0; a barrier
+// between the k-steps frees the stage; the loads of tile t+2 go out one per four MFMAs of k-step 1; a barrier in
+// the middle of k-step 1 publishes tile t+1, whose first fragments are read during the rest of it.
+template <int BM, int BN, int WAVES_M, int WAVES_N>
+__global__ void __launch_bounds__(WAVES_M* WAVES_N * 64)
+    gemm16_bf16_kernel(const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ W, int64_t ldw,
+                       void* __restrict__ C, int64_t ldc, const void* __restrict__ R, int64_t ldr, int M, int N, int K,
+                       int epi, int tiles_m, int tiles_n) {
+  constexpr int NW = WAVES_M * WAVES_N;
+  constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
+  constexpr int TM = WTM / 16, TN = WTN / 16;  // 16x16 MFMA tiles per wave
+  constexpr int A_INST = BM / RPI / NW, W_INST = BN / RPI / NW;
+  constexpr int PER_TILE = A_INST + W_INST;
+  constexpr int NM = TM * TN;                  // MFMAs per k-step
+  constexpr int NF = TM + TN;                  // fragment reads per k-step
+  static_assert(WTN == 64 && BK == 64 && PER_TILE % 2 == 0 && NM % 4 == 0, "written for 64-column wave tiles, two k-steps");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  bf16_t* sA = (bf16_t*)smem_raw;
+  bf16_t* sW = sA + NSTAGE * BM * BK;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave % WAVES_M, wn = wave / WAVES_M;
+  int pid = blockIdx.x;
+  {
+    const int nb = gridDim.x;
+    const int q = nb / N_XCD, rem = nb % N_XCD;
+    const int xcd = pid % N_XCD, loc = pid / N_XCD;
+    pid = (xcd < rem) ? xcd * (q + 1) + loc : rem * (q + 1) + (xcd - rem) * q + loc;
+  }
+  const int per_group = GROUP_M * tiles_n;
+  const int group = pid / per_group;
+  const int first_m = group * GROUP_M;
+  const int gsz = min(GROUP_M, tiles_m - first_m);
+  const int in_group = pid - group * per_group;
+  const int m0 = (first_m + in_group % gsz) * BM, n0 = (in_group / gsz) * BN;
+
+  const int lr = lane / CH, lp = lane % CH;
+  uint32_t a_off[A_INST], w_off[W_INST];
+#pragma unroll
+  for (int i = 0; i < A_INST; ++i) {
+    int row = RPI * (wave * A_INST + i) + lr;
+    a_off[i] = (uint32_t)(((int64_t)min(m0 + row, M - 1) * lda + (lp ^ ((row >> 1) & (CH - 1))) * 8) * 2);
+  }
+#pragma unroll
+  for (int i = 0; i < W_INST; ++i) {
+    int row = RPI * (wave * W_INST + i) + lr;
+    w_off[i] = (uint32_t)(((int64_t)min(n0 + row, N - 1) * ldw + (lp ^ ((row >> 1) & (CH - 1))) * 8) * 2);
+  }
+  const uint32_t sA_lds = (uint32_t)(uintptr_t)sA, sW_lds = (uint32_t)(uintptr_t)sW;
+  auto issue_load = [&](int stage, int k0, int idx) {
+    const bool is_a = idx < A_INST;
+    const int li = is_a ? idx : idx - A_INST;
+    const char* base = (is_a ? (const char*)A : (const char*)W) + (int64_t)k0 * 2;
+    const uint32_t voff = is_a ? a_off[li] : w_off[li];
+    const uint32_t dst = is_a ? sA_lds + (uint32_t)(stage * BM * BK + RPI * (wave * A_INST + li) * BK) * 2
+                              : sW_lds + (uint32_t)(stage * BN * BK + RPI * (wave * W_INST + li) * BK) * 2;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(dst), "v"(voff), "s"(base)
+                 : "memory", "m0");
+  };
+
+  f32x4 acc[TN][TM];
+#pragma unroll
+  for (int j = 0; j < TN; ++j)
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) acc[j][i][r] = 0.f;
+
+  // fragment f of a k-step, in the order the MFMAs (j outer, i inner) first need them: W 0, X 0..TM-1, W 1..TN-1
+  const int frow = lane & 15, fq = lane >> 4;
+  bf16x8 xs[2][TM], ws[2][TN];
+  auto read_frag = [&](const bf16_t* a_s, const bf16_t* w_s, int ks, int f) {
+    const int ch = ks * 4 + fq;
+    if (f == 0) ws[ks][0] = *(const bf16x8*)(w_s + slot(wn * WTN + frow, ch));
+    else if (f <= TM) xs[ks][f - 1] = *(const bf16x8*)(a_s + slot(wm * WTM + (f - 1) * 16 + frow, ch));
+    else ws[ks][f - TM] = *(const bf16x8*)(w_s + slot(wn * WTN + (f - TM) * 16 + frow, ch));
+  };
+
+  const int n_kt = K / BK;
+#pragma unroll
+  for (int i = 0; i < PER_TILE; ++i) issue_load(0, 0, i);
+  if (n_kt > 1) {
+#pragma unroll
+    for (int i = 0; i < PER_TILE; ++i) issue_load(1, BK, i);
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PER_TILE) : "memory");
+  } else {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  }
+  __syncthreads();
+#pragma unroll
+  for (int f = 0; f < NF; ++f) read_frag(sA, sW, 0, f);
+
+  constexpr int LD = PER_TILE / 2;  // loads per wave in each half of k-step 1
+  auto tile_step = [&](int t, auto has_next, auto has_next2) {
+    const int stage = t & 1;
+    const bf16_t* a_s = sA + stage * BM * BK;
+    const bf16_t* w_s = sW + stage * BN * BK;
+    const bf16_t* a_n = sA + (stage ^ 1) * BM * BK;
+    const bf16_t* w_n = sW + (stage ^ 1) * BN * BK;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      if (ks == 1) {
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+          const int m = j * TM + i;
+          if (ks == 1 && m == NM / 2) {
+            if (has_next2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LD) : "memory");
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+          }
+          // fragment reads between the MFMAs: k-step 1's during k-step 0 (done a quarter before its end), the
+          // next tile's first ones during the second half of k-step 1
+          if (ks == 0 && m >= 1) {
+            constexpr int D = NM * 3 / 4 - 1;
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int f = min(NF, (m - 1) * NF / D); f < min(NF, m * NF / D); ++f) read_frag(a_s, w_s, 1, f);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+          if (ks == 1 && has_next && m > NM / 2) {
+            constexpr int D = NM / 2 - 2;
+            const int mm = m - NM / 2;
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int f = min(NF, (mm - 1) * NF / D); f < min(NF, mm * NF / D); ++f) read_frag(a_n, w_n, 0, f);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+          acc[j][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ws[ks][j], xs[ks][i], acc[j][i], 0, 0, 0);
+          if (ks == 1 && has_next2) {
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int q = m * PER_TILE / NM; q < (m + 1) * PER_TILE / NM; ++q) issue_load(stage, (t + 2) * BK, q);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  int t = 0;
+  for (; t + 2 < n_kt; ++t) tile_step(t, std::true_type{}, std::true_type{});
+  if (t + 1 < n_kt) { tile_step(t, std::true_type{}, std::false_type{}); ++t; }
+  if (t < n_kt) tile_step(t, std::false_type{}, std::false_type{});
+
+  // ---- epilogue through the wave's own LDS region, 32 rows at a time (as in the 32x32 kernel) ----
+  constexpr int ROW_F = 64 + 4;
+  float* stage_f = (float*)smem_raw + wave * (32 * ROW_F);
+  static_assert(NW * 32 * ROW_F * 4 <= NSTAGE * (BM + BN) * BK * 2, "staging region fits the tile ring");
+  const bool swiglu = (epi & EPI_SWIGLU) != 0;
+  int lane_e = lane;
+  asm volatile("" : "+v"(lane_e));  // indices derived after the k loop: not kept in registers across it
+  const int er = lane_e & 15, eq = lane_e >> 4;
+  const int rr = lane_e >> 4, c4 = (lane_e & 15) * 4;
+  const int rr_s = lane_e >> 3, c4_s = (lane_e & 7) * 4;
+#pragma unroll
+  for (int ib = 0; ib < TM / 2; ++ib) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int i = 2 * ib + h;
+      float* rowp = stage_f + (16 * h + er) * ROW_F + 4 * eq;
+      if (swiglu) {
+        // gate rows are the first 32 W rows of the wave's 64, up rows the next 32: tiles j and j + TN/2
+#pragma unroll
+        for (int j = 0; j < TN / 2; ++j) {
+          f32x4 o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float g = acc[j][i][e], u = acc[j + TN / 2][i][e];
+            const float sig = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * g));
+            o[e] = g * sig * u;
+          }
+          *(f32x4*)(rowp + 16 * j) = o;
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) *(f32x4*)(rowp + 16 * j) = acc[j][i];
+      }
+    }
+    __builtin_amdgcn_wave_barrier();
+    const int mb = m0 + wm * WTM + ib * 32;
+    if (swiglu) {
+      const int fb = (n0 + wn * WTN) / 2;
+#pragma unroll
+      for (int it = 0; it < 4; ++it) {
+        const int r = it * 8 + rr_s, m = mb + r, f = fb + c4_s;
+        const f32x4 v = *(const f32x4*)(stage_f + r * ROW_F + c4_s);
+        if (m < M && f < N / 2) {
+          bf16x4 o;
+          o[0] = (bf16_t)v[0]; o[1] = (bf16_t)v[1]; o[2] = (bf16_t)v[2]; o[3] = (bf16_t)v[3];
+          *(bf16x4*)((bf16_t*)C + (int64_t)m * ldc + f) = o;
+        }
+      }
+    } else {
+      const int n = n0 + wn * WTN + c4;
+      f32x4 res[8];
+      if (epi & EPI_RESIDUAL) {
+#pragma unroll
+        for (int it = 0; it < 8; ++it) {
+          const int m = min(mb + it * 4 + rr, M - 1), nn = min(n, N - 4);
+          if (epi & EPI_R_F32) {
+            res[it] = *(const f32x4*)((const float*)R + (int64_t)m * ldr + nn);
+          } else {
+            const bf16x4 rb = *(const bf16x4*)((const bf16_t*)R + (int64_t)m * ldr + nn);
+            res[it][0] = (float)rb[0]; res[it][1] = (float)rb[1]; res[it][2] = (float)rb[2]; res[it][3] = (float)rb[3];
+          }
+        }
+      }
+#pragma unroll
+      for (int it = 0; it < 8; ++it) {
+        const int r = it * 4 + rr, m = mb + r;
+        f32x4 v = *(const f32x4*)(stage_f + r * ROW_F + c4);
+        if (epi & EPI_RESIDUAL) v += res[it];
+        if (m < M && n < N) store_quad(C, ldc, nullptr, 0, m, n, v, epi & ~(EPI_RESIDUAL | EPI_R_F32));
+      }
+    }
+    __builtin_amdgcn_wave_barrier();
+  }
+}
+
 // C[m][n] = bf16( sum_s P[s][m][n] (+ R[m][n]) ), the partials added in split order.
 __global__ void __launch_bounds__(256) splitk_reduce_kernel(const float* __restrict__ P, void* __restrict__ C, int64_t ldc,
                                                             const void* __restrict__ R, int64_t ldr, int M, int N,
@@ -610,6 +844,23 @@ hipError_t launch(const void* A, int64_t lda, const void* W, int64_t ldw, void* 
   return hipGetLastError();
 }
 
+template <int BM, int BN, int WAVES_M, int WAVES_N>
+hipError_t launch16(const void* A, int64_t lda, const void* W, int64_t ldw, void* C, int64_t ldc, const void* R, int64_t ldr,
+                    int M, int N, int K, int epi, hipStream_t s) {
+  auto kern = gemm16_bf16_kernel<BM, BN, WAVES_M, WAVES_N>;
+  constexpr int lds = NSTAGE * (BM + BN) * BK * 2;
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(WAVES_M * WAVES_N * 64), lds, s, (const bf16_t*)A, lda,
+                     (const bf16_t*)W, ldw, C, ldc, R, ldr, M, N, K, epi, tiles_m, tiles_n);
+  return hipGetLastError();
+}
+
 int g_variant = 0;
 
 }  // namespace
@@ -674,8 +925,10 @@ hipError_t launch_gemm_mfma_bf16(const void* A, int64_t lda, const void* W, int6
                          (const float*)ws, (bf16_t*)C, ldc, M, N, splits);
       return hipGetLastError();
     }
+    if (variant == 5) return launch<256, 256, 2, 4, false, 1>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
+    if (variant == 6) return launch16<128, 128, 2, 2>(A, lda, W, ldw, C, ldc, R, ldr, M, N, K, epi, s);
     if ((int64_t)((M + 255) / 256) * ((N + 255) / 256) >= 192 || variant == 1)
-      return launch<256, 256, 2, 4, false, 1>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
+      return launch16<256, 256, 2, 4>(A, lda, W, ldw, C, ldc, R, ldr, M, N, K, epi, s);
     return launch<128, 128, 2, 2, false, 1>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
   }
   // A few hundred token rows: too few 128 x 128 tiles to fill the chip, so K is split over workgroups as on the
@@ -718,9 +971,15 @@ hipError_t launch_gemm_mfma_bf16(const void* A, int64_t lda, const void* W, int6
       }
       return launch<64, 64, 1, 2, false>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
     }
+    // what the library picks: the 256x256 tile on the 16x16x32 MFMA (default; power-limited there, and that
+    // instruction is the thriftier one) and the 128x128 tile on the 32x32x16 MFMA (2: medium sizes are issue- and
+    // latency-bound, where it is 15-30 % faster).  For tests and comparisons: 4, 5 = 256x256 on 32x32x16 with the
+    // one-barrier schedule / the early-freed stage, 6 = 128x128 on 16x16x32.
     case 2: return launch<128, 128, 2, 2, false, 1>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
     case 4: return launch<256, 256, 2, 4, false, 0>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
-    default: return launch<256, 256, 2, 4, false, 1>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
+    case 5: return launch<256, 256, 2, 4, false, 1>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
+    case 6: return launch16<128, 128, 2, 2>(A, lda, W, ldw, C, ldc, R, ldr, M, N, K, epi, s);
+    default: return launch16<256, 256, 2, 4>(A, lda, W, ldw, C, ldc, R, ldr, M, N, K, epi, s);
   }
 }
 

@@ -37,10 +37,10 @@ def test_linear_bf16(B, M, N, K, residual):
     assert O.max_rel_err(y.float().cpu().numpy(), ref) <= 2 ** -8
 
 
-# every tiling of the prefill GEMM (1: 256x256 with the early-freed stage, 4: 256x256 with one barrier per k-tile,
-# 2: 128x128) forced on shapes with 1, 2, 3 and 7 k-tiles (the peeled head and tail of the software pipeline),
-# ragged M and N, with and without residual
-@pytest.mark.parametrize("variant", [1, 4, 2])
+# every tiling of the prefill GEMM (1, 6: 256x256 and 128x128 on the 16x16x32 MFMA; 5, 2: the same tiles on the
+# 32x32x16 MFMA with the early-freed stage; 4: 256x256 with one barrier per k-tile) forced on shapes with 1, 2, 3
+# and 7 k-tiles (the peeled head and tail of the software pipeline), ragged M and N, with and without residual
+@pytest.mark.parametrize("variant", [1, 2, 4, 5, 6])
 @pytest.mark.parametrize("M,N,K,residual", [(300, 516, 64, False), (257, 512, 128, True), (513, 260, 192, False),
                                             (700, 1028, 448, True)])
 def test_linear_bf16_forced_tiling(B, variant, M, N, K, residual):
