@@ -1,7 +1,9 @@
 // bf16 MFMA GEMM for gfx950:  C[M,N] = A[M,K] * W[N,K]^T  (+ R), fp32 accumulation, bf16 output.
 //
-// Both operands are K-contiguous, so both feed v_mfma_f32_32x32x16_bf16 with 16-byte vectors and no
-// transposition.  A workgroup owns a BM x BN tile of C and walks K in steps of 64 through a two-stage
+// Both operands are K-contiguous, so both feed the MFMA with 16-byte vectors and no transposition.  Two
+// kernels: gemm16_bf16_kernel on v_mfma_f32_16x16x32_bf16 for the large prefill problems (256 x 256 tile; the chip
+// is power-limited there and that instruction takes less energy per flop), gemm_bf16_kernel on
+// v_mfma_f32_32x32x16_bf16 for everything else (128 x 128 tile, K-split tiles for few rows).  A workgroup owns a BM x BN tile of C and walks K in steps of 64 through a two-stage
 // LDS ring filled by direct global->LDS loads (global_load_lds_dwordx4: no staging registers, no
 // ds_write).  The loads of k-tile kt+2 go out, between MFMAs, as soon as a barrier shows that every wave
 // has read k-tile kt out of the stage they overwrite; fragments are read from LDS one or two k-steps ahead
@@ -15,7 +17,8 @@
 // touch 16 different 16-byte bank groups of the 256-byte LDS line.
 //
 // W rows play the MFMA "A" role and activation rows the "B" role: a lane then holds four consecutive
-// output columns of one row in four consecutive accumulator registers and stores them as 8 bytes.
+// output columns of one row in four consecutive accumulator registers (the epilogue regroups them through LDS so
+// that stores cover whole rows of the tile).
 // Workgroup ids are remapped so that each XCD (own L2) works on a compact patch of the tile grid.
 //
 // Small M (the suffix pass: tens of rows) is a weight-streaming problem: a 64 x 64 tile, K split over
