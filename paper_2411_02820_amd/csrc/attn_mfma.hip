@@ -48,9 +48,12 @@ struct AttnParams {
 // MFMA row of key offset u inside a 64-key tile: bits 2 and 3 swapped (an involution)
 __device__ __forceinline__ int perm_key(int u) { return (u & ~0xC) | ((u & 4) << 1) | ((u & 8) >> 1); }
 
-template <int DH, bool SPLIT, int NW>
+// PACK (few queries per sequence, several q heads per kv head): the NW waves of a workgroup take the same 32
+// query rows of NW different q heads of one kv group instead of 32*NW rows of one head, so that no wave idles on
+// rows past the end of a short sequence and the K / Vt tiles of the group are loaded once for NW heads.
+template <int DH, bool SPLIT, int NW, bool PACK = false>
 __global__ void __launch_bounds__(64 * NW, 8 / NW) attn_bf16_kernel(AttnParams p) {
-  constexpr int BQ = 32 * NW;             // query rows per workgroup: 32 per wave
+  constexpr int BQ = PACK ? 32 : 32 * NW;  // query rows per workgroup: 32 per wave
   constexpr int KCH = DH / 8;             // 16-byte slots per K row
   constexpr int K_RPI = 64 / KCH;         // K rows per wave load instruction
   constexpr int K_INST = BKV / K_RPI / NW; // per wave
@@ -69,7 +72,12 @@ __global__ void __launch_bounds__(64 * NW, 8 / NW) attn_bf16_kernel(AttnParams p
   //      that is a multiple of 8 each XCD serves a fixed eighth of the heads, so the q heads of one kv group
   //      read their K and Vt through the same L2. ----
   int h, rank;
-  {
+  if (PACK) {
+    const int quads = p.Hq / NW;  // groups of NW q heads, all within one kv group (the host checks (Hq/Hkv) % NW == 0)
+    const int L = blockIdx.x;
+    h = (L % quads) * NW + wave;
+    rank = L / quads;
+  } else {
     const int L = blockIdx.x;
     if ((p.Hq & 7) == 0) {
       const int hpx = p.Hq >> 3, j = L >> 3;
@@ -92,7 +100,7 @@ __global__ void __launch_bounds__(64 * NW, 8 / NW) attn_bf16_kernel(AttnParams p
   }
   const int q0 = seq_begin + tile * BQ;  // first query row (packed index) of this workgroup
   if (q0 >= seq_end) return;              // cannot happen for a well-formed grid
-  const int qw0 = q0 + 32 * wave;         // first query row of this wave
+  const int qw0 = PACK ? q0 : q0 + 32 * wave;  // first query row of this wave
   const bool wave_active = qw0 < seq_end;
   const int qi = min(qw0 + lq, seq_end - 1);  // this lane's query (clamped for the padding rows)
 
@@ -508,9 +516,9 @@ hipError_t launch_transpose_v(const void* v_rows, void* vt, int64_t ldvt, int wi
   return hipGetLastError();
 }
 
-template <int DH, bool SPLIT, int NW>
+template <int DH, bool SPLIT, int NW, bool PACK = false>
 hipError_t launch_attn(const AttnParams& p, dim3 grid, hipStream_t s) {
-  auto kern = attn_bf16_kernel<DH, SPLIT, NW>;
+  auto kern = attn_bf16_kernel<DH, SPLIT, NW, PACK>;
   constexpr int lds = (2 * BKV * DH + 2 * DH * BKV) * 2;
   static bool configured = false;
   if (!configured) {
@@ -541,39 +549,50 @@ hipError_t launch_attn_mfma_bf16(const AttnArgs& a, hipStream_t s) {
     return t;
   };
   constexpr int nw = 4;
-  const int bq = 32 * nw;
-  int total = (int)count_tiles(bq);
   int64_t max_keys = 0;
+  int max_len = 0;
   for (int b = 0; b < a.n_seqs; ++b) {
     const int len = a.q_cu_host[b + 1] - a.q_cu_host[b];
     int64_t keys = len + (a.p_cu_host ? a.p_cu_host[b + 1] - a.p_cu_host[b] : 0);
     if (keys > max_keys) max_keys = keys;
+    if (len > max_len) max_len = len;
   }
-  p.total_tiles = total;
+  // sequences of at most 64 queries would leave half of a 128-row workgroup idle: there the four waves take four
+  // q heads of a kv group and 32 rows each (the key-split path only; needs four heads per kv group)
+  bool pack = a.ws && a.dh == 128 && max_len <= 64 && (a.Hq / a.Hkv) % nw == 0 && g_variant != 2;
   p.c = (float)(1.4426950408889634 / sqrt((double)a.dh));
   p.k_row_max = (int)(a.own_row0 + a.n_q - 1);
-  // split the key tiles when the grid alone cannot fill the chip
-  int splits = 1;
-  const int64_t blocks = (int64_t)total * a.Hq;
   const int key_tiles = (int)((max_keys + BKV - 1) / BKV) + 1;
-  if (a.ws && blocks < 512 && key_tiles >= 8) {
-    // about two workgroups per CU; measured on 64 queries against 8k and 16k keys: 16 splits beat 8 and 32
-    // (more splits pay more for partial outputs and the per-workgroup start-up than they gain in parallelism)
-    splits = (int)((512 + blocks - 1) / blocks);
-    if (splits > key_tiles / 4) splits = key_tiles / 4;
-    while (splits > 1 && ((int64_t)a.n_q * splits > kMaxSplitRows ||
-                          (int64_t)a.n_q * splits * a.Hq * (a.dh + 2) * 4 > a.ws_bytes))
-      --splits;
+  int total = 0, splits = 1;
+  int64_t blocks = 0;
+  for (;;) {
+    total = (int)count_tiles(pack ? 32 : 32 * nw);
+    blocks = pack ? (int64_t)total * (a.Hq / nw) : (int64_t)total * a.Hq;
+    // split the key tiles when the grid alone cannot fill the chip
+    splits = 1;
+    if (a.ws && blocks < 512 && key_tiles >= 8) {
+      // about two workgroups per CU; measured on 64 queries against 8k and 16k keys: 16 splits beat 8 and 32
+      // (more splits pay more for partial outputs and the per-workgroup start-up than they gain in parallelism)
+      splits = (int)(((pack ? 256 : 512) + blocks - 1) / blocks);
+      if (splits > key_tiles / 4) splits = key_tiles / 4;
+      while (splits > 1 && ((int64_t)a.n_q * splits > kMaxSplitRows ||
+                            (int64_t)a.n_q * splits * a.Hq * (a.dh + 2) * 4 > a.ws_bytes))
+        --splits;
+    }
+    if (g_variant == 1) splits = 1;
+    if (pack && splits <= 1) { pack = false; continue; }  // the packed mapping exists for the key-split kernel only
+    break;
   }
-  if (g_variant == 1) splits = 1;
+  p.total_tiles = total;
   p.splits = splits;
   p.part_o = nullptr;
   p.part_ml = nullptr;
   if (splits > 1) {
     p.part_o = (float*)a.ws;
     p.part_ml = p.part_o + (int64_t)a.n_q * a.Hq * splits * a.dh;
-    dim3 grid((unsigned)total * a.Hq, 1, splits);
-    hipError_t e = a.dh == 128 ? launch_attn<128, true, 4>(p, grid, s) : launch_attn<64, true, 4>(p, grid, s);
+    dim3 grid((unsigned)blocks, 1, splits);
+    hipError_t e = pack ? launch_attn<128, true, 4, true>(p, grid, s)
+                        : a.dh == 128 ? launch_attn<128, true, 4>(p, grid, s) : launch_attn<64, true, 4>(p, grid, s);
     if (e != hipSuccess) return e;
     dim3 cgrid(a.n_q, a.Hq);
     if (a.dh == 128)
