@@ -288,7 +288,11 @@ DSK_API int dsk_attention(int dtype, const void* q, const void* k_rows, const vo
 DSK_API int dsk_measure_mfma_peak(double* tflops, void* stream);
 
 /* Integer knobs for benchmarks and tests; unknown names return DSK_EINVAL.
- *   "gemm_variant", "attn_variant": pick a kernel tiling (default 0 = what the library picks by itself)
+ *   "gemm_variant": force a tiling of the bf16 GEMM for M > 64 (default 0 = what the library picks by itself):
+ *                1 = 256x256 on the 16x16x32 MFMA, 2 = 128x128 on the 32x32x16 MFMA (the two it picks from),
+ *                4 / 5 = 256x256 on 32x32x16 with one / two barriers per k-tile, 6 = 128x128 on 16x16x32
+ *   "attn_variant": 1 = never split the keys of the bf16 attention over workgroups, 2 = split but do not pack the
+ *                q heads of a kv group into one workgroup (default 0 = both when few queries meet many keys)
  *   "force_generic": 1 = use the plain-ALU kernels even for bf16
  *   "time_gemm": 1 = bracket every tensor-core GEMM launch that runs on the 256 x 256 prefill tiling (at least
  *                192 such tiles) by a pair of HIP events on its stream (read back through dsk_get_stat)
