@@ -301,7 +301,9 @@ DSK_API int dsk_measure_mfma_peak(double* tflops, void* stream);
 DSK_API int dsk_set_option(const char* name, int value);
 
 /* Counters since the last reset: "gemm_mfma_launches", "gemm_generic_launches", "attn_mfma_launches",
- * "attn_generic_launches"; and for the launches bracketed under "time_gemm": "timed_gemm_launches",
+ * "attn_generic_launches", "attn_key_split_launches" (tensor-core attention launches that split the keys over
+ * workgroups) and, of those, "attn_packed_head_launches" (four q heads of a kv group per workgroup); and for the
+ * launches bracketed under "time_gemm": "timed_gemm_launches",
  * "timed_gemm_ms" (sum of their durations; waits for them to finish), "timed_gemm_flops" (sum of 2*M*N*K). */
 DSK_API int dsk_get_stat(const char* name, double* value);
 

@@ -502,6 +502,14 @@ int g_variant = 0;
 
 void attn_mfma_set_variant(int v) { g_variant = v; }
 
+// how many launches took the key-split path, and how many of those with four q heads packed per workgroup
+static int64_t g_split_launches = 0, g_packed_launches = 0;
+void attn_mfma_counts(int64_t* split, int64_t* packed, int reset) {
+  if (split) *split = g_split_launches;
+  if (packed) *packed = g_packed_launches;
+  if (reset) g_split_launches = g_packed_launches = 0;
+}
+
 // fp32 scratch for the split mode: n_q * splits <= kMaxSplitRows partial rows of (dh + 2) floats per q head
 constexpr int64_t kMaxSplitRows = 4096;
 int64_t attn_mfma_workspace_bytes(int Hq, int dh) { return kMaxSplitRows * Hq * (dh + 2) * 4; }
@@ -591,6 +599,8 @@ hipError_t launch_attn_mfma_bf16(const AttnArgs& a, hipStream_t s) {
     p.part_o = (float*)a.ws;
     p.part_ml = p.part_o + (int64_t)a.n_q * a.Hq * splits * a.dh;
     dim3 grid((unsigned)blocks, 1, splits);
+    ++g_split_launches;
+    if (pack) ++g_packed_launches;
     hipError_t e = pack ? launch_attn<128, true, 4, true>(p, grid, s)
                         : a.dh == 128 ? launch_attn<128, true, 4>(p, grid, s) : launch_attn<64, true, 4>(p, grid, s);
     if (e != hipSuccess) return e;

@@ -671,6 +671,7 @@ int dsk_set_option(const char* name, int value) {
     g_stats.gemm_mfma = g_stats.gemm_generic = g_stats.attn_mfma = g_stats.attn_generic = 0;
     g_stats.n_timed = 0;
     g_stats.timed_flops = 0.0;
+    attn_mfma_counts(nullptr, nullptr, 1);
   } else return DSK_EINVAL;
   return DSK_OK;
 }
@@ -681,6 +682,11 @@ int dsk_get_stat(const char* name, double* value) {
   else if (!strcmp(name, "gemm_generic_launches")) *value = (double)g_stats.gemm_generic;
   else if (!strcmp(name, "attn_mfma_launches")) *value = (double)g_stats.attn_mfma;
   else if (!strcmp(name, "attn_generic_launches")) *value = (double)g_stats.attn_generic;
+  else if (!strcmp(name, "attn_key_split_launches") || !strcmp(name, "attn_packed_head_launches")) {
+    int64_t split = 0, packed = 0;
+    attn_mfma_counts(&split, &packed, 0);
+    *value = (double)(name[5] == 'k' ? split : packed);
+  }
   else if (!strcmp(name, "timed_gemm_launches")) *value = (double)g_stats.n_timed;
   else if (!strcmp(name, "timed_gemm_flops")) *value = g_stats.timed_flops;
   else if (!strcmp(name, "timed_gemm_ms")) {

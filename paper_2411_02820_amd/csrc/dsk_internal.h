@@ -135,5 +135,6 @@ hipError_t launch_fill_weight(int dtype, void* packed, int64_t rows, int64_t col
 
 // tuning knobs (dsk_set_option)
 void gemm_mfma_set_variant(int v);
+void attn_mfma_counts(int64_t* split, int64_t* packed, int reset);
 bool gemm_mfma_uses_prefill_tile(int M, int N);
 void attn_mfma_set_variant(int v);

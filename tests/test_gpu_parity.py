@@ -16,6 +16,7 @@ TOL = {"f32": 1e-3, "bf16": 2e-2}
 
 SMALL_BF16 = synth.ModelShape(3, 512, 8, 2, 128, 1536, 500000.0, 1e-5, "bf16")
 SMALL_BF16_DH64 = synth.ModelShape(2, 256, 4, 4, 64, 512, 10000.0, 1e-5, "bf16")
+SMALL_BF16_G8 = synth.ModelShape(2, 512, 16, 2, 128, 1024, 500000.0, 1e-5, "bf16")
 
 
 @pytest.fixture(scope="module")
@@ -113,6 +114,31 @@ def test_small_bf16_strong_weights_ragged(G):
 
 def test_small_bf16_dh64(G):
     run_case(G, SMALL_BF16_DH64, [257, 64], 0, 2, [31, 2], 2.0)
+
+
+# suffix attention with the keys split over workgroups (few queries against >= 7 key tiles): four q heads of a kv
+# group packed into one workgroup (sequences of at most 64 queries; 4 and 8 heads per kv group), and unpacked
+def _split_counts(G, fn):
+    from paper_2411_02820_amd import binding as B
+    B.dsk_set_option("reset_stats", 0)
+    fn()
+    return B.dsk_get_stat("attn_key_split_launches"), B.dsk_get_stat("attn_packed_head_launches")
+
+
+def test_small_bf16_key_split_packed_heads(G):
+    split, packed = _split_counts(G, lambda: run_case(G, SMALL_BF16, [700], 1, 3, [40], None))
+    # the suffix pass of every layer packs; the prefix pass (700 queries) splits the keys too, unpacked
+    assert packed == SMALL_BF16.n_layers and split > packed
+
+
+def test_small_bf16_key_split_packed_heads_group_of_8_ragged(G):
+    split, packed = _split_counts(G, lambda: run_case(G, SMALL_BF16_G8, [600, 450], 0, 2, [40, 9], 2.0))
+    assert packed == SMALL_BF16_G8.n_layers and split > packed
+
+
+def test_small_bf16_key_split_unpacked(G):
+    split, packed = _split_counts(G, lambda: run_case(G, SMALL_BF16, [700], 1, 3, [100], None))
+    assert split >= SMALL_BF16.n_layers and packed == 0
 
 
 def test_pure_splice_and_aliasing(G):
