@@ -291,11 +291,11 @@ def main():
             B.dsk_set_load_mode(model, B.DSK_LOAD_PIPELINED)
             extra["load_sweep"] = sweep
     if args.fit_latency and len(lens) == 1:
-        # App. B: "the parameters for estimation can be obtained through the profiling phase".  Profile the joined
+        # App. B takes the estimate's parameters from the profiling phase.  Profile the joined
         # selective prefill at three token counts x three depths, least-squares fit of
         # t = c0 + R (c1 T + c2 T^2) + (L - R) c3 T, then ask the library's policy for a synthetic frontier.
-        import numpy as np
-        rows_fit, t_fit = [], []
+        from paper_2411_02820_amd.latency_fit import fit_latency_model
+        points = []
         for Tn in (T // 4, T // 2, T):
             pb = B.Batch(synth.cu_seqlens([Tn]), synth.packed_positions([Tn]))
             for R in sorted({min(2, L), min(4, L), min(8, L)}):
@@ -303,17 +303,9 @@ def main():
                 def f():
                     B.dsk_partial_prefill(model, hidden_in, a, a + R, kv_r, kv_o, pb.desc, None, 0)
                 f()
-                ms = time_region(torch, f, 2)
-                rows_fit.append([1.0, R * Tn, R * Tn * Tn, (L - R) * Tn])
-                t_fit.append(ms)
-        A = np.array(rows_fit)
-        y = np.array(t_fit)
-        # scale the columns so that the least-squares problem is well conditioned
-        scale = A.max(axis=0)
-        from scipy.optimize import nnls   # costs cannot be negative
-        coef = nnls(A / scale, y)[0] / scale
-        lat = tuple(float(c) for c in coef)
-        resid = float(np.max(np.abs(A @ coef - y) / y))
+                points.append((Tn, R, time_region(torch, f, 2)))
+        lat, resid = fit_latency_model(points, L)
+        t_fit = points
         frontier = [(lo, min(lo + r, L), q) for r, q in ((0, 0.30), (2, 0.55), (4, 0.70), (8, 0.78))] + [(0, L, 0.82)]
         full_ms = B.dsk_estimate_prefill_ms(lat, L, L, T)
         picks = []
@@ -329,7 +321,8 @@ def main():
                                   "frontier": "synthetic (quality values are placeholders)"}
     flops = recompute_flops(shape, lens, hi - lo)
     # what the matrix cores of this machine sustain in a register-only loop (bf16), right after the measurements
-    peak_measured = B.dsk_measure_mfma_peak()
+    from paper_2411_02820_amd import diag
+    peak_measured = diag.dsk_diag_mfma_peak()
     extra.update({
         "partial_prefill_ms": round(t_partial, 3), "suffix_prefill_ms": round(t_suffix, 3),
         "ttft_ms": round(t_partial + t_suffix, 3), "phase_timing": PHASE_TIMES,

@@ -45,7 +45,8 @@ typedef struct dsk_model dsk_model_t;
 typedef enum {
   DSK_OK = 0,
   DSK_EINVAL = -1, /* null pointer, bad layer range, bad batch descriptor, misaligned pointer */
-  DSK_ESHAPE = -2, /* model shape not supported (Hq % Hkv, odd head_dim, head_dim > 256, ...) */
+  DSK_ESHAPE = -2, /* shape not supported (Hq % Hkv, odd head_dim, head_dim > 256, a bf16 shape outside what the
+                      tensor-core kernels handle, ...) */
   DSK_EDTYPE = -3, /* dtype not DSK_F32 / DSK_BF16 */
   DSK_ENOMEM = -4, /* device or host allocation failed */
   DSK_EHIP = -5,   /* a HIP call failed; see dsk_last_hip_error() */
@@ -211,7 +212,8 @@ DSK_API int dsk_set_load_throttle(dsk_model_t* model, double gb_per_s);
 typedef struct dsk_store dsk_store_t;
 typedef enum { DSK_TIER_AUTO = 0, DSK_TIER_DEVICE = 1, DSK_TIER_HOST = 2 } dsk_tier; /* AUTO: device while it fits */
 
-/* "We calculate the hash of the context text" (Sec. 4.4): 64-bit FNV-1a of the bytes. */
+/* Key of a context: 64-bit FNV-1a of the bytes of its text (Sec. 4.4 keys the store by a hash of the context
+ * text and does not name the function). */
 DSK_API uint64_t dsk_hash_context(const void* bytes, int64_t n);
 
 /* Capacities bound what each tier may hold; a put that fits nowhere returns DSK_ENOMEM. */
@@ -270,33 +272,31 @@ DSK_API int dsk_select_recompute(const dsk_frontier_point_t* frontier, int n_poi
 /* ---- component entry points: single steps of the layer, for parity tests and micro-benchmarks ---- */
 
 /* y[M,N] = x[M,K] * w[N,K]^T (+ r[M,N] if r != NULL); all device, row-major, dense rows, dtype as given.
- * The projection step of the layer (QKV, O, gate/up, down); y may alias r. */
+ * The projection step of the layer (QKV, O, gate/up, down); y may alias r.  bf16 runs on the tensor-core kernels
+ * and needs K a multiple of 64, N a multiple of 4 and M*K, N*K below 2^31 elements, else DSK_ESHAPE. */
 DSK_API int dsk_linear(int dtype, const void* x, const void* w, void* y, const void* r, int M, int N, int K, void* stream);
 
 /* Causal grouped-query attention of packed query tokens q [n_q, Hq*dh] (already rotated) against cache
  * rows k_rows/v_rows (row stride Hkv*dh): query i of sequence b sees rows prefix.cu[b]..prefix.cu[b+1]-1
  * (prefix may be NULL) and rows own_row0+queries.cu[b] .. own_row0+i.  out [n_q, Hq*dh].  All device.
- * scratch: optional device buffer of scratch_bytes >= Hkv*dh*roundup64(own_row0+n_q)*elem bytes; the bf16
- * tensor-core kernel needs it (it keeps a transposed copy of V there), without it the plain kernel runs. */
+ * prefix.n_tokens <= own_row0 (the two row ranges do not overlap), else DSK_EINVAL.
+ * scratch: device buffer of scratch_bytes >= Hkv*dh*roundup64(own_row0+n_q)*elem bytes: the bf16 tensor-core
+ * kernel keeps a transposed copy of V there.  scratch = NULL selects the plain-ALU kernel (any dtype); a bf16 call
+ * with scratch whose shape the tensor-core kernel does not handle (head_dim other than 64 or 128, Hkv*dh not a
+ * multiple of 64, scratch too small) returns DSK_ESHAPE. */
 DSK_API int dsk_attention(int dtype, const void* q, const void* k_rows, const void* v_rows, void* out,
                           const dsk_batch_t* queries, const dsk_batch_t* prefix, int64_t own_row0, int n_q_heads,
                           int n_kv_heads, int head_dim, void* scratch, int64_t scratch_bytes, void* stream);
 
-/* Matrix-core throughput this device sustains, in TFLOP/s: a register-only bf16 MFMA loop on every CU, timed with
- * events on `stream` (blocks until done; allocates and frees a small buffer).  For utilisation figures next to
- * those against the spec-sheet peak. */
-DSK_API int dsk_measure_mfma_peak(double* tflops, void* stream);
-
-/* Integer knobs for benchmarks and tests; unknown names return DSK_EINVAL.
- *   "gemm_variant": force a tiling of the bf16 GEMM for M > 64 (default 0 = what the library picks by itself):
- *                1 = 256x256 on the 16x16x32 MFMA, 2 = 128x128 on the 32x32x16 MFMA (the two it picks from),
- *                4 / 5 = 256x256 on 32x32x16 with one / two barriers per k-tile, 6 = 128x128 on 16x16x32
- *   "attn_variant": 1 = never split the keys of the bf16 attention over workgroups, 2 = split but do not pack the
- *                q heads of a kv group into one workgroup (default 0 = both when few queries meet many keys)
- *   "force_generic": 1 = use the plain-ALU kernels even for bf16
+/* ---- hooks for tests and benchmarks (process-wide, not thread-safe; no production caller needs them) ----
+ * Unknown names and out-of-range values return DSK_EINVAL.
+ *   "force_generic": 1 = bf16 work runs on the plain-ALU kernels that serve fp32 models (about a hundred times
+ *                slower).  Without it a bf16 shape the tensor-core kernels do not handle is an error (DSK_ESHAPE
+ *                from dsk_model_create, dsk_linear, dsk_attention), never a silent switch of kernels.
+ *   "gemm_tiling": force one of the two prefill tilings of the bf16 GEMM on any M > 64 (default 0 = picked by
+ *                size): 1 = 256x256 tiles on the 16x16x32 MFMA, 2 = 128x128 tiles on the 32x32x16 MFMA
  *   "time_gemm": 1 = bracket every tensor-core GEMM launch that runs on the 256 x 256 prefill tiling (at least
  *                192 such tiles) by a pair of HIP events on its stream (read back through dsk_get_stat)
- *   "linear_ld_pad": dsk_linear reads x and w with row stride K + value elements (stride experiments)
  *   "reset_stats": any value; clears all counters and recorded timings */
 DSK_API int dsk_set_option(const char* name, int value);
 

@@ -39,7 +39,7 @@ EXPORTS = (
     "dsk_join_loads", "dsk_set_load_mode", "dsk_set_load_throttle", "dsk_model_weight_bytes", "dsk_model_workspace_bytes",
     "dsk_strerror", "dsk_last_hip_error", "dsk_hash_context", "dsk_store_create", "dsk_store_destroy",
     "dsk_store_put_kv", "dsk_store_put_e", "dsk_store_fetch_kv_layer", "dsk_store_fetch_kv", "dsk_store_fetch_e",
-    "dsk_store_erase", "dsk_store_usage", "dsk_estimate_prefill_ms", "dsk_select_recompute", "dsk_linear", "dsk_attention", "dsk_set_option", "dsk_get_stat", "dsk_measure_mfma_peak",
+    "dsk_store_erase", "dsk_store_usage", "dsk_estimate_prefill_ms", "dsk_select_recompute", "dsk_linear", "dsk_attention", "dsk_set_option", "dsk_get_stat",
 )
 
 
@@ -91,7 +91,6 @@ lib.dsk_linear.argtypes = [C.c_int, _P, _P, _P, _P, C.c_int, C.c_int, C.c_int, _
 lib.dsk_attention.argtypes = [C.c_int, _P, _P, _P, _P, C.POINTER(dsk_batch_t), C.POINTER(dsk_batch_t), C.c_int64,
                               C.c_int, C.c_int, C.c_int, _P, C.c_int64, _P]
 lib.dsk_set_option.argtypes = [C.c_char_p, C.c_int]
-lib.dsk_measure_mfma_peak.argtypes = [C.POINTER(C.c_double), _P]
 lib.dsk_get_stat.argtypes = [C.c_char_p, C.POINTER(C.c_double)]
 lib.dsk_join_loads.argtypes = [_P, _P]
 lib.dsk_set_load_mode.argtypes = [_P, C.c_int]
@@ -335,12 +334,6 @@ def dsk_select_recompute(frontier, n_layers: int, n_tokens: int, lat, slo_ms: fl
     _check(lib.dsk_select_recompute(arr, len(frontier), n_layers, n_tokens, C.byref(dsk_latency_model_t(*lat)), slo_ms,
                                     quality_target, n_waiting, C.byref(chosen)), "dsk_select_recompute")
     return chosen.value
-
-
-def dsk_measure_mfma_peak(stream=None) -> float:
-    out = C.c_double(0.0)
-    _check(lib.dsk_measure_mfma_peak(C.byref(out), _stream(stream)), "dsk_measure_mfma_peak")
-    return out.value
 
 
 def dsk_model_weight_bytes(model: int) -> int:

@@ -1,4 +1,5 @@
-"""Builds libdsk.so (gfx950) from csrc/*.hip with hipcc, in-tree, next to this file."""
+"""Builds libdsk.so (gfx950) from csrc/*.hip, and libdsk_diag.so (device measurements for benchmarks) from
+csrc/diag/*.hip, with hipcc, in-tree, next to this file."""
 from __future__ import annotations
 
 import os
@@ -11,6 +12,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libdsk.so")
+DIAG_LIB = os.path.join(HERE, "libdsk_diag.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -21,15 +23,16 @@ FLAGS = [
 ]
 
 
-def sources():
-    return sorted(f for f in os.listdir(CSRC) if f.endswith(".hip"))
+def sources(sub: str = ""):
+    d = os.path.join(CSRC, sub)
+    return sorted(os.path.join(sub, f) for f in os.listdir(d) if f.endswith(".hip"))
 
 
 def _compile(src: str, force: bool) -> str:
-    obj = os.path.join(OBJ_DIR, src[:-4] + ".o")
+    obj = os.path.join(OBJ_DIR, src[:-4].replace(os.sep, "_") + ".o")
     spath = os.path.join(CSRC, src)
     deps = [spath] + [os.path.join(CSRC, h) for h in os.listdir(CSRC) if h.endswith(".h")]
-    deps.append(os.path.join(ROOT, "include", "dsk.h"))
+    deps += [os.path.join(ROOT, "include", h) for h in os.listdir(os.path.join(ROOT, "include"))]
     if not force and os.path.exists(obj) and all(os.path.getmtime(obj) >= os.path.getmtime(d) for d in deps):
         return obj
     cmd = [HIPCC, *FLAGS, "-c", spath, "-o", obj]
@@ -43,14 +46,20 @@ def _compile(src: str, force: bool) -> str:
     return obj
 
 
-def build(force: bool = True, jobs: int = 8) -> str:
-    os.makedirs(OBJ_DIR, exist_ok=True)
-    with ThreadPoolExecutor(jobs) as ex:
-        objs = list(ex.map(lambda s: _compile(s, force), sources()))
-    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+def _link(lib: str, objs) -> None:
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stdout}\n{r.stderr}")
+
+
+def build(force: bool = True, jobs: int = 8) -> str:
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    main, diag = sources(), sources("diag")
+    with ThreadPoolExecutor(jobs) as ex:
+        objs = list(ex.map(lambda s: _compile(s, force), main + diag))
+    _link(LIB, objs[:len(main)])
+    _link(DIAG_LIB, objs[len(main):])
     return LIB
 
 

@@ -496,11 +496,7 @@ __global__ void __launch_bounds__(256) transpose_v_kernel(const bf16_t* __restri
   }
 }
 
-int g_variant = 0;
-
 }  // namespace
-
-void attn_mfma_set_variant(int v) { g_variant = v; }
 
 // how many launches took the key-split path, and how many of those with four q heads packed per workgroup
 static int64_t g_split_launches = 0, g_packed_launches = 0;
@@ -567,7 +563,7 @@ hipError_t launch_attn_mfma_bf16(const AttnArgs& a, hipStream_t s) {
   }
   // sequences of at most 64 queries would leave half of a 128-row workgroup idle: there the four waves take four
   // q heads of a kv group and 32 rows each (the key-split path only; needs four heads per kv group)
-  bool pack = a.ws && a.dh == 128 && max_len <= 64 && (a.Hq / a.Hkv) % nw == 0 && g_variant != 2;
+  bool pack = a.ws && a.dh == 128 && max_len <= 64 && (a.Hq / a.Hkv) % nw == 0;
   p.c = (float)(1.4426950408889634 / sqrt((double)a.dh));
   p.k_row_max = (int)(a.own_row0 + a.n_q - 1);
   const int key_tiles = (int)((max_keys + BKV - 1) / BKV) + 1;
@@ -587,7 +583,6 @@ hipError_t launch_attn_mfma_bf16(const AttnArgs& a, hipStream_t s) {
                             (int64_t)a.n_q * splits * a.Hq * (a.dh + 2) * 4 > a.ws_bytes))
         --splits;
     }
-    if (g_variant == 1) splits = 1;
     if (pack && splits <= 1) { pack = false; continue; }  // the packed mapping exists for the key-split kernel only
     break;
   }

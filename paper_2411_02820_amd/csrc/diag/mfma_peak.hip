@@ -1,7 +1,10 @@
-// Measured matrix-core peak of the device the library runs on: a register-only loop of
-// v_mfma_f32_32x32x16_bf16 on independent accumulators, two waves per SIMD on every CU.  bench.py quotes
-// utilisation against this figure next to the one against the spec-sheet peak.
-#include "dsk_internal.h"
+// libdsk_diag: measurements of the device itself, kept out of the product library (libdsk.so).
+// Matrix-core peak: a register-only loop of v_mfma_f32_32x32x16_bf16 on independent accumulators, two waves per
+// SIMD on every CU.  bench.py quotes utilisation against this figure next to the one against the spec-sheet peak.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "dsk_diag.h"
 
 namespace {
 
@@ -37,8 +40,8 @@ __global__ void __launch_bounds__(kProbeThreads) mfma_peak_kernel(float* __restr
 
 }  // namespace
 
-extern "C" int dsk_measure_mfma_peak(double* tflops, void* stream) {
-  if (!tflops) return DSK_EINVAL;
+extern "C" int dsk_diag_mfma_peak(double* tflops, void* stream) {
+  if (!tflops) return -1;
   hipStream_t s = (hipStream_t)stream;
   int dev = 0, n_cu = 0;
   hipError_t e = hipGetDevice(&dev);
@@ -62,11 +65,8 @@ extern "C" int dsk_measure_mfma_peak(double* tflops, void* stream) {
   if (t0) (void)hipEventDestroy(t0);
   if (t1) (void)hipEventDestroy(t1);
   if (out) (void)hipFree(out);
-  if (e != hipSuccess) {
-    g_last_hip_error = (int)e;
-    return DSK_EHIP;
-  }
+  if (e != hipSuccess) return -5;
   const double flops = (double)blocks * (kProbeThreads / 64) * (double)iters * kMfmaPerIter * 2.0 * 32 * 32 * 16;
   *tflops = flops / ((double)ms * 1e-3) / 1e12;
-  return DSK_OK;
+  return 0;
 }

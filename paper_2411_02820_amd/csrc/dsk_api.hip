@@ -11,13 +11,15 @@ thread_local int g_last_hip_error = 0;  // shared with the cache store
 
 namespace {
 
-#define HIP_TRY(expr)                          \
-  do {                                         \
-    hipError_t e_ = (expr);                    \
-    if (e_ != hipSuccess) {                    \
-      g_last_hip_error = (int)e_;              \
-      return DSK_EHIP;                         \
-    }                                          \
+// A launcher that answers hipErrorNotSupported has refused the shape before enqueuing anything: that is the
+// caller's DSK_ESHAPE, not a failed HIP call.
+#define HIP_TRY(expr)                                                   \
+  do {                                                                  \
+    hipError_t e_ = (expr);                                             \
+    if (e_ != hipSuccess) {                                             \
+      g_last_hip_error = (int)e_;                                       \
+      return e_ == hipErrorNotSupported ? DSK_ESHAPE : DSK_EHIP;        \
+    }                                                                   \
   } while (0)
 
 inline bool aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
@@ -87,7 +89,6 @@ inline char* kv_v(const dsk_kv_t* kv, int l) { return kv_k(kv, l) + kv->v_offset
 
 int g_force_generic = 0;
 int g_time_gemm = 0;
-int g_linear_ld_pad = 0;  // experiment knob: dsk_linear reads x and w with row stride K + pad
 
 // launch counters and the event pairs recorded under "time_gemm"
 struct Stats {
@@ -114,18 +115,18 @@ hipError_t gemm_any(int dtype, const void* A, int64_t lda, const void* W, int64_
       hipError_t ee = hipEventRecord(g_stats.ev[2 * g_stats.n_timed], s);
       if (ee != hipSuccess) return ee;
     }
+    // a shape the tensor-core kernels refuse comes back as hipErrorNotSupported (the caller's DSK_ESHAPE): a bf16
+    // problem never drops to the plain-ALU kernel behind the caller's back, that kernel is a hundred times slower
     hipError_t e = launch_gemm_mfma_bf16(A, lda, W, ldw, C, ldc, R, ldr, M, N, K, epi, ws, ws_bytes, s);
-    if (e != hipErrorNotSupported) {
-      if (e == hipSuccess) {
-        ++g_stats.gemm_mfma;
-        if (timed) {
-          e = hipEventRecord(g_stats.ev[2 * g_stats.n_timed + 1], s);
-          g_stats.timed_flops += 2.0 * M * N * K;
-          ++g_stats.n_timed;
-        }
+    if (e == hipSuccess) {
+      ++g_stats.gemm_mfma;
+      if (timed) {
+        e = hipEventRecord(g_stats.ev[2 * g_stats.n_timed + 1], s);
+        g_stats.timed_flops += 2.0 * M * N * K;
+        ++g_stats.n_timed;
       }
-      return e;
     }
+    return e;
   }
   ++g_stats.gemm_generic;
   return launch_gemm_generic(dtype, A, lda, W, ldw, C, ldc, R, ldr, M, N, K, epi, s);
@@ -137,12 +138,10 @@ hipError_t gemm(const dsk_model* m, const void* A, int64_t lda, const void* W, i
 }
 
 hipError_t attention_any(int dtype, const AttnArgs& a, hipStream_t s) {
-  if (dtype == DSK_BF16 && !g_force_generic) {
+  if (dtype == DSK_BF16 && !g_force_generic && a.vt) {  // no transposed V: the caller chose the plain kernel
     hipError_t e = launch_attn_mfma_bf16(a, s);
-    if (e != hipErrorNotSupported) {
-      if (e == hipSuccess) ++g_stats.attn_mfma;
-      return e;
-    }
+    if (e == hipSuccess) ++g_stats.attn_mfma;
+    return e;
   }
   ++g_stats.attn_generic;
   return launch_attn_generic(dtype, a, s);
@@ -169,7 +168,7 @@ int run_layer(dsk_model* m, int l, const void* h_in, int h_in_f32, void* h_out, 
   // few token rows (the suffix pass) on the tensor-core path: RoPE + KV write, and below the post-attention
   // RMSNorm, are done by the split-K reduction of the projection in front of them
   const bool few_rows = c.dtype == DSK_BF16 && !g_force_generic && n <= 64 && m->gemm_ws;
-  if (few_rows && gemm_small_m_fused_supported(n, m->n_qkv, d, d, d, m->gemm_ws_bytes)) {
+  if (few_rows && gemm_small_m_rope_supported(n, d, c.n_q_heads, c.n_kv_heads, c.head_dim, d, d, m->n_qkv, m->gemm_ws_bytes)) {
     HIP_TRY(launch_gemm_small_m_rope(m->xn, d, w.wqkv, d, m->qkv, m->n_qkv, m->rope_cs, k_own, v_own, n, d, c.n_q_heads,
                                      c.n_kv_heads, c.head_dim, m->gemm_ws, m->gemm_ws_bytes, s));
     ++g_stats.gemm_mfma;
@@ -188,7 +187,7 @@ int run_layer(dsk_model* m, int l, const void* h_in, int h_in_f32, void* h_out, 
     a.vt = m->vt; a.ldvt = m->ldvt;
   }
   HIP_TRY(attention(m, a, s));
-  if (few_rows && gemm_small_m_fused_supported(n, d, nq, nq, nq, m->gemm_ws_bytes)) {
+  if (few_rows && gemm_small_m_rmsnorm_supported(n, d, nq, nq, nq, m->gemm_ws_bytes)) {
     HIP_TRY(launch_gemm_small_m_rmsnorm(m->attn, nq, w.wo, nq, m->h, h_in, h_in_f32 ? 1 : 0, w.g2, m->xn, (float)c.rms_eps, n,
                                         d, nq, m->gemm_ws, m->gemm_ws_bytes, s));
     ++g_stats.gemm_mfma;
@@ -246,6 +245,19 @@ int dsk_model_create(const dsk_config_t* cfg, int64_t max_tokens, int64_t max_kv
   const int per16 = 16 / elem;
   if (cfg->hidden % per16 || cfg->ffn % per16 || cfg->head_dim % per16) return DSK_ESHAPE;
   if (!(cfg->rope_base > 0.0) || !(cfg->rms_eps >= 0.0)) return DSK_EINVAL;
+  // A bf16 model runs on the tensor-core kernels or not at all (the plain-ALU kernels serve fp32 models and the
+  // "force_generic" test hook): contraction lengths in whole 64-element k-tiles, head_dim 64 or 128, K/V rows in
+  // whole 64-element blocks, and token rows addressable by the kernels' 32-bit byte offsets.
+  if (cfg->dtype == DSK_BF16 && !g_force_generic) {
+    const int64_t nq_ = (int64_t)cfg->n_q_heads * cfg->head_dim, kvw_ = (int64_t)cfg->n_kv_heads * cfg->head_dim;
+    if (cfg->hidden % 64 || nq_ % 64 || cfg->ffn % 64 || kvw_ % 64 || (cfg->head_dim != 64 && cfg->head_dim != 128))
+      return DSK_ESHAPE;
+    const int64_t d_ = cfg->hidden, f_ = cfg->ffn, lim = (int64_t)1 << 32;
+    int64_t widest = d_ > f_ ? d_ : f_;  // longest activation row the projections read
+    if (nq_ > widest) widest = nq_;
+    if (max_tokens * widest * 2 >= lim) return DSK_ESHAPE;
+    if ((nq_ + 2 * kvw_) * d_ * 2 >= lim || d_ * nq_ * 2 >= lim || 2 * f_ * d_ * 2 >= lim) return DSK_ESHAPE;
+  }
 
   dsk_model* m = (dsk_model*)calloc(1, sizeof(dsk_model));
   if (!m) return DSK_ENOMEM;
@@ -452,6 +464,9 @@ int dsk_partial_prefill_groups(dsk_model_t* model, const dsk_group_t* groups, in
     return false;
   };
 
+  // Loads that an earlier call with DSK_DEFER_JOIN left outstanding, and that no suffix pass or dsk_join_loads
+  // has waited for, are joined here: the per-layer events and flags are about to be reused for this call.
+  if (m->any_pending) HIP_TRY(hipStreamWaitEvent(s, m->ev_all, 0));
   // loads start after everything the caller already enqueued on `stream`
   HIP_TRY(hipEventRecord(m->ev_entry, s));
   HIP_TRY(hipStreamWaitEvent(ls, m->ev_entry, 0));
@@ -621,8 +636,8 @@ int dsk_linear(int dtype, const void* x, const void* w, void* y, const void* r, 
     HIP_TRY(hipMalloc(&ws, (size_t)gemm_mfma_workspace_bytes(N)));
     ws_bytes = gemm_mfma_workspace_bytes(N);
   }
-  HIP_TRY(gemm_any(dtype, x, K + g_linear_ld_pad, w, K + g_linear_ld_pad, y, N, r, N, M, N, K, epi, may_split ? ws : nullptr,
-                   may_split ? ws_bytes : 0, (hipStream_t)stream));
+  HIP_TRY(gemm_any(dtype, x, K, w, K, y, N, r, N, M, N, K, epi, may_split ? ws : nullptr, may_split ? ws_bytes : 0,
+                   (hipStream_t)stream));
   return DSK_OK;
 }
 
@@ -639,6 +654,7 @@ int dsk_attention(int dtype, const void* q, const void* k_rows, const void* v_ro
   if (prefix) {
     if ((rc = check_batch(prefix, false))) return rc;
     if (prefix->n_seqs != queries->n_seqs) return DSK_EINVAL;
+    if (prefix->n_tokens > own_row0) return DSK_EINVAL;  // the two row ranges must not overlap
   }
   AttnArgs a;
   a.q = q; a.ldq = (int64_t)n_q_heads * head_dim; a.k_rows = k_rows; a.v_rows = v_rows; a.out = out;
@@ -651,7 +667,9 @@ int dsk_attention(int dtype, const void* q, const void* k_rows, const void* v_ro
   a.vt = nullptr; a.ldvt = 0;
   const int64_t kvw = (int64_t)n_kv_heads * head_dim;
   const int64_t rows64 = (own_row0 + queries->n_tokens + 63) / 64 * 64;
-  if (dtype == DSK_BF16 && !g_force_generic && scratch && kvw % 64 == 0 && scratch_bytes >= kvw * rows64 * 2) {
+  if (dtype == DSK_BF16 && !g_force_generic && scratch) {
+    // the caller asked for the tensor-core kernel: a shape it does not handle is an error, not a slower kernel
+    if (kvw % 64 || (head_dim != 64 && head_dim != 128) || scratch_bytes < kvw * rows64 * 2) return DSK_ESHAPE;
     HIP_TRY(launch_transpose_v(v_rows, scratch, rows64, (int)kvw, prefix ? prefix->n_tokens : 0, own_row0,
                                queries->n_tokens, (hipStream_t)stream));
     a.vt = scratch; a.ldvt = rows64;
@@ -662,11 +680,11 @@ int dsk_attention(int dtype, const void* q, const void* k_rows, const void* v_ro
 
 int dsk_set_option(const char* name, int value) {
   if (!name) return DSK_EINVAL;
-  if (!strcmp(name, "gemm_variant")) gemm_mfma_set_variant(value);
-  else if (!strcmp(name, "attn_variant")) attn_mfma_set_variant(value);
-  else if (!strcmp(name, "force_generic")) g_force_generic = value;
+  if (!strcmp(name, "gemm_tiling")) {
+    if (value < 0 || value > 2) return DSK_EINVAL;
+    gemm_mfma_set_variant(value);
+  } else if (!strcmp(name, "force_generic")) g_force_generic = value;
   else if (!strcmp(name, "time_gemm")) g_time_gemm = value;
-  else if (!strcmp(name, "linear_ld_pad")) g_linear_ld_pad = value;
   else if (!strcmp(name, "reset_stats")) {
     g_stats.gemm_mfma = g_stats.gemm_generic = g_stats.attn_mfma = g_stats.attn_generic = 0;
     g_stats.n_timed = 0;

@@ -84,6 +84,9 @@ int64_t gemm_mfma_workspace_bytes(int max_n);
 bool gemm_mfma_swiglu_supported(int M, int N, int K, int64_t ws_bytes);
 // Few token rows (M <= 64, bf16): the projection and the step that follows it in one pass of the split-K reduction.
 bool gemm_small_m_fused_supported(int M, int N, int K, int64_t lda, int64_t ldw, int64_t ws_bytes);
+bool gemm_small_m_rope_supported(int M, int K, int Hq, int Hkv, int dh, int64_t lda, int64_t ldw, int64_t ldq,
+                                 int64_t ws_bytes);
+bool gemm_small_m_rmsnorm_supported(int M, int d, int K, int64_t lda, int64_t ldw, int64_t ws_bytes);
 hipError_t launch_gemm_small_m_rope(const void* A, int64_t lda, const void* W, int64_t ldw, void* qkv, int64_t ldq,
                                     const float2* cs, void* k_rows, void* v_rows, int M, int K, int Hq, int Hkv, int dh,
                                     void* ws, int64_t ws_bytes, hipStream_t s);
@@ -137,4 +140,3 @@ hipError_t launch_fill_weight(int dtype, void* packed, int64_t rows, int64_t col
 void gemm_mfma_set_variant(int v);
 void attn_mfma_counts(int64_t* split, int64_t* packed, int reset);
 bool gemm_mfma_uses_prefill_tile(int M, int N);
-void attn_mfma_set_variant(int v);

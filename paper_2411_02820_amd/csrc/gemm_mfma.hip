@@ -928,8 +928,6 @@ hipError_t launch_gemm_mfma_bf16(const void* A, int64_t lda, const void* W, int6
                          (const float*)ws, (bf16_t*)C, ldc, M, N, splits);
       return hipGetLastError();
     }
-    if (variant == 5) return launch<256, 256, 2, 4, false, 1>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
-    if (variant == 6) return launch16<128, 128, 2, 2>(A, lda, W, ldw, C, ldc, R, ldr, M, N, K, epi, s);
     if ((int64_t)((M + 255) / 256) * ((N + 255) / 256) >= 192 || variant == 1)
       return launch16<256, 256, 2, 4>(A, lda, W, ldw, C, ldc, R, ldr, M, N, K, epi, s);
     return launch<128, 128, 2, 2, false, 1>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
@@ -974,14 +972,10 @@ hipError_t launch_gemm_mfma_bf16(const void* A, int64_t lda, const void* W, int6
       }
       return launch<64, 64, 1, 2, false>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
     }
-    // what the library picks: the 256x256 tile on the 16x16x32 MFMA (default; power-limited there, and that
-    // instruction is the thriftier one) and the 128x128 tile on the 32x32x16 MFMA (2: medium sizes are issue- and
-    // latency-bound, where it is 15-30 % faster).  For tests and comparisons: 4, 5 = 256x256 on 32x32x16 with the
-    // one-barrier schedule / the early-freed stage, 6 = 128x128 on 16x16x32.
+    // the two prefill tilings: the 256x256 tile on the 16x16x32 MFMA (1; large problems are power-limited, and that
+    // instruction is the thriftier one) and the 128x128 tile on the 32x32x16 MFMA (2; medium sizes are issue- and
+    // latency-bound, where it is 15-30 % faster)
     case 2: return launch<128, 128, 2, 2, false, 1>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
-    case 4: return launch<256, 256, 2, 4, false, 0>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
-    case 5: return launch<256, 256, 2, 4, false, 1>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
-    case 6: return launch16<128, 128, 2, 2>(A, lda, W, ldw, C, ldc, R, ldr, M, N, K, epi, s);
     default: return launch16<256, 256, 2, 4>(A, lda, W, ldw, C, ldc, R, ldr, M, N, K, epi, s);
   }
 }
@@ -1006,12 +1000,23 @@ static hipError_t small_m_partials(const void* A, int64_t lda, const void* W, in
               : launch<64, 64, 1, 2, true>(A, lda, W, ldw, nullptr, N, nullptr, 0, (float*)ws, M, N, K, 0, *splits, per, s);
 }
 
+// The two fused launchers below refuse exactly what these predicates refuse; the layer asks them first and takes
+// the unfused steps (projection, then RoPE / RMSNorm kernel) otherwise.
+bool gemm_small_m_rope_supported(int M, int K, int Hq, int Hkv, int dh, int64_t lda, int64_t ldw, int64_t ldq,
+                                 int64_t ws_bytes) {
+  return dh % 8 == 0 && (ldq & 3) == 0 && gemm_small_m_fused_supported(M, (Hq + 2 * Hkv) * dh, K, lda, ldw, ws_bytes);
+}
+
+bool gemm_small_m_rmsnorm_supported(int M, int d, int K, int64_t lda, int64_t ldw, int64_t ws_bytes) {
+  return d % 4 == 0 && d <= 8192 && gemm_small_m_fused_supported(M, d, K, lda, ldw, ws_bytes);
+}
+
 // qkv projection + RoPE + KV-cache write: N = (Hq + 2 Hkv) dh
 hipError_t launch_gemm_small_m_rope(const void* A, int64_t lda, const void* W, int64_t ldw, void* qkv, int64_t ldq,
                                     const float2* cs, void* k_rows, void* v_rows, int M, int K, int Hq, int Hkv, int dh,
                                     void* ws, int64_t ws_bytes, hipStream_t s) {
   const int N = (Hq + 2 * Hkv) * dh;
-  if (dh % 8 || (ldq & 3)) return hipErrorNotSupported;
+  if (!ws || !gemm_small_m_rope_supported(M, K, Hq, Hkv, dh, lda, ldw, ldq, ws_bytes)) return hipErrorNotSupported;
   int splits = 0;
   hipError_t e = small_m_partials(A, lda, W, ldw, M, N, K, ws, ws_bytes, &splits, s);
   if (e != hipSuccess) return e;
@@ -1025,7 +1030,7 @@ hipError_t launch_gemm_small_m_rope(const void* A, int64_t lda, const void* W, i
 hipError_t launch_gemm_small_m_rmsnorm(const void* A, int64_t lda, const void* W, int64_t ldw, float* h, const void* R,
                                        int r_f32, const void* g, void* xn, float eps, int M, int d, int K, void* ws,
                                        int64_t ws_bytes, hipStream_t s) {
-  if (d % 4 || d > 8192) return hipErrorNotSupported;
+  if (!ws || !gemm_small_m_rmsnorm_supported(M, d, K, lda, ldw, ws_bytes)) return hipErrorNotSupported;
   int splits = 0;
   hipError_t e = small_m_partials(A, lda, W, ldw, M, d, K, ws, ws_bytes, &splits, s);
   if (e != hipSuccess) return e;

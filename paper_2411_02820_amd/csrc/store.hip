@@ -101,7 +101,7 @@ int dsk_store_put_kv(dsk_store_t* store, uint64_t context, uint64_t model_id, co
   std::lock_guard<std::mutex> lock(store->mu);
   const dsk_store::Key key(context, model_id, 0, -1);
   if (inserted) *inserted = 0;
-  if (store->entries.count(key)) return DSK_OK;  // "put it into the store if the context does not exist"
+  if (store->entries.count(key)) return DSK_OK;  // an existing (context, model) entry is kept (Sec. 4.4)
   dsk_store::Entry e;
   const int64_t half = n_rows * row_bytes;
   int rc = store_alloc(store, tier, (int64_t)n_layers * 2 * half, &e);

@@ -26,6 +26,16 @@ def test_library_exports_every_declared_symbol():
     assert set(declared_symbols()) == set(B.EXPORTS)
 
 
+def test_diag_library_exports_what_its_header_declares():
+    from paper_2411_02820_amd import diag
+    text = open(os.path.join(ROOT, "include", "dsk_diag.h")).read()
+    names = re.findall(r"DSK_DIAG_API\s+[\w\s\*]+?\b(dsk_\w+)\s*\(", text)
+    lib = ctypes.CDLL(diag.LIB_PATH)
+    assert names and set(names) == set(diag.EXPORTS)
+    for name in names:
+        assert hasattr(lib, name), name
+
+
 def test_error_strings_without_gpu():
     from paper_2411_02820_amd import binding as B
     assert B.lib.dsk_strerror(B.DSK_OK) == b"ok"

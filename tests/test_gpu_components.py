@@ -22,7 +22,7 @@ def _bf16(a):
 # shapes span: several tiles + ragged M tail, small-M weight-streaming path, N not a multiple of the tile, K tail
 @pytest.mark.parametrize("M,N,K,residual", [
     (300, 512, 256, False), (1000, 768, 512, True), (64, 1024, 2048, True), (17, 4096, 1024, False),
-    (1, 256, 64, True), (513, 320, 192, False), (130, 6144, 4096, True), (100, 96, 100, False),
+    (1, 256, 64, True), (513, 320, 192, False), (130, 6144, 4096, True),
 ])
 def test_linear_bf16(B, M, N, K, residual):
     x = _bf16(synth.normal(M * K, 11, 0, 1.0).reshape(M, K))
@@ -37,10 +37,52 @@ def test_linear_bf16(B, M, N, K, residual):
     assert O.max_rel_err(y.float().cpu().numpy(), ref) <= 2 ** -8
 
 
-# every tiling of the prefill GEMM (1, 6: 256x256 and 128x128 on the 16x16x32 MFMA; 5, 2: the same tiles on the
-# 32x32x16 MFMA with the early-freed stage; 4: 256x256 with one barrier per k-tile) forced on shapes with 1, 2, 3
-# and 7 k-tiles (the peeled head and tail of the software pipeline), ragged M and N, with and without residual
-@pytest.mark.parametrize("variant", [1, 2, 4, 5, 6])
+# The few-row weight-streaming path at the widths the 8B and 70B suffix passes run it at: the 64x128 tiling it takes
+# for a very wide N (gate/up: 2F = 28672 and 57344 columns), the 64x64 tiling for the others, full (64) and ragged
+# (17) row counts, the long contraction of the down projection.
+@pytest.mark.parametrize("M,N,K,residual", [
+    (64, 28672, 4096, False), (17, 57344, 8192, False), (64, 57344, 8192, False), (64, 6144, 4096, False),
+    (64, 4096, 14336, True), (33, 8192, 28672, True), (64, 10240, 8192, False),
+])
+def test_linear_bf16_few_rows_at_model_widths(B, M, N, K, residual):
+    x = _bf16(synth.normal(M * K, 16, 0, 1.0).reshape(M, K))
+    w = _bf16(synth.normal(N * K, 16, 1, 0.02).reshape(N, K))
+    r = _bf16(synth.normal(M * N, 16, 2, 1.0).reshape(M, N)) if residual else None
+    ref = x.astype(np.float64) @ w.astype(np.float64).T + (0 if r is None else r.astype(np.float64))
+    dev = lambda a: torch.from_numpy(a).to(torch.bfloat16).cuda()
+    y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    B.dsk_set_option("reset_stats", 0)
+    B.dsk_linear(B.DSK_BF16, dev(x), dev(w), y, None if r is None else dev(r), M, N, K)
+    torch.cuda.synchronize()
+    assert B.dsk_get_stat("gemm_mfma_launches") == 1 and B.dsk_get_stat("gemm_generic_launches") == 0
+    assert O.max_rel_err(y.float().cpu().numpy(), ref) <= 2 ** -8
+
+
+def test_linear_bf16_unsupported_shape_is_an_error_not_a_slower_kernel(B):
+    # K = 100 is no whole number of 64-element k-tiles: the tensor-core kernel refuses it, and the call says so;
+    # the plain-ALU kernel runs only when the test hook asks for it
+    M, N, K = 100, 96, 100
+    x = _bf16(synth.normal(M * K, 11, 0, 1.0).reshape(M, K))
+    w = _bf16(synth.normal(N * K, 11, 1, 0.05).reshape(N, K))
+    dev = lambda a: torch.from_numpy(a).to(torch.bfloat16).cuda()
+    y = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(B.DskError) as e:
+        B.dsk_linear(B.DSK_BF16, dev(x), dev(w), y, None, M, N, K)
+    assert e.value.status == B.DSK_ESHAPE
+    torch.cuda.synchronize()
+    assert torch.isnan(y.float()).all(), "a refused call writes nothing"
+    B.dsk_set_option("force_generic", 1)
+    try:
+        B.dsk_linear(B.DSK_BF16, dev(x), dev(w), y, None, M, N, K)
+        torch.cuda.synchronize()
+    finally:
+        B.dsk_set_option("force_generic", 0)
+    assert O.max_rel_err(y.float().cpu().numpy(), x.astype(np.float64) @ w.astype(np.float64).T) <= 2 ** -8
+
+
+# the two prefill tilings (1: 256x256 on the 16x16x32 MFMA, 2: 128x128 on the 32x32x16 MFMA) forced on shapes with
+# 1, 2, 3 and 7 k-tiles (the peeled head and tail of the software pipeline), ragged M and N, with and without residual
+@pytest.mark.parametrize("variant", [1, 2])
 @pytest.mark.parametrize("M,N,K,residual", [(300, 516, 64, False), (257, 512, 128, True), (513, 260, 192, False),
                                             (700, 1028, 448, True)])
 def test_linear_bf16_forced_tiling(B, variant, M, N, K, residual):
@@ -50,12 +92,12 @@ def test_linear_bf16_forced_tiling(B, variant, M, N, K, residual):
     ref = x.astype(np.float64) @ w.astype(np.float64).T + (0 if r is None else r.astype(np.float64))
     dev = lambda a: torch.from_numpy(a).to(torch.bfloat16).cuda()
     y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
-    B.dsk_set_option("gemm_variant", variant)
+    B.dsk_set_option("gemm_tiling", variant)
     try:
         B.dsk_linear(B.DSK_BF16, dev(x), dev(w), y, None if r is None else dev(r), M, N, K)
         torch.cuda.synchronize()
     finally:
-        B.dsk_set_option("gemm_variant", 0)
+        B.dsk_set_option("gemm_tiling", 0)
     assert O.max_rel_err(y.float().cpu().numpy(), ref) <= 2 ** -8
 
 
@@ -162,6 +204,37 @@ def test_attention_plain_kernel_both_dtypes(B):
     assert _attention_case(B, [90, 33], [50, 20], 4, 2, 64, "f32", False) <= 1e-5
     assert _attention_case(B, [90, 33], [50, 20], 4, 2, 64, "bf16", False) <= 1e-2
     assert B.dsk_get_stat("attn_generic_launches") == 1
+
+
+def test_attention_bf16_unsupported_shape_is_an_error(B):
+    from paper_2411_02820_amd import binding
+    n_q, Hq, Hkv, dh = 16, 4, 2, 32     # head_dim 32: not a shape of the tensor-core kernel
+    t = lambda *s: torch.zeros(s, dtype=torch.bfloat16, device="cuda")
+    qb = binding.Batch(synth.cu_seqlens([n_q]))
+    scratch = t(Hkv * dh * 64)
+    with pytest.raises(B.DskError) as e:
+        B.dsk_attention(B.DSK_BF16, t(n_q, Hq * dh), t(n_q, Hkv * dh), t(n_q, Hkv * dh), t(n_q, Hq * dh), qb.desc, None, 0,
+                        Hq, Hkv, dh, scratch)
+    assert e.value.status == B.DSK_ESHAPE
+    # a prefix range that reaches into the queries' own rows
+    pb = binding.Batch(synth.cu_seqlens([8]))
+    with pytest.raises(B.DskError) as e:
+        B.dsk_attention(B.DSK_BF16, t(n_q, 8 * 128), t(n_q + 4, 2 * 128), t(n_q + 4, 2 * 128), t(n_q, 8 * 128), qb.desc,
+                        pb.desc, 4, 8, 2, 128, t(2 * 128 * 64))
+    assert e.value.status == B.DSK_EINVAL
+    torch.cuda.synchronize()
+
+
+def test_bf16_model_with_unsupported_shape_is_refused_at_creation(B):
+    # hidden 96 is no whole number of k-tiles; head_dim 32 has no tensor-core attention kernel
+    for bad in (synth.ModelShape(2, 96, 2, 2, 64, 128, 1e4, 1e-5, "bf16"),
+                synth.ModelShape(2, 128, 4, 4, 32, 128, 1e4, 1e-5, "bf16")):
+        with pytest.raises(B.DskError) as e:
+            B.dsk_model_create(B.config_from_shape(bad), 8, 8)
+        assert e.value.status == B.DSK_ESHAPE
+    # the same shapes are fine as fp32 models (plain-ALU kernels by design)
+    ok = synth.ModelShape(2, 96, 2, 2, 64, 128, 1e4, 1e-5, "f32")
+    B.dsk_model_destroy(B.dsk_model_create(B.config_from_shape(ok), 8, 8))
 
 
 def test_bf16_model_runs_on_tensor_core_kernels(B):

@@ -39,6 +39,7 @@ def host_weights(shape, seed, layers):
     def get(l):
         assert l in layers, f"layer {l} was not requested"
         if l not in cache:
+            print(f"[host] generating layer {l} of the {shape.hidden}-wide model", flush=True)
             cache[l] = {k: v.astype(np.float64) for k, v in synth.layer_weights(shape, seed, l).items()}
         return cache[l]
     return get
@@ -68,6 +69,64 @@ def device_kv_cache(B, shape, n_rows, n_fill_rows, pinned=False):
         h.copy_(kv)
         return h
     return kv
+
+
+def host_layer(shape, seed, layer, names=None):
+    """One layer's tensors as fp64 arrays, generated on the host (nothing is kept: a 70B layer is 6.8 GB in fp64)."""
+    names = synth.TENSOR_NAMES if names is None else names
+    print(f"[host] generating layer {layer} of the {shape.hidden}-wide model ({len(names)} tensors)", flush=True)
+    return {n: synth.layer_tensor(shape, seed, layer, synth.TENSOR_NAMES.index(n)).astype(np.float64) for n in names}
+
+
+def suffix_kv_of_first_two_layers(cfg, shape, xs_host, spos, cu, cus, n_rows, seqs):
+    """What the suffix pass must write for layers 0 and 1, for the suffix rows of the sequences `seqs`, when layers
+    0 and 1 of the cache hold the seeded N(0,1) rows: layer 0's K/V come straight from the suffix embeddings, layer
+    1's from the state leaving layer 0 (attention over the sequence's whole prefix and its own suffix rows, MLP).
+    Returns (rows, [(K0, V0), (K1, V1)]) with rows the packed suffix row indices."""
+    seqs = sorted(set(seqs))
+    rows = np.concatenate([np.arange(cus[b], cus[b + 1]) for b in seqs])
+    seq_of = np.concatenate([np.full(cus[b + 1] - cus[b], b) for b in seqs])
+    w0 = host_layer(shape, synth.SEED_RECEIVER, 0)
+    Kp, Vp = host_kv_rows(shape, 0, n_rows)
+    x, pos = xs_host[rows].astype(np.float64), np.asarray(spos)[rows]
+    K0, V0 = O.project_kv(cfg, w0, x, pos)
+
+    def visible(i):
+        b = seq_of[i]
+        first = int(np.searchsorted(rows, cus[b]))   # first selected row of this sequence
+        return (np.concatenate([Kp[cu[b]:cu[b + 1]], K0[first:i + 1]]), np.concatenate([Vp[cu[b]:cu[b + 1]], V0[first:i + 1]]))
+
+    h1 = O.layer_rows(cfg, w0, x, pos, visible)
+    del w0
+    K1, V1 = O.project_kv(cfg, host_layer(shape, synth.SEED_RECEIVER, 1, ("g1", "wk", "wv")), h1, pos)
+    return rows, [(K0, V0), (K1, V1)]
+
+
+def check_suffix_kv(G, kv_out, T, rows, ref, label):
+    rows_t = torch.from_numpy(rows).cuda() + T
+    errs = {}
+    for l, (K, V) in enumerate(ref):
+        errs[f"sK{l}"] = O.max_rel_err(G.to_np(kv_out[l, 0].index_select(0, rows_t)), K)
+        errs[f"sV{l}"] = O.max_rel_err(G.to_np(kv_out[l, 1].index_select(0, rows_t)), V)
+    print(f"{label} suffix max-rel-err:", {k: f"{v:.2e}" for k, v in errs.items()})
+    assert max(errs.values()) <= TOL, errs
+
+
+def check_one_layer_full_length(G, m, shape, hidden_dev, hidden_host, l, kv_r, lens, rows, kv_of_l=None):
+    """Layer l over the whole prefix: K and V of every row (they depend on the row's own hidden state only) and the
+    state leaving the layer at the sampled rows (attention over everything before them), against the oracle."""
+    T = sum(lens)
+    kv_1, h_1 = m.partial(hidden_dev, l, l + 1, kv_r, lens)
+    torch.cuda.synchronize()
+    if kv_of_l is not None:   # the multi-layer call started from the same E cache: same bits for its first layer
+        assert torch.equal(kv_1[l, :, :T], kv_of_l[:, :T])
+    w = host_layer(shape, synth.SEED_RECEIVER, l)
+    h_ref, K, V = O.prefix_layer(oracle_config(shape), w, hidden_host.astype(np.float64), synth.packed_positions(lens),
+                                 synth.cu_seqlens(lens), rows=rows)
+    errs = {"K": O.max_rel_err(G.to_np(kv_1[l, 0, :T]), K), "V": O.max_rel_err(G.to_np(kv_1[l, 1, :T]), V),
+            "hidden_rows": O.max_rel_err(G.to_np(h_1)[rows], h_ref)}
+    print(f"layer {l} over {T} tokens, rows {rows}: max-rel-err:", {k: f"{v:.2e}" for k, v in errs.items()})
+    assert max(errs.values()) <= TOL, errs
 
 
 def host_kv_rows(shape, layer, n_rows):
@@ -111,6 +170,12 @@ def test_config2_8b_prefix4096_layers_8_16(G, B):
         for l in list(range(0, lo)) + list(range(hi, shape.n_layers)):
             assert torch.equal(kv_out[l, :, :T], kv_r[l]), f"splice of layer {l}"
         assert torch.isfinite(hs.float()).all() and torch.isfinite(kv_out.float()).all()
+        # the suffix pass against the 4096-row prefix: what it wrote for layers 0 and 1
+        cfg = oracle_config(shape)
+        spos = synth.packed_positions([S], start=[T])
+        xs_host = synth.hidden_states(shape, S, seed=synth.SEED_SUFFIX)
+        rows, ref = suffix_kv_of_first_two_layers(cfg, shape, xs_host, spos, synth.cu_seqlens([T]), synth.cu_seqlens([S]), T, [0])
+        check_suffix_kv(G, kv_out, T, rows, ref, "C2")
         # the whole recomputed chain on the first 256 tokens
         check_truncated(G, shape, kv_out, h_out, hidden_host, lo, hi, [T], 256)
         # composition at full size: [8,12) then [12,16) through hidden_out reproduces [8,16) up to the one bf16
@@ -151,15 +216,30 @@ def test_config3_8b_ragged_batch(G, B):
     lo = int(synth.uniform_ints(1, 0, 28, synth.SEED_LENGTHS, 1)[0])
     hi = lo + 4
     T = sum(lens)
+    slens = [128] * len(lens)
+    S = sum(slens)
     hidden_host = synth.hidden_states(shape, T)
-    with G.GpuModel(shape, T) as m:
+    with G.GpuModel(shape, T, T + S) as m:
         m.init_random(synth.SEED_RECEIVER)
         kv_r = device_kv_cache(B, shape, T, T)
-        kv_out, h_out = m.partial(G.to_dev(hidden_host, shape), lo, hi, kv_r, lens)
+        kv_out, h_out = m.partial(G.to_dev(hidden_host, shape), lo, hi, kv_r, lens, n_rows=T + S)
         torch.cuda.synchronize()
         for l in (0, lo - 1, hi, shape.n_layers - 1):
             if 0 <= l < shape.n_layers and not (lo <= l < hi):
-                assert torch.equal(kv_out[l], kv_r[l]), f"splice of layer {l}"
+                assert torch.equal(kv_out[l, :, :T], kv_r[l]), f"splice of layer {l}"
+        # the 128-token suffixes (1024 rows: the K-split 128x128 projections, unsplit attention) through all 32
+        # layers; layers 0 and 1 are reused ones here, so what the pass wrote for them is checked for the suffixes
+        # of the shortest and of the longest sequence
+        assert lo > 1
+        xs = device_normal(B, (S, shape.hidden), synth.SEED_SUFFIX, 0)
+        hs = m.suffix(xs, kv_out, lens, slens)
+        torch.cuda.synchronize()
+        assert torch.isfinite(hs.float()).all()
+        assert torch.equal(kv_out[0, :, :T], kv_r[0]), "the suffix pass must not touch prefix rows"
+        rows, ref = suffix_kv_of_first_two_layers(oracle_config(shape), shape, synth.hidden_states(shape, S, seed=synth.SEED_SUFFIX),
+                                                  synth.packed_positions(slens, start=lens), synth.cu_seqlens(lens),
+                                                  synth.cu_seqlens(slens), T, [int(np.argmin(lens)), int(np.argmax(lens))])
+        check_suffix_kv(G, kv_out, T, rows, ref, "C3")
         # every sequence's first 48 tokens, with its own positions, against the oracle's ragged batch
         check_truncated(G, shape, kv_out, h_out, hidden_host, lo, hi, lens, 48)
         # the last row of the shortest sequence through one layer: full-length attention inside a packed batch
@@ -172,7 +252,7 @@ def test_config3_8b_ragged_batch(G, B):
         h_ref, K, V = O.prefix_layer(cfg, w, hidden_host[s:e].astype(np.float64), np.arange(n), np.array([0, n]),
                                      rows=[n - 1])
         assert O.max_rel_err(G.to_np(kv_out[lo, 0, s:e]), K) <= TOL
-        kv1, h1 = m.partial(G.to_dev(hidden_host, shape), lo, lo + 1, kv_r, lens)
+        kv1, h1 = m.partial(G.to_dev(hidden_host, shape), lo, lo + 1, kv_r, lens, n_rows=T + S)
         torch.cuda.synchronize()
         assert O.max_rel_err(G.to_np(h1[e - 1:e]), h_ref) <= TOL
 
@@ -208,6 +288,38 @@ def test_8b_shape_suffix_ragged_against_oracle(G, B):
         assert B.dsk_get_stat("attn_generic_launches") == 0 and B.dsk_get_stat("gemm_generic_launches") == 0
 
 
+@pytest.mark.parametrize("name,width,S", [("8B", synth.LLAMA_8B, 64), ("8B", synth.LLAMA_8B, 17), ("70B", synth.LLAMA_70B, 64)])
+def test_suffix_pass_at_model_width_against_oracle(G, B, name, width, S):
+    # Two layers of the 8B / 70B layer shape, 8192 seeded N(0,1) prefix rows in the cache, S <= 64 new tokens: the
+    # whole suffix pass (Sec. 4.1) against the oracle - few-row projections on the K-split weight-streaming tiles
+    # (64x128 tiles for gate/up), RoPE + cache write, residual + RMSNorm and SwiGLU applied by the split-K
+    # reductions, key-split attention with the q heads of a kv group packed per workgroup, at real widths.
+    shape = synth.ModelShape(2, width.hidden, width.n_q_heads, width.n_kv_heads, width.head_dim, width.ffn,
+                             width.rope_base, width.rms_eps, "bf16")
+    cfg = oracle_config(shape)
+    T = 8192
+    cu, cus = synth.cu_seqlens([T]), synth.cu_seqlens([S])
+    spos = synth.packed_positions([S], start=[T])
+    xs_host = synth.hidden_states(shape, S, seed=synth.SEED_SUFFIX)
+    with G.GpuModel(shape, S, T + S) as m:
+        m.init_random(synth.SEED_RECEIVER)
+        kv = device_kv_cache(B, shape, T + S, T)
+        B.dsk_set_option("reset_stats", 0)
+        hs = m.suffix(G.to_dev(xs_host, shape), kv, [T], [S])
+        torch.cuda.synchronize()
+        assert B.dsk_get_stat("attn_packed_head_launches") == 2 and B.dsk_get_stat("attn_generic_launches") == 0
+        assert B.dsk_get_stat("gemm_mfma_launches") == 8 and B.dsk_get_stat("gemm_generic_launches") == 0
+        kv_s, hs_ref = O.suffix_prefill(cfg, lambda l: host_layer(shape, synth.SEED_RECEIVER, l), xs_host.astype(np.float64),
+                                        [host_kv_rows(shape, l, T) for l in range(2)], spos, cu, cus)
+        errs = {"suffix_hidden": O.max_rel_err(G.to_np(hs), hs_ref)}
+        for l in range(2):
+            errs[f"sK{l}"] = O.max_rel_err(G.to_np(kv[l, 0, T:]), kv_s[l][0])
+            errs[f"sV{l}"] = O.max_rel_err(G.to_np(kv[l, 1, T:]), kv_s[l][1])
+            assert np.array_equal(G.to_np(kv[l, 0, :T]), host_kv_rows(shape, l, T)[0].astype(np.float32)), "prefix rows untouched"
+        print(f"{name} width, S={S}: max-rel-err:", {k: f"{v:.2e}" for k, v in errs.items()})
+        assert max(errs.values()) <= TOL, errs
+
+
 def test_config4_8b_prefix16384_kv_in_pinned_host_memory(G, B):
     # reused KV (2 GiB, bf16) and the E cache live in pinned host memory; loads are pipelined under layers [4,12)
     shape, T, lo, hi, S = synth.LLAMA_8B, 16384, 4, 12, 64
@@ -224,8 +336,17 @@ def test_config4_8b_prefix16384_kv_in_pinned_host_memory(G, B):
         for l in list(range(0, lo)) + list(range(hi, shape.n_layers)):
             assert torch.equal(kv_out[l, :, :T].cpu(), kv_r[l]), f"splice of layer {l}"
         assert torch.isfinite(hs.float()).all()
+        # the suffix pass against the 16384-row prefix (key-split attention over 256 key tiles): layers 0 and 1
+        rows, ref = suffix_kv_of_first_two_layers(oracle_config(shape), shape, synth.hidden_states(shape, S, seed=synth.SEED_SUFFIX),
+                                                  synth.packed_positions([S], start=[T]), synth.cu_seqlens([T]),
+                                                  synth.cu_seqlens([S]), T, [0])
+        check_suffix_kv(G, kv_out, T, rows, ref, "C4")
         # first two recomputed layers on a truncated prefix (the whole chain is covered at 4096 tokens)
         check_truncated(G, shape, kv_out, None, hidden_host, lo, lo + 2, [T], 128)
+        # the first recomputed layer at full length: K/V of all 16384 rows, the layer output at sampled rows up to
+        # the last one (256 key tiles, every query-tile position of the heavy-first launch order)
+        check_one_layer_full_length(G, m, shape, e_host, hidden_host, lo, kv_r, [T],
+                                    [0, 127, 128, 5000, 8191, 8192, 12345, 16320, 16383], kv_of_l=kv_out[lo])
         # the three loading strategies give the same bits
         B.dsk_set_load_mode(m.handle, B.DSK_LOAD_ALL_FIRST)
         kv_2, h_2 = m.partial(e_host, lo, hi, kv_r, [T], n_rows=T + S)
@@ -240,12 +361,26 @@ def test_config5_70b_prefix8192_layers_20_36(G, B):
         m.init_random(synth.SEED_RECEIVER)
         assert B.dsk_model_weight_bytes(m.handle) > 136e9
         kv_r = device_kv_cache(B, shape, T, T)
-        kv_out, h_out = m.partial(G.to_dev(hidden_host, shape), lo, hi, kv_r, [T], n_rows=T + S)
+        hidden_dev = G.to_dev(hidden_host, shape)
+        kv_out, h_out = m.partial(hidden_dev, lo, hi, kv_r, [T], n_rows=T + S)
+        xs = device_normal(B, (S, shape.hidden), synth.SEED_SUFFIX, 0)
+        B.dsk_set_option("reset_stats", 0)
+        hs = m.suffix(xs, kv_out, [T], [S])
         torch.cuda.synchronize()
+        assert B.dsk_get_stat("attn_packed_head_launches") == shape.n_layers and B.dsk_get_stat("gemm_generic_launches") == 0
         for l in (0, lo - 1, hi, shape.n_layers - 1):
             assert torch.equal(kv_out[l, :, :T], kv_r[l]), f"splice of layer {l}"
-        assert torch.isfinite(h_out.float()).all()
+        assert torch.isfinite(h_out.float()).all() and torch.isfinite(hs.float()).all()
+        # the suffix pass at 70B width (8 q heads per kv head packed per workgroup, 64x128 few-row tiles, the
+        # 8192-wide fused reduce + RMSNorm): what it wrote for layers 0 and 1
+        rows, ref = suffix_kv_of_first_two_layers(oracle_config(shape), shape, synth.hidden_states(shape, S, seed=synth.SEED_SUFFIX),
+                                                  synth.packed_positions([S], start=[T]), synth.cu_seqlens([T]),
+                                                  synth.cu_seqlens([S]), T, [0])
+        check_suffix_kv(G, kv_out, T, rows, ref, "C5")
         # device-generated weights of one layer against the host generator, bit for bit (largest tensors)
         for kind in (synth.WQ, synth.WD):
             assert np.array_equal(m.get_tensor(lo, kind).float().cpu().numpy(), synth.layer_tensor(shape, 0, lo, kind))
         check_truncated(G, shape, kv_out, None, hidden_host, lo, lo + 2, [T], 64)
+        # the first recomputed layer at full length: K/V of all 8192 rows, the layer output at sampled rows
+        check_one_layer_full_length(G, m, shape, hidden_dev, hidden_host, lo, kv_r, [T],
+                                    [0, 255, 256, 3000, 4095, 4096, 7000, 8100, 8191], kv_of_l=kv_out[lo])
