@@ -50,7 +50,8 @@ typedef enum {
   DSK_EDTYPE = -3, /* dtype not DSK_F32 / DSK_BF16 */
   DSK_ENOMEM = -4, /* device or host allocation failed */
   DSK_EHIP = -5,   /* a HIP call failed; see dsk_last_hip_error() */
-  DSK_ENOENT = -6  /* the cache store holds no such entry */
+  DSK_ENOENT = -6, /* the cache store holds no such entry */
+  DSK_ELIMIT = -7  /* size beyond the fixed limit of an entry point that works without allocating */
 } dsk_status;
 
 typedef enum { DSK_F32 = 0, DSK_BF16 = 1 } dsk_dtype;
@@ -275,6 +276,22 @@ DSK_API int dsk_select_recompute(const dsk_frontier_point_t* frontier, int n_poi
  * The projection step of the layer (QKV, O, gate/up, down); y may alias r.  bf16 runs on the tensor-core kernels
  * and needs K a multiple of 64, N a multiple of 4 and M*K, N*K below 2^31 elements, else DSK_ESHAPE. */
 DSK_API int dsk_linear(int dtype, const void* x, const void* w, void* y, const void* r, int M, int N, int K, void* stream);
+
+/* dsk_linear for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same kernels and same results as dsk_linear for the few-row
+ * projections of the suffix pass, M <= DSK_STATIC_MAX_M rows and N <= DSK_STATIC_MAX_N columns (any K the
+ * kernels handle); larger M or N return DSK_ELIMIT and nothing is enqueued.  The fp32 partial sums of the K-split
+ * go to a fixed array of DSK_STATIC_SCRATCH_BYTES inside the library's code object (every GPU the library runs on
+ * holds its copy until the process ends) instead of a buffer allocated on first use: the call allocates and frees
+ * nothing, on the host or on the device.  Nothing in the array has to start at zero (a call writes every partial
+ * sum before its reduction reads it), so it is never cleared.  All calls on one GPU share the array: calls that
+ * overlap in time (different streams, or one stream under concurrent graph launches) race on it and must be
+ * ordered by the caller. */
+#define DSK_STATIC_MAX_M 64
+#define DSK_STATIC_MAX_N 65536
+#define DSK_STATIC_SCRATCH_BYTES (32 << 20) /* 64 rows x (at most 131072 split x column pairs) x 4 bytes */
+DSK_API int dsk_linear_static(int dtype, const void* x, const void* w, void* y, const void* r, int M, int N, int K,
+                              void* stream);
 
 /* Causal grouped-query attention of packed query tokens q [n_q, Hq*dh] (already rotated) against cache
  * rows k_rows/v_rows (row stride Hkv*dh): query i of sequence b sees rows prefix.cu[b]..prefix.cu[b+1]-1

@@ -39,7 +39,7 @@ EXPORTS = (
     "dsk_join_loads", "dsk_set_load_mode", "dsk_set_load_throttle", "dsk_model_weight_bytes", "dsk_model_workspace_bytes",
     "dsk_strerror", "dsk_last_hip_error", "dsk_hash_context", "dsk_store_create", "dsk_store_destroy",
     "dsk_store_put_kv", "dsk_store_put_e", "dsk_store_fetch_kv_layer", "dsk_store_fetch_kv", "dsk_store_fetch_e",
-    "dsk_store_erase", "dsk_store_usage", "dsk_estimate_prefill_ms", "dsk_select_recompute", "dsk_linear", "dsk_attention", "dsk_set_option", "dsk_get_stat",
+    "dsk_store_erase", "dsk_store_usage", "dsk_estimate_prefill_ms", "dsk_select_recompute", "dsk_linear", "dsk_linear_static", "dsk_attention", "dsk_set_option", "dsk_get_stat",
 )
 
 
@@ -88,6 +88,7 @@ lib.dsk_partial_prefill_groups.argtypes = [_P, C.POINTER(dsk_group_t), C.c_int, 
 lib.dsk_suffix_prefill.argtypes = [_P, _P, C.POINTER(dsk_kv_t), C.POINTER(dsk_batch_t), C.POINTER(dsk_batch_t),
                                    C.c_int64, _P, _P]
 lib.dsk_linear.argtypes = [C.c_int, _P, _P, _P, _P, C.c_int, C.c_int, C.c_int, _P]
+lib.dsk_linear_static.argtypes = [C.c_int, _P, _P, _P, _P, C.c_int, C.c_int, C.c_int, _P]
 lib.dsk_attention.argtypes = [C.c_int, _P, _P, _P, _P, C.POINTER(dsk_batch_t), C.POINTER(dsk_batch_t), C.c_int64,
                               C.c_int, C.c_int, C.c_int, _P, C.c_int64, _P]
 lib.dsk_set_option.argtypes = [C.c_char_p, C.c_int]
@@ -223,6 +224,10 @@ def dsk_linear(dtype: int, x, w, y, r, M: int, N: int, K: int, stream=None):
     _check(lib.dsk_linear(dtype, _ptr(x), _ptr(w), _ptr(y), _ptr(r), M, N, K, _stream(stream)), "dsk_linear")
 
 
+def dsk_linear_static(dtype: int, x, w, y, r, M: int, N: int, K: int, stream=None):
+    _check(lib.dsk_linear_static(dtype, _ptr(x), _ptr(w), _ptr(y), _ptr(r), M, N, K, _stream(stream)), "dsk_linear_static")
+
+
 def dsk_attention(dtype: int, q, k_rows, v_rows, out, queries: dsk_batch_t, prefix, own_row0: int, n_q_heads: int,
                   n_kv_heads: int, head_dim: int, scratch=None, stream=None):
     nbytes = 0 if scratch is None else scratch.numel() * scratch.element_size()
@@ -254,6 +259,8 @@ def dsk_set_load_throttle(model: int, gb_per_s: float):
 
 
 DSK_ENOENT = -6
+DSK_ELIMIT = -7
+DSK_STATIC_MAX_M, DSK_STATIC_MAX_N = 64, 65536
 DSK_TIER_AUTO, DSK_TIER_DEVICE, DSK_TIER_HOST = 0, 1, 2
 
 

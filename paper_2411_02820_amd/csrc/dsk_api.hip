@@ -3,9 +3,15 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 
 #include "dsk_internal.h"
+
+// Split-K partial sums of dsk_linear_static, the entry point for callers that cannot allocate: a fixed array in the
+// code object, one copy per GPU, held until the process ends.  In host code the name is only a handle for
+// hipGetSymbolAddress; kernels and copies get the per-device address that call returns.
+static __device__ __align__(256) unsigned char scratch[DSK_STATIC_SCRATCH_BYTES];
 
 thread_local int g_last_hip_error = 0;  // shared with the cache store
 
@@ -641,6 +647,37 @@ int dsk_linear(int dtype, const void* x, const void* w, void* y, const void* r, 
   return DSK_OK;
 }
 
+int dsk_linear_static(int dtype, const void* x, const void* w, void* y, const void* r, int M, int N, int K, void* stream) {
+  if (!x || !w || !y || M < 1 || N < 1 || K < 1) return DSK_EINVAL;
+  if (dtype != DSK_F32 && dtype != DSK_BF16) return DSK_EDTYPE;
+  if (!aligned16(x) || !aligned16(w) || !aligned16(y) || !aligned16(r)) return DSK_EINVAL;
+  if (M > DSK_STATIC_MAX_M || N > DSK_STATIC_MAX_N) return DSK_ELIMIT;
+  // the device's own copy of the array: looked up once per device, with that device current
+  constexpr int kMaxDevices = 64;
+  static void* dev_ptr[kMaxDevices] = {};
+  static std::mutex mu;
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return DSK_ELIMIT;
+  void* ptr = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(mu);
+    if (!dev_ptr[dev]) HIP_TRY(hipGetSymbolAddress(&dev_ptr[dev], HIP_SYMBOL(scratch)));
+    ptr = dev_ptr[dev];
+  }
+  const int epi = r ? EPI_RESIDUAL : EPI_STORE;
+  hipStream_t s = (hipStream_t)stream;
+  // no launch timing here (its event pool is allocated on first use); the kernels are those of dsk_linear
+  if (dtype == DSK_BF16 && !g_force_generic) {
+    HIP_TRY(launch_gemm_mfma_bf16(x, K, w, K, y, N, r, N, M, N, K, epi, ptr, DSK_STATIC_SCRATCH_BYTES, s));
+    ++g_stats.gemm_mfma;
+  } else {
+    HIP_TRY(launch_gemm_generic(dtype, x, K, w, K, y, N, r, N, M, N, K, epi, s));
+    ++g_stats.gemm_generic;
+  }
+  return DSK_OK;
+}
+
 int dsk_attention(int dtype, const void* q, const void* k_rows, const void* v_rows, void* out,
                   const dsk_batch_t* queries, const dsk_batch_t* prefix, int64_t own_row0, int n_q_heads,
                   int n_kv_heads, int head_dim, void* scratch, int64_t scratch_bytes, void* stream) {
@@ -732,6 +769,7 @@ const char* dsk_strerror(int status) {
     case DSK_ENOMEM: return "out of memory";
     case DSK_EHIP: return "HIP call failed";
     case DSK_ENOENT: return "no such entry in the cache store";
+    case DSK_ELIMIT: return "size beyond the fixed limit of this entry point";
     default: return "unknown status";
   }
 }
