@@ -144,7 +144,8 @@ DSK_API int dsk_fill_normal(void* dst_device, int64_t n, uint64_t seed, uint64_t
 
 /* Selective-layer prefill (Sec. 4.1; the partial_prefill interface of Sec. 4.4).
  *   hidden_in   [n_tokens, d]  E cache at the transition layer lo (the token embeddings when lo = 0);
- *               device, or pinned host (then it is transferred first, before any KV: Fig. 13(c)).
+ *               device, or pinned host (then it is transferred first, before any KV: Fig. 13(c); a long single
+ *               sequence arrives in row chunks and layer lo starts on the first chunk while the rest is in flight).
  *   kv_reused   the sender's cache, device or pinned host; may be NULL when lo=0 and hi=L.
  *   kv_out      device cache that receives, for lo <= l < hi, K and V recomputed by the receiver
  *               (rows 0..n_tokens-1), and for every other l a byte-exact copy of kv_reused's rows
@@ -312,12 +313,17 @@ DSK_API int dsk_attention(int dtype, const void* q, const void* k_rows, const vo
  *                from dsk_model_create, dsk_linear, dsk_attention), never a silent switch of kernels.
  *   "gemm_tiling": force one of the two prefill tilings of the bf16 GEMM on any M > 64 (default 0 = picked by
  *                size): 1 = 256x256 tiles on the 16x16x32 MFMA, 2 = 128x128 tiles on the 32x32x16 MFMA
+ *   "e_chunk_rows": how a host-resident E cache is cut into row chunks that the first recomputed layer follows as
+ *                they arrive: 0 (default) = 4096-row chunks where that keeps every result bit-identical to the
+ *                unchunked run (one sequence, bf16, chunks that still fill the chip), -1 = never, n > 0 (a multiple
+ *                of 256) = n-row chunks on any single-sequence bf16 call (results then agree within tolerance only)
  *   "time_gemm": 1 = bracket every tensor-core GEMM launch that runs on the 256 x 256 prefill tiling (at least
  *                192 such tiles) by a pair of HIP events on its stream (read back through dsk_get_stat)
  *   "reset_stats": any value; clears all counters and recorded timings */
 DSK_API int dsk_set_option(const char* name, int value);
 
-/* Counters since the last reset: "gemm_mfma_launches", "gemm_generic_launches", "attn_mfma_launches",
+/* Counters since the last reset: "e_cache_chunks" (row chunks of host-resident E caches that a first recomputed
+ * layer followed as they arrived), "gemm_mfma_launches", "gemm_generic_launches", "attn_mfma_launches",
  * "attn_generic_launches", "attn_key_split_launches" (tensor-core attention launches that split the keys over
  * workgroups) and, of those, "attn_packed_head_launches" (four q heads of a kv group per workgroup); and for the
  * launches bracketed under "time_gemm": "timed_gemm_launches",

@@ -462,9 +462,9 @@ __global__ void __launch_bounds__(64) attn_combine_kernel(const float* __restric
 // 64-row tiles.  valid(row) = row < n_pre || own_row0 <= row < own_row0 + n_own.
 __global__ void __launch_bounds__(256) transpose_v_kernel(const bf16_t* __restrict__ v_rows, bf16_t* __restrict__ vt,
                                                           int64_t ldvt, int width, int64_t n_pre, int64_t own_row0,
-                                                          int64_t n_own) {
+                                                          int64_t n_own, int64_t tile0) {
   __shared__ bf16_t tile[64][66];
-  const int64_t r0 = (int64_t)blockIdx.x * 64;
+  const int64_t r0 = ((int64_t)blockIdx.x + tile0) * 64;
   const int c0 = blockIdx.y * 64;
   const int tid = threadIdx.x;
   {
@@ -511,12 +511,12 @@ constexpr int64_t kMaxSplitRows = 4096;
 int64_t attn_mfma_workspace_bytes(int Hq, int dh) { return kMaxSplitRows * Hq * (dh + 2) * 4; }
 
 hipError_t launch_transpose_v(const void* v_rows, void* vt, int64_t ldvt, int width, int64_t n_pre, int64_t own_row0,
-                              int64_t n_own, hipStream_t s) {
-  const int64_t end = own_row0 + n_own;
-  if (end <= 0) return hipSuccess;
-  dim3 grid((unsigned)((end + 63) / 64), width / 64);
+                              int64_t n_own, int64_t first_row, hipStream_t s) {
+  const int64_t end = own_row0 + n_own, tile0 = first_row / 64;
+  if (end <= tile0 * 64) return hipSuccess;
+  dim3 grid((unsigned)((end + 63) / 64 - tile0), width / 64);
   hipLaunchKernelGGL(transpose_v_kernel, grid, dim3(256), 0, s, (const bf16_t*)v_rows, (bf16_t*)vt, ldvt, width, n_pre,
-                     own_row0, n_own);
+                     own_row0, n_own, tile0);
   return hipGetLastError();
 }
 

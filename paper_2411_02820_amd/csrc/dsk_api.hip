@@ -63,6 +63,9 @@ void free_model(dsk_model* m) {
   if (m->ev_e) (void)hipEventDestroy(m->ev_e);
   if (m->ev_stage_free) (void)hipEventDestroy(m->ev_stage_free);
   if (m->ev_all) (void)hipEventDestroy(m->ev_all);
+  for (int i = 0; i < DSK_MAX_E_CHUNKS; ++i)
+    if (m->ev_e_chunk[i]) (void)hipEventDestroy(m->ev_e_chunk[i]);
+  (void)hipFree(m->chunk_cu);
   if (m->load_stream) (void)hipStreamDestroy(m->load_stream);
   free(m->pending);
   free(m);
@@ -95,10 +98,12 @@ inline char* kv_v(const dsk_kv_t* kv, int l) { return kv_k(kv, l) + kv->v_offset
 
 int g_force_generic = 0;
 int g_time_gemm = 0;
+int g_e_chunk_rows = 0;  // test hook: 0 = chunk a host-resident E cache by the rule below, -1 = never, > 0 = this many rows
 
 // launch counters and the event pairs recorded under "time_gemm"
 struct Stats {
   int64_t gemm_mfma = 0, gemm_generic = 0, attn_mfma = 0, attn_generic = 0;
+  int64_t e_chunks = 0;  // row chunks of host-resident E caches that the first recomputed layer followed
   static constexpr int kMaxTimed = 8192;
   hipEvent_t* ev = nullptr;  // 2*kMaxTimed events, created on first use
   int n_timed = 0;
@@ -159,10 +164,15 @@ hipError_t attention(const dsk_model* m, const AttnArgs& a, hipStream_t s) { ret
 // state leaving the layer is written (may equal h_in).  K/V of the tokens go to rows own_row0.. of the
 // cache layer (k_rows, v_rows); attention additionally sees the prefix rows delimited by p_cu.
 // h_in is the model dtype unless h_in_f32; h_out likewise unless h_out_f32 (the workspace stream m->h is fp32).
+// h_mid: fp32 rows that receive the state after the attention block (h_out may be the same rows); cs: rotary table
+// of the n tokens.  vt_first_row: rows of the layer's V before it are already in the transposed copy m->vt.
 int run_layer(dsk_model* m, int l, const void* h_in, int h_in_f32, void* h_out, int h_out_f32, char* k_layer,
               char* v_layer, int64_t own_row0,
               const int32_t* q_cu, const int32_t* q_cu_host, const int32_t* p_cu, const int32_t* p_cu_host,
-              int64_t n_pre_rows, int n_seqs, int n, hipStream_t s) {
+              int64_t n_pre_rows, int n_seqs, int n, hipStream_t s, float* h_mid = nullptr, const float2* cs = nullptr,
+              int64_t vt_first_row = 0) {
+  if (!h_mid) h_mid = m->h;
+  if (!cs) cs = m->rope_cs;
   const dsk_config_t& c = m->cfg;
   const LayerWeights& w = m->layers[l];
   const int d = c.hidden, F = c.ffn, nq = c.n_q_heads * c.head_dim;
@@ -175,12 +185,12 @@ int run_layer(dsk_model* m, int l, const void* h_in, int h_in_f32, void* h_out, 
   // RMSNorm, are done by the split-K reduction of the projection in front of them
   const bool few_rows = c.dtype == DSK_BF16 && !g_force_generic && n <= 64 && m->gemm_ws;
   if (few_rows && gemm_small_m_rope_supported(n, d, c.n_q_heads, c.n_kv_heads, c.head_dim, d, d, m->n_qkv, m->gemm_ws_bytes)) {
-    HIP_TRY(launch_gemm_small_m_rope(m->xn, d, w.wqkv, d, m->qkv, m->n_qkv, m->rope_cs, k_own, v_own, n, d, c.n_q_heads,
+    HIP_TRY(launch_gemm_small_m_rope(m->xn, d, w.wqkv, d, m->qkv, m->n_qkv, cs, k_own, v_own, n, d, c.n_q_heads,
                                      c.n_kv_heads, c.head_dim, m->gemm_ws, m->gemm_ws_bytes, s));
     ++g_stats.gemm_mfma;
   } else {
     HIP_TRY(gemm(m, m->xn, d, w.wqkv, d, m->qkv, m->n_qkv, nullptr, 0, n, m->n_qkv, d, EPI_STORE, s));
-    HIP_TRY(launch_rope_kv_write(c.dtype, m->qkv, m->rope_cs, k_own, v_own, n, c.n_q_heads, c.n_kv_heads, c.head_dim, s));
+    HIP_TRY(launch_rope_kv_write(c.dtype, m->qkv, cs, k_own, v_own, n, c.n_q_heads, c.n_kv_heads, c.head_dim, s));
   }
   AttnArgs a;
   a.q = m->qkv; a.ldq = m->n_qkv; a.k_rows = k_layer; a.v_rows = v_layer; a.out = m->attn;
@@ -189,18 +199,18 @@ int run_layer(dsk_model* m, int l, const void* h_in, int h_in_f32, void* h_out, 
   a.Hq = c.n_q_heads; a.Hkv = c.n_kv_heads; a.dh = c.head_dim;
   a.vt = nullptr; a.ldvt = 0;
   if (m->vt && !g_force_generic) {
-    HIP_TRY(launch_transpose_v(v_layer, m->vt, m->ldvt, c.n_kv_heads * c.head_dim, n_pre_rows, own_row0, n, s));
+    HIP_TRY(launch_transpose_v(v_layer, m->vt, m->ldvt, c.n_kv_heads * c.head_dim, n_pre_rows, own_row0, n, vt_first_row, s));
     a.vt = m->vt; a.ldvt = m->ldvt;
   }
   HIP_TRY(attention(m, a, s));
   if (few_rows && gemm_small_m_rmsnorm_supported(n, d, nq, nq, nq, m->gemm_ws_bytes)) {
-    HIP_TRY(launch_gemm_small_m_rmsnorm(m->attn, nq, w.wo, nq, m->h, h_in, h_in_f32 ? 1 : 0, w.g2, m->xn, (float)c.rms_eps, n,
+    HIP_TRY(launch_gemm_small_m_rmsnorm(m->attn, nq, w.wo, nq, h_mid, h_in, h_in_f32 ? 1 : 0, w.g2, m->xn, (float)c.rms_eps, n,
                                         d, nq, m->gemm_ws, m->gemm_ws_bytes, s));
     ++g_stats.gemm_mfma;
   } else {
-    HIP_TRY(gemm(m, m->attn, nq, w.wo, nq, m->h, d, h_in, d, n, d, nq,
+    HIP_TRY(gemm(m, m->attn, nq, w.wo, nq, h_mid, d, h_in, d, n, d, nq,
                  EPI_RESIDUAL | EPI_C_F32 | ((h_in_f32 || all_f32) ? EPI_R_F32 : 0), s));
-    HIP_TRY(launch_rmsnorm(c.dtype, m->h, 1, w.g2, m->xn, n, d, (float)c.rms_eps, s));
+    HIP_TRY(launch_rmsnorm(c.dtype, h_mid, 1, w.g2, m->xn, n, d, (float)c.rms_eps, s));
   }
   if (c.dtype == DSK_BF16 && !g_force_generic && m->gu_block == 32 && gemm_mfma_swiglu_supported(n, 2 * F, d, m->gemm_ws ? m->gemm_ws_bytes : 0)) {
     HIP_TRY(gemm(m, m->xn, d, w.wgu, d, m->act, F, nullptr, 0, n, 2 * F, d, EPI_SWIGLU, s));  // SwiGLU in the epilogue
@@ -208,9 +218,38 @@ int run_layer(dsk_model* m, int l, const void* h_in, int h_in_f32, void* h_out, 
     HIP_TRY(gemm(m, m->xn, d, w.wgu, d, m->gu, 2 * (int64_t)F, nullptr, 0, n, 2 * F, d, EPI_STORE, s));
     HIP_TRY(launch_swiglu(c.dtype, m->gu, m->act, n, F, m->gu_block, s));
   }
-  HIP_TRY(gemm(m, m->act, F, w.wd, F, h_out, d, m->h, d, n, d, F,
+  HIP_TRY(gemm(m, m->act, F, w.wd, F, h_out, d, h_mid, d, n, d, F,
                EPI_RESIDUAL | EPI_R_F32 | ((h_out_f32 || all_f32) ? EPI_C_F32 : 0), s));
   return DSK_OK;
+}
+
+// A host-resident E cache arrives over the link in row chunks, and the first recomputed layer runs chunk by chunk
+// behind it (each chunk attends to the rows before it through the cache rows already written), so that all but the
+// first chunk's transfer hides under compute (Sec. 4.3, Fig. 13(c): recomputation starts when the E cache is there).
+// Returns the number of chunks (0 or 1: not chunked) and their row boundaries in bounds[0..n].
+// By itself the library chunks only where every row's result keeps its bits: one sequence, a bf16 model, chunks of
+// 4096 rows (a multiple of every tile) that each still fill the chip, i.e. run the same GEMM tiling and the same
+// unsplit attention as the whole prefix would.
+int plan_e_chunks(const dsk_model* m, int T, int n_seqs, int* bounds) {
+  const dsk_config_t& c = m->cfg;
+  if (g_e_chunk_rows < 0 || n_seqs != 1 || c.dtype != DSK_BF16 || g_force_generic || !m->vt) return 0;
+  int rows = g_e_chunk_rows;
+  if (rows == 0) {
+    rows = 4096;
+    const int widths[4] = {m->n_qkv, c.hidden, 2 * c.ffn, c.hidden};
+    for (int i = 0; i < 4; ++i)
+      if (!gemm_mfma_uses_prefill_tile(rows, widths[i])) return 0;
+    if ((int64_t)(rows / 128) * c.n_q_heads < 512) return 0;
+  }
+  if (rows % 256 || T < 2 * rows) return 0;
+  int n = T / rows;
+  if (n > DSK_MAX_E_CHUNKS) {
+    rows = ((T + DSK_MAX_E_CHUNKS - 1) / DSK_MAX_E_CHUNKS + 255) / 256 * 256;
+    n = T / rows;
+  }
+  for (int i = 0; i < n; ++i) bounds[i] = i * rows;
+  bounds[n] = T;  // the last chunk takes the remainder
+  return n;
 }
 
 struct TensorPlace { void* base; int64_t rows, cols; int map; int64_t row_off; };
@@ -302,6 +341,7 @@ int dsk_model_create(const dsk_config_t* cfg, int64_t max_tokens, int64_t max_kv
   if (rc == DSK_OK) rc = alloc_dev((void**)&m->h, T * d * 4, &m->workspace_bytes);
   if (rc == DSK_OK) rc = alloc_dev(&m->e_stage, T * d * elem, &m->workspace_bytes);
   if (rc == DSK_OK) rc = alloc_dev((void**)&m->pace_t0, 8, &m->workspace_bytes);
+  if (rc == DSK_OK) rc = alloc_dev((void**)&m->chunk_cu, DSK_MAX_E_CHUNKS * 4 * (int64_t)sizeof(int32_t), &m->workspace_bytes);
   if (rc == DSK_OK) rc = alloc_dev((void**)&m->rope_cs, T * half * (int64_t)sizeof(float2), &m->workspace_bytes);
   if (rc == DSK_OK) rc = alloc_dev((void**)&m->theta, half * (int64_t)sizeof(double), &m->workspace_bytes);
   const int64_t kvw = (int64_t)cfg->n_kv_heads * cfg->head_dim;
@@ -337,6 +377,7 @@ int dsk_model_create(const dsk_config_t* cfg, int64_t max_tokens, int64_t max_kv
     hip_ok(hipEventCreateWithFlags(&m->ev_stage_free, hipEventDisableTiming));
     hip_ok(hipEventCreateWithFlags(&m->ev_all, hipEventDisableTiming));
     for (int l = 0; l < L; ++l) hip_ok(hipEventCreateWithFlags(&m->ev_kv[l], hipEventDisableTiming));
+    for (int i = 0; i < DSK_MAX_E_CHUNKS; ++i) hip_ok(hipEventCreateWithFlags(&m->ev_e_chunk[i], hipEventDisableTiming));
   }
   if (rc != DSK_OK) {
     free_model(m);
@@ -489,8 +530,22 @@ int dsk_partial_prefill_groups(dsk_model_t* model, const dsk_group_t* groups, in
     HIP_TRY(hipEventRecord(m->ev_e, ls));
     return DSK_OK;
   };
-  if (n_groups > 0 && groups[0].hidden_in_mem == DSK_MEM_HOST_PINNED)
-    if ((rc = stage_e(groups[0]))) return rc;
+  int e_bounds[DSK_MAX_E_CHUNKS + 1];
+  int n_e_chunks = 0;
+  if (n_groups > 0 && groups[0].hidden_in_mem == DSK_MEM_HOST_PINNED) {
+    if (groups[0].hi > groups[0].lo && mode == DSK_LOAD_PIPELINED) n_e_chunks = plan_e_chunks(m, T, batch->n_seqs, e_bounds);
+    if (n_e_chunks > 1) {
+      const int64_t row_b = (int64_t)c.hidden * m->elem;
+      for (int ch = 0; ch < n_e_chunks; ++ch) {
+        const int64_t off = e_bounds[ch] * row_b;
+        if ((rc = load_copy(m, (char*)m->e_stage + off, (const char*)groups[0].hidden_in + off,
+                            (e_bounds[ch + 1] - e_bounds[ch]) * row_b, hipMemcpyHostToDevice)))
+          return rc;
+        HIP_TRY(hipEventRecord(m->ev_e_chunk[ch], ls));
+      }
+      HIP_TRY(hipEventRecord(m->ev_e, ls));
+    } else if ((rc = stage_e(groups[0]))) return rc;
+  }
 
   // reused layers, ascending (the order the suffix prefill consumes them), one event per layer
   memset(m->pending, 0, L);
@@ -518,8 +573,10 @@ int dsk_partial_prefill_groups(dsk_model_t* model, const dsk_group_t* groups, in
   for (int g = 0; g < n_groups; ++g) {
     const dsk_group_t& G = groups[g];
     const void* h_cur = G.hidden_in;
+    const bool chunked = g == 0 && n_e_chunks > 1;
     if (G.hidden_in_mem == DSK_MEM_HOST_PINNED) {
-      HIP_TRY(hipStreamWaitEvent(s, m->ev_e, 0));  // this group's copy into the staging buffer (recorded above / below)
+      // this group's copy into the staging buffer (recorded above / below); a chunked one is waited for chunk by chunk
+      if (!chunked) HIP_TRY(hipStreamWaitEvent(s, m->ev_e, 0));
       h_cur = m->e_stage;
     }
     // the next host-resident E cache may enter the staging buffer once this group's first layer has read
@@ -538,6 +595,28 @@ int dsk_partial_prefill_groups(dsk_model_t* model, const dsk_group_t* groups, in
       for (int l = G.lo; l < G.hi; ++l) {
         const bool last = l == G.hi - 1 && G.hidden_out;
         void* h_next = last ? G.hidden_out : (void*)m->h;
+        if (chunked && l == G.lo) {
+          // the first layer, chunk by chunk behind the arriving E cache: rows before the chunk are a fully visible
+          // prefix range of the cache layer, the chunk's own rows the causal range
+          const int half = c.head_dim / 2;
+          for (int ch = 0; ch < n_e_chunks; ++ch) {
+            const int r0 = e_bounds[ch], n = e_bounds[ch + 1] - r0;
+            const int32_t p_host[2] = {0, r0}, q_host[2] = {0, n};
+            int32_t* cu = m->chunk_cu + 4 * ch;
+            HIP_TRY(launch_set_int4(cu, 0, r0, 0, n, s));
+            HIP_TRY(hipStreamWaitEvent(s, m->ev_e_chunk[ch], 0));
+            const char* h_in = (const char*)m->e_stage + (int64_t)r0 * c.hidden * m->elem;
+            float* h_mid = m->h + (int64_t)r0 * c.hidden;
+            void* h_out = last ? (void*)((char*)G.hidden_out + (int64_t)r0 * c.hidden * m->elem) : (void*)h_mid;
+            rc = run_layer(m, l, h_in, 0, h_out, !last, kv_k(kv_out, l), kv_v(kv_out, l), r0, cu + 2, q_host, cu, p_host, r0, 1,
+                           n, s, h_mid, m->rope_cs + (int64_t)r0 * half, r0);
+            if (rc) return rc;
+            ++g_stats.e_chunks;
+          }
+          h_cur = h_next;
+          if (next_host && (rc = hand_over_stage())) return rc;
+          continue;
+        }
         rc = run_layer(m, l, h_cur, l > G.lo, h_next, !last, kv_k(kv_out, l), kv_v(kv_out, l), 0, batch->cu_seqlens_dev,
                        batch->cu_seqlens_host, nullptr, nullptr, 0, batch->n_seqs, T, s);
         if (rc) return rc;
@@ -708,7 +787,7 @@ int dsk_attention(int dtype, const void* q, const void* k_rows, const void* v_ro
     // the caller asked for the tensor-core kernel: a shape it does not handle is an error, not a slower kernel
     if (kvw % 64 || (head_dim != 64 && head_dim != 128) || scratch_bytes < kvw * rows64 * 2) return DSK_ESHAPE;
     HIP_TRY(launch_transpose_v(v_rows, scratch, rows64, (int)kvw, prefix ? prefix->n_tokens : 0, own_row0,
-                               queries->n_tokens, (hipStream_t)stream));
+                               queries->n_tokens, 0, (hipStream_t)stream));
     a.vt = scratch; a.ldvt = rows64;
   }
   HIP_TRY(attention_any(dtype, a, (hipStream_t)stream));
@@ -720,10 +799,13 @@ int dsk_set_option(const char* name, int value) {
   if (!strcmp(name, "gemm_tiling")) {
     if (value < 0 || value > 2) return DSK_EINVAL;
     gemm_mfma_set_variant(value);
+  } else if (!strcmp(name, "e_chunk_rows")) {
+    if (value < -1 || (value > 0 && value % 256)) return DSK_EINVAL;
+    g_e_chunk_rows = value;
   } else if (!strcmp(name, "force_generic")) g_force_generic = value;
   else if (!strcmp(name, "time_gemm")) g_time_gemm = value;
   else if (!strcmp(name, "reset_stats")) {
-    g_stats.gemm_mfma = g_stats.gemm_generic = g_stats.attn_mfma = g_stats.attn_generic = 0;
+    g_stats.gemm_mfma = g_stats.gemm_generic = g_stats.attn_mfma = g_stats.attn_generic = g_stats.e_chunks = 0;
     g_stats.n_timed = 0;
     g_stats.timed_flops = 0.0;
     attn_mfma_counts(nullptr, nullptr, 1);
@@ -737,6 +819,7 @@ int dsk_get_stat(const char* name, double* value) {
   else if (!strcmp(name, "gemm_generic_launches")) *value = (double)g_stats.gemm_generic;
   else if (!strcmp(name, "attn_mfma_launches")) *value = (double)g_stats.attn_mfma;
   else if (!strcmp(name, "attn_generic_launches")) *value = (double)g_stats.attn_generic;
+  else if (!strcmp(name, "e_cache_chunks")) *value = (double)g_stats.e_chunks;
   else if (!strcmp(name, "attn_key_split_launches") || !strcmp(name, "attn_packed_head_launches")) {
     int64_t split = 0, packed = 0;
     attn_mfma_counts(&split, &packed, 0);

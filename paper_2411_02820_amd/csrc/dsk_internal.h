@@ -28,6 +28,8 @@ struct LayerWeights {
   void* wd;    // [d, F]
 };
 
+constexpr int DSK_MAX_E_CHUNKS = 16;
+
 struct dsk_model {
   dsk_config_t cfg;
   int elem;         // bytes per element
@@ -57,6 +59,8 @@ struct dsk_model {
   // load pipeline
   hipStream_t load_stream;
   hipEvent_t ev_entry, ev_e, ev_all, ev_stage_free;
+  hipEvent_t ev_e_chunk[DSK_MAX_E_CHUNKS];  // arrival of the row chunks of a host-resident E cache
+  int32_t* chunk_cu;                        // device [DSK_MAX_E_CHUNKS][4]: {0, rows before the chunk, 0, rows of the chunk}
   hipEvent_t* ev_kv;        // [L]
   unsigned char* pending;   // [L] 1 if ev_kv[l] must be waited for by the suffix
   int any_pending;
@@ -124,9 +128,12 @@ hipError_t launch_attn_generic(int dtype, const AttnArgs& a, hipStream_t s);
 hipError_t launch_attn_mfma_bf16(const AttnArgs& a, hipStream_t s);
 int64_t attn_mfma_workspace_bytes(int Hq, int dh);
 // vt[(c)*ldvt + row] = v_rows[row][c] for valid rows (row < n_pre or own_row0 <= row < own_row0+n_own), 0 otherwise,
-// over whole 64-row tiles up to own_row0+n_own; width = Hkv*dh must be a multiple of 64.
+// over the whole 64-row tiles from the one that holds first_row up to own_row0+n_own (earlier tiles of vt are left as
+// they are); width = Hkv*dh must be a multiple of 64.
 hipError_t launch_transpose_v(const void* v_rows, void* vt, int64_t ldvt, int width, int64_t n_pre, int64_t own_row0,
-                              int64_t n_own, hipStream_t s);
+                              int64_t n_own, int64_t first_row, hipStream_t s);
+// cu[0..3] = {a, b, c, d} on the device (sequence boundaries of a row chunk, set in stream order)
+hipError_t launch_set_int4(int32_t* dst, int a, int b, int c, int d, hipStream_t s);
 
 hipError_t launch_fill_normal(void* dst, int64_t n, uint64_t seed, uint64_t stream_id, float std, float offset,
                               int64_t idx0, int dtype, hipStream_t s);

@@ -184,6 +184,15 @@ __global__ void pace_wait_kernel(const unsigned long long* t0, unsigned long lon
 
 }  // namespace
 
+static __global__ void set_int4_kernel(int32_t* dst, int a, int b, int c, int d) {
+  if (threadIdx.x == 0) { dst[0] = a; dst[1] = b; dst[2] = c; dst[3] = d; }
+}
+
+hipError_t launch_set_int4(int32_t* dst, int a, int b, int c, int d, hipStream_t s) {
+  hipLaunchKernelGGL(set_int4_kernel, dim3(1), dim3(64), 0, s, dst, a, b, c, d);
+  return hipGetLastError();
+}
+
 hipError_t launch_pace_start(unsigned long long* t0, hipStream_t s) {
   hipLaunchKernelGGL(pace_start_kernel, dim3(1), dim3(1), 0, s, t0);
   return hipGetLastError();

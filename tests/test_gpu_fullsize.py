@@ -329,7 +329,9 @@ def test_config4_8b_prefix16384_kv_in_pinned_host_memory(G, B):
         kv_r = device_kv_cache(B, shape, T, T, pinned=True)
         assert kv_r.numel() * 2 == 2 << 30
         e_host = G.to_dev(hidden_host, shape, pinned=True)
+        B.dsk_set_option("reset_stats", 0)
         kv_out, h_out = m.partial(e_host, lo, hi, kv_r, [T], n_rows=T + S, flags=B.DSK_DEFER_JOIN)
+        assert B.dsk_get_stat("e_cache_chunks") == 4, "layer 4 follows the E cache in four 4096-row chunks"
         xs = device_normal(B, (S, shape.hidden), synth.SEED_SUFFIX, 0)
         hs = m.suffix(xs, kv_out, [T], [S])
         torch.cuda.synchronize()
@@ -347,7 +349,8 @@ def test_config4_8b_prefix16384_kv_in_pinned_host_memory(G, B):
         # the last one (256 key tiles, every query-tile position of the heavy-first launch order)
         check_one_layer_full_length(G, m, shape, e_host, hidden_host, lo, kv_r, [T],
                                     [0, 127, 128, 5000, 8191, 8192, 12345, 16320, 16383], kv_of_l=kv_out[lo])
-        # the three loading strategies give the same bits
+        # the three loading strategies give the same bits; "load everything first" also runs layer 4 in one piece,
+        # so this is the chunked first layer against the unchunked one, bit for bit
         B.dsk_set_load_mode(m.handle, B.DSK_LOAD_ALL_FIRST)
         kv_2, h_2 = m.partial(e_host, lo, hi, kv_r, [T], n_rows=T + S)
         torch.cuda.synchronize()

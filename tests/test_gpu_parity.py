@@ -350,6 +350,47 @@ def test_deferred_join_then_suffix(G):
         assert torch.equal(kv_a, kv_b)
 
 
+def test_first_layer_follows_the_e_cache_chunk_by_chunk(G):
+    # A host-resident E cache is transferred in row chunks and the first recomputed layer runs chunk by chunk
+    # behind it (Sec. 4.3, Fig. 13(c)).  Forced here on a small model with 256-row chunks (the last one ragged):
+    # against the oracle, and against the unchunked run of the same call.
+    from paper_2411_02820_amd import binding as B
+    shape, lens, lo, hi = SMALL_BF16, [1100], 1, 3
+    cfg = oracle_config(shape)
+    T = lens[0]
+    hidden_in = synth.hidden_states(shape, T)
+    kv_r = synth.kv_cache(shape, T)
+    w = weights_fn(shape, synth.SEED_RECEIVER)
+    with G.GpuModel(shape, T) as m:
+        m.load_from_generator(synth.SEED_RECEIVER)
+        e_host = G.to_dev(hidden_in, shape, pinned=True)
+        kv_dev = G.to_dev(kv_r, shape)
+        B.dsk_set_option("e_chunk_rows", 256)
+        B.dsk_set_option("reset_stats", 0)
+        try:
+            kv_c, h_c = m.partial(e_host, lo, hi, kv_dev, lens)
+            torch.cuda.synchronize()
+            assert B.dsk_get_stat("e_cache_chunks") == 4
+            kv_1, h_1 = m.partial(e_host, lo, lo + 1, kv_dev, lens)   # a one-layer group: chunks write hidden_out directly
+            torch.cuda.synchronize()
+        finally:
+            B.dsk_set_option("e_chunk_rows", 0)
+        kv_u, h_u = m.partial(e_host, lo, hi, kv_dev, lens)           # too short for the library's own rule: unchunked
+        torch.cuda.synchronize()
+        assert B.dsk_get_stat("e_cache_chunks") == 8
+        kv_ref, h_ref = O.partial_prefill(cfg, w, hidden_in.astype(np.float64), lo, hi, kv_list(kv_r), synth.packed_positions(lens),
+                                          synth.cu_seqlens(lens))
+        for l in range(lo, hi):
+            for j in range(2):
+                assert O.max_rel_err(G.to_np(kv_c[l, j]), kv_ref[l][j]) <= TOL["bf16"], (l, j)
+        assert O.max_rel_err(G.to_np(h_c), h_ref) <= TOL["bf16"]
+        assert torch.equal(kv_c[0], kv_dev[0]) and torch.equal(kv_1[lo], kv_c[lo])
+        assert O.max_rel_err(G.to_np(kv_c), G.to_np(kv_u)) <= 1e-2 and O.max_rel_err(G.to_np(h_c), G.to_np(h_u)) <= 1e-2
+        _, h_1u = m.partial(e_host, lo, lo + 1, kv_dev, lens)
+        torch.cuda.synchronize()
+        assert O.max_rel_err(G.to_np(h_1), G.to_np(h_1u)) <= 1e-2
+
+
 def test_second_deferred_call_does_not_drop_the_first_calls_loads(G):
     # Call A defers its join; call B on the same model (another output cache, a group that starts at layer 0, so
     # that nothing of B waits for a load) defers as well and reuses the per-layer events; A's suffix pass follows.
