@@ -257,6 +257,32 @@ def test_config3_8b_ragged_batch(G, B):
         assert O.max_rel_err(G.to_np(h1[e - 1:e]), h_ref) <= TOL
 
 
+def test_8b_ragged_batch_at_its_maximum_lengths(G, B):
+    # workload 3 draws its lengths from [1024, 8192]: eight prefixes of 8192 tokens (65 536 packed rows) are the
+    # largest batch it can produce.  One recomputed layer; the first and the last sequence of the batch (all their
+    # K/V rows, sampled rows of the layer output incl. their last rows) against the oracle run on that sequence
+    # alone - a packed batch equals its sequences run separately.
+    shape, n, l = synth.LLAMA_8B, 8192, 12
+    lens = [n] * 8
+    T = sum(lens)
+    cfg = oracle_config(shape)
+    hidden_host = synth.hidden_states(shape, T)
+    with G.GpuModel(shape, T) as m:
+        m.init_random(synth.SEED_RECEIVER)
+        kv = torch.empty((shape.n_layers, 2, T, shape.n_kv_heads, shape.head_dim), dtype=torch.bfloat16, device="cuda")
+        kv_out, h_out = m.partial(G.to_dev(hidden_host, shape), l, l + 1, kv, lens, kv_out=kv)
+        torch.cuda.synchronize()
+        w = host_layer(shape, synth.SEED_RECEIVER, l)
+        rows = [0, 1, 4095, 4096, 8190, 8191]
+        for b in (0, 7):
+            s0 = b * n
+            h_ref, K, V = O.prefix_layer(cfg, w, hidden_host[s0:s0 + n].astype(np.float64), np.arange(n), np.array([0, n]), rows=rows)
+            errs = {"K": O.max_rel_err(G.to_np(kv_out[l, 0, s0:s0 + n]), K), "V": O.max_rel_err(G.to_np(kv_out[l, 1, s0:s0 + n]), V),
+                    "hidden_rows": O.max_rel_err(G.to_np(h_out[s0:s0 + n])[rows], h_ref)}
+            print(f"sequence {b} of 8 x {n}: max-rel-err:", {k: f"{v:.2e}" for k, v in errs.items()})
+            assert max(errs.values()) <= TOL, errs
+
+
 def test_8b_shape_suffix_ragged_against_oracle(G, B):
     # the 8B layer shape with 3 layers: ragged prefixes, 128-token suffixes, whole suffix pass against the oracle
     shape = synth.ModelShape(3, 4096, 32, 8, 128, 14336, 500000.0, 1e-5, "bf16")
