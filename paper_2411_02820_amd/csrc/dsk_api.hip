@@ -3,6 +3,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <atomic>
 #include <mutex>
 #include <new>
 
@@ -100,10 +101,12 @@ int g_force_generic = 0;
 int g_time_gemm = 0;
 int g_e_chunk_rows = 0;  // test hook: 0 = chunk a host-resident E cache by the rule below, -1 = never, > 0 = this many rows
 
-// launch counters and the event pairs recorded under "time_gemm"
+// Launch counters (atomic: models on different host threads share them) and the event pairs recorded under
+// "time_gemm" (a benchmark hook; the timed list is guarded by its mutex)
 struct Stats {
-  int64_t gemm_mfma = 0, gemm_generic = 0, attn_mfma = 0, attn_generic = 0;
-  int64_t e_chunks = 0;  // row chunks of host-resident E caches that the first recomputed layer followed
+  std::atomic<int64_t> gemm_mfma{0}, gemm_generic{0}, attn_mfma{0}, attn_generic{0};
+  std::atomic<int64_t> e_chunks{0};  // row chunks of host-resident E caches that the first recomputed layer followed
+  std::mutex timed_mu;
   static constexpr int kMaxTimed = 8192;
   hipEvent_t* ev = nullptr;  // 2*kMaxTimed events, created on first use
   int n_timed = 0;
@@ -113,6 +116,8 @@ struct Stats {
 hipError_t gemm_any(int dtype, const void* A, int64_t lda, const void* W, int64_t ldw, void* C, int64_t ldc,
                     const void* R, int64_t ldr, int M, int N, int K, int epi, void* ws, int64_t ws_bytes, hipStream_t s) {
   if (dtype == DSK_BF16 && !g_force_generic) {
+    std::unique_lock<std::mutex> timed_lock(g_stats.timed_mu, std::defer_lock);
+    if (g_time_gemm) timed_lock.lock();
     const bool timed = g_time_gemm && gemm_mfma_uses_prefill_tile(M, N) && g_stats.n_timed < Stats::kMaxTimed;
     if (timed) {
       if (!g_stats.ev) {
@@ -714,6 +719,8 @@ int dsk_linear(int dtype, const void* x, const void* w, void* y, const void* r, 
   // (calls that overlap on different streams would share it: this entry point is for tests and micro-benchmarks)
   static void* ws = nullptr;
   static int64_t ws_bytes = 0;
+  static std::mutex ws_mu;
+  std::lock_guard<std::mutex> ws_lock(ws_mu);  // host threads take turns; the buffer itself is still one per process
   const bool may_split = M <= 4096;  // the K-split paths are for few and for a few hundred token rows
   if (dtype == DSK_BF16 && may_split && gemm_mfma_workspace_bytes(N) > ws_bytes) {
     if (ws) HIP_TRY(hipFree(ws));
@@ -805,7 +812,8 @@ int dsk_set_option(const char* name, int value) {
   } else if (!strcmp(name, "force_generic")) g_force_generic = value;
   else if (!strcmp(name, "time_gemm")) g_time_gemm = value;
   else if (!strcmp(name, "reset_stats")) {
-    g_stats.gemm_mfma = g_stats.gemm_generic = g_stats.attn_mfma = g_stats.attn_generic = g_stats.e_chunks = 0;
+    g_stats.gemm_mfma = 0; g_stats.gemm_generic = 0; g_stats.attn_mfma = 0; g_stats.attn_generic = 0; g_stats.e_chunks = 0;
+    std::lock_guard<std::mutex> timed_lock(g_stats.timed_mu);
     g_stats.n_timed = 0;
     g_stats.timed_flops = 0.0;
     attn_mfma_counts(nullptr, nullptr, 1);
@@ -815,11 +823,11 @@ int dsk_set_option(const char* name, int value) {
 
 int dsk_get_stat(const char* name, double* value) {
   if (!name || !value) return DSK_EINVAL;
-  if (!strcmp(name, "gemm_mfma_launches")) *value = (double)g_stats.gemm_mfma;
-  else if (!strcmp(name, "gemm_generic_launches")) *value = (double)g_stats.gemm_generic;
-  else if (!strcmp(name, "attn_mfma_launches")) *value = (double)g_stats.attn_mfma;
-  else if (!strcmp(name, "attn_generic_launches")) *value = (double)g_stats.attn_generic;
-  else if (!strcmp(name, "e_cache_chunks")) *value = (double)g_stats.e_chunks;
+  if (!strcmp(name, "gemm_mfma_launches")) *value = (double)g_stats.gemm_mfma.load();
+  else if (!strcmp(name, "gemm_generic_launches")) *value = (double)g_stats.gemm_generic.load();
+  else if (!strcmp(name, "attn_mfma_launches")) *value = (double)g_stats.attn_mfma.load();
+  else if (!strcmp(name, "attn_generic_launches")) *value = (double)g_stats.attn_generic.load();
+  else if (!strcmp(name, "e_cache_chunks")) *value = (double)g_stats.e_chunks.load();
   else if (!strcmp(name, "attn_key_split_launches") || !strcmp(name, "attn_packed_head_launches")) {
     int64_t split = 0, packed = 0;
     attn_mfma_counts(&split, &packed, 0);
@@ -828,6 +836,7 @@ int dsk_get_stat(const char* name, double* value) {
   else if (!strcmp(name, "timed_gemm_launches")) *value = (double)g_stats.n_timed;
   else if (!strcmp(name, "timed_gemm_flops")) *value = g_stats.timed_flops;
   else if (!strcmp(name, "timed_gemm_ms")) {
+    std::lock_guard<std::mutex> timed_lock(g_stats.timed_mu);
     double total = 0.0;
     for (int i = 0; i < g_stats.n_timed; ++i) {
       HIP_TRY(hipEventSynchronize(g_stats.ev[2 * i + 1]));
