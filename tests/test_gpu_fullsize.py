@@ -14,6 +14,7 @@ import torch
 
 from oracle import dsk_oracle as O
 from paper_2411_02820_amd import synth
+from tests import bf16_storage_model as SM
 from tests.helpers import oracle_config
 
 pytestmark = pytest.mark.gpu
@@ -154,6 +155,36 @@ def check_truncated(G, shape, kv_out, h_out, hidden_in_host, lo, hi_checked, len
         errs["hidden"] = O.max_rel_err(G.to_np(h_out.index_select(0, rows_t)), h_ref)
     print("max-rel-err:", {k: f"{v:.2e}" for k, v in errs.items()})
     assert max(errs.values()) <= TOL, errs
+
+
+def check_truncated_deep(G, shape, kv_out, h_out, hidden_in_host, lo, hi, T, t_trunc, first_strict):
+    """Every recomputed layer of a deep group on the first t_trunc tokens, against the fp64 oracle and against the
+    oracle's arithmetic on bf16-rounded operands (tests/bf16_storage_model.py: what the number format alone costs).
+    The benchmark spec's 2e-2 must hold for the first `first_strict` layers; beyond, where bf16 operands alone exceed it,
+    the device may be at most half as far again from the oracle as the storage model is."""
+    cfg = oracle_config(shape)
+    pos, cu = np.arange(t_trunc), np.array([0, t_trunc])
+    h_ref = hidden_in_host[:t_trunc].astype(np.float64)
+    h_mod = h_ref.copy()
+    worst = {}
+    for l in range(lo, hi):
+        w = host_layer(shape, synth.SEED_RECEIVER, l)
+        h_ref, K, V = O.prefix_layer(cfg, w, h_ref, pos, cu)
+        h_mod, Km, Vm = SM.prefix_layer(cfg, w, h_mod, pos, cu)
+        del w
+        gK, gV = G.to_np(kv_out[l, 0, :t_trunc]), G.to_np(kv_out[l, 1, :t_trunc])
+        e_gpu = max(O.max_rel_err(gK, K), O.max_rel_err(gV, V))
+        e_mod = max(O.max_rel_err(Km, K), O.max_rel_err(Vm, V))
+        d = max(O.max_rel_err(gK, Km), O.max_rel_err(gV, Vm))
+        print(f"layer {l}: device vs oracle {e_gpu:.2e}, bf16-operand model vs oracle {e_mod:.2e}, device vs model {d:.2e}", flush=True)
+        worst[l] = (e_gpu, e_mod, d)
+        bound = TOL if l < lo + first_strict else max(TOL, 1.5 * e_mod)
+        assert e_gpu <= bound, (l, e_gpu, e_mod)
+    if h_out is not None:
+        e_gpu, e_mod = O.max_rel_err(G.to_np(h_out[:t_trunc]), h_ref), O.max_rel_err(h_mod, h_ref)
+        print(f"hidden_out: device vs oracle {e_gpu:.2e}, bf16-operand model vs oracle {e_mod:.2e}", flush=True)
+        assert e_gpu <= max(TOL, 1.5 * e_mod)
+    return worst
 
 
 def test_config2_8b_prefix4096_layers_8_16(G, B):
@@ -410,6 +441,11 @@ def test_config5_70b_prefix8192_layers_20_36(G, B):
         for kind in (synth.WQ, synth.WD):
             assert np.array_equal(m.get_tensor(lo, kind).float().cpu().numpy(), synth.layer_tensor(shape, 0, lo, kind))
         check_truncated(G, shape, kv_out, None, hidden_host, lo, lo + 2, [T], 64)
+        # All 16 recomputed layers on the first 64 tokens.  With N(0, 0.02) weights at this width every layer adds
+        # 2-4e-3 of max-rel-err (attention scores with a standard deviation of 3.3, an activation stream that grows
+        # from layer to layer): the first three layers are inside 2e-2; by layer 36 the fp64 oracle evaluated on
+        # bf16-rounded operands is itself 4e-2 from the exact one, and the device follows it.
+        check_truncated_deep(G, shape, kv_out, h_out, hidden_host, lo, hi, T, 64, first_strict=3)
         # the first recomputed layer at full length: K/V of all 8192 rows, the layer output at sampled rows
         check_one_layer_full_length(G, m, shape, hidden_dev, hidden_host, lo, kv_r, [T],
                                     [0, 255, 256, 3000, 4095, 4096, 7000, 8100, 8191], kv_of_l=kv_out[lo])
