@@ -400,8 +400,8 @@ def test_config4_8b_prefix16384_kv_in_pinned_host_memory(G, B):
                                                   synth.packed_positions([S], start=[T]), synth.cu_seqlens([T]),
                                                   synth.cu_seqlens([S]), T, [0])
         check_suffix_kv(G, kv_out, T, rows, ref, "C4")
-        # first two recomputed layers on a truncated prefix (the whole chain is covered at 4096 tokens)
-        check_truncated(G, shape, kv_out, None, hidden_host, lo, lo + 2, [T], 128)
+        # the whole recomputed chain [4,12) on the first 128 tokens, final hidden state included
+        check_truncated(G, shape, kv_out, h_out, hidden_host, lo, hi, [T], 128)
         # the first recomputed layer at full length: K/V of all 16384 rows, the layer output at sampled rows up to
         # the last one (256 key tiles, every query-tile position of the heavy-first launch order)
         check_one_layer_full_length(G, m, shape, e_host, hidden_host, lo, kv_r, [T],
