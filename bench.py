@@ -243,6 +243,7 @@ def main():
     gemm_ms = B.dsk_get_stat("timed_gemm_ms")
     gemm_n = B.dsk_get_stat("timed_gemm_launches")
     gemm_flops = B.dsk_get_stat("timed_gemm_flops")
+    attn_ms, attn_n, attn_flops = (B.dsk_get_stat("timed_attn_" + k) for k in ("ms", "launches", "flops"))
 
     # ---- phase split, full-prefill comparison (outside the timed region) ----
     def partial_joined():
@@ -377,6 +378,13 @@ def main():
         out["roofline"] = {"bound": "alu", "achieved": round(flops / (t_partial * 1e-3) / 1e12, 3), "peak": 157.3,
                            "unit": "TFLOP/s", "frac": round(flops / (t_partial * 1e-3) / 157.3e12, 5), "traffic": None,
                            "kernel": "fp32 plain-ALU path (latency bound at this size)"}
+    if shape.dtype == "bf16" and attn_n > 0:
+        a_tf = attn_flops / (attn_ms * 1e-3) / 1e12
+        out["roofline_attention"] = {"bound": "mfma", "achieved": round(a_tf, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                                     "frac": round(a_tf / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                                     "kernel": "attn_bf16_kernel<128,false,4> (causal attention over the prefix; HIP events in the timed steps)",
+                                     "launches": int(attn_n), "avg_launch_ms": round(attn_ms / attn_n, 4),
+                                     "flops_per_launch": round(attn_flops / attn_n / 1e9, 1), "flops_unit": "GFLOP (causal)"}
     # The suffix pass streams every weight once and reads the prefix K/V of every layer: HBM-bound (few rows).
     kv_layer_bytes = 2 * T * shape.kv_width * shape.elem_bytes
     suffix_bytes = B.dsk_model_weight_bytes(model) + L * kv_layer_bytes

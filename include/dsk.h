@@ -318,7 +318,8 @@ DSK_API int dsk_attention(int dtype, const void* q, const void* k_rows, const vo
  *                unchunked run (one sequence, bf16, chunks that still fill the chip), -1 = never, n > 0 (a multiple
  *                of 256) = n-row chunks on any single-sequence bf16 call (results then agree within tolerance only)
  *   "time_gemm": 1 = bracket every tensor-core GEMM launch that runs on the 256 x 256 prefill tiling (at least
- *                192 such tiles) by a pair of HIP events on its stream (read back through dsk_get_stat)
+ *                192 such tiles), and every tensor-core attention launch of the prefix pass (at least 1024 query rows, no earlier rows), by a pair
+ *                of HIP events on its stream (read back through dsk_get_stat)
  *   "reset_stats": any value; clears all counters and recorded timings */
 DSK_API int dsk_set_option(const char* name, int value);
 
@@ -326,8 +327,9 @@ DSK_API int dsk_set_option(const char* name, int value);
  * layer followed as they arrived), "gemm_mfma_launches", "gemm_generic_launches", "attn_mfma_launches",
  * "attn_generic_launches", "attn_key_split_launches" (tensor-core attention launches that split the keys over
  * workgroups) and, of those, "attn_packed_head_launches" (four q heads of a kv group per workgroup); and for the
- * launches bracketed under "time_gemm": "timed_gemm_launches",
- * "timed_gemm_ms" (sum of their durations; waits for them to finish), "timed_gemm_flops" (sum of 2*M*N*K). */
+ * launches bracketed under "time_gemm": "timed_gemm_launches", "timed_gemm_ms" (sum of their durations; waits for
+ * them to finish), "timed_gemm_flops" (sum of 2*M*N*K), and the same three as "timed_attn_..." for the attention
+ * launches (flops = 4*Hq*dh per (query, visible key) pair, i.e. causal). */
 DSK_API int dsk_get_stat(const char* name, double* value);
 
 /* Sizes, for callers that budget memory. */

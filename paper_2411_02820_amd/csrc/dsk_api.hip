@@ -102,33 +102,62 @@ int g_time_gemm = 0;
 int g_e_chunk_rows = 0;  // test hook: 0 = chunk a host-resident E cache by the rule below, -1 = never, > 0 = this many rows
 
 // Launch counters (atomic: models on different host threads share them) and the event pairs recorded under
-// "time_gemm" (a benchmark hook; the timed list is guarded by its mutex)
+// "time_gemm" (a benchmark hook; the timed lists are guarded by their mutex): one list for the prefill GEMM
+// launches, one for the attention launches over the prefix (at least 1024 query rows)
+struct TimedList {
+  static constexpr int kMax = 8192;
+  hipEvent_t* ev = nullptr;  // 2*kMax events, created on first use
+  int n = 0;
+  double flops = 0.0;
+  // records the start event of the next launch; false when the list is full
+  hipError_t begin(hipStream_t s, bool* on) {
+    *on = false;
+    if (n >= kMax) return hipSuccess;
+    if (!ev) {
+      ev = (hipEvent_t*)calloc(2 * kMax, sizeof(hipEvent_t));
+      if (!ev) return hipErrorOutOfMemory;
+      for (int i = 0; i < 2 * kMax; ++i) {
+        hipError_t e = hipEventCreate(&ev[i]);
+        if (e != hipSuccess) return e;
+      }
+    }
+    *on = true;
+    return hipEventRecord(ev[2 * n], s);
+  }
+  hipError_t end(hipStream_t s, double launch_flops) {
+    hipError_t e = hipEventRecord(ev[2 * n + 1], s);
+    flops += launch_flops;
+    ++n;
+    return e;
+  }
+  int total_ms(double* ms_out) {
+    double total = 0.0;
+    for (int i = 0; i < n; ++i) {
+      HIP_TRY(hipEventSynchronize(ev[2 * i + 1]));
+      float ms = 0.f;
+      HIP_TRY(hipEventElapsedTime(&ms, ev[2 * i], ev[2 * i + 1]));
+      total += ms;
+    }
+    *ms_out = total;
+    return DSK_OK;
+  }
+};
+
 struct Stats {
   std::atomic<int64_t> gemm_mfma{0}, gemm_generic{0}, attn_mfma{0}, attn_generic{0};
   std::atomic<int64_t> e_chunks{0};  // row chunks of host-resident E caches that the first recomputed layer followed
   std::mutex timed_mu;
-  static constexpr int kMaxTimed = 8192;
-  hipEvent_t* ev = nullptr;  // 2*kMaxTimed events, created on first use
-  int n_timed = 0;
-  double timed_flops = 0.0;
+  TimedList gemm, attn;
 } g_stats;
 
 hipError_t gemm_any(int dtype, const void* A, int64_t lda, const void* W, int64_t ldw, void* C, int64_t ldc,
                     const void* R, int64_t ldr, int M, int N, int K, int epi, void* ws, int64_t ws_bytes, hipStream_t s) {
   if (dtype == DSK_BF16 && !g_force_generic) {
     std::unique_lock<std::mutex> timed_lock(g_stats.timed_mu, std::defer_lock);
-    if (g_time_gemm) timed_lock.lock();
-    const bool timed = g_time_gemm && gemm_mfma_uses_prefill_tile(M, N) && g_stats.n_timed < Stats::kMaxTimed;
-    if (timed) {
-      if (!g_stats.ev) {
-        g_stats.ev = (hipEvent_t*)calloc(2 * Stats::kMaxTimed, sizeof(hipEvent_t));
-        if (!g_stats.ev) return hipErrorOutOfMemory;
-        for (int i = 0; i < 2 * Stats::kMaxTimed; ++i) {
-          hipError_t ee = hipEventCreate(&g_stats.ev[i]);
-          if (ee != hipSuccess) return ee;
-        }
-      }
-      hipError_t ee = hipEventRecord(g_stats.ev[2 * g_stats.n_timed], s);
+    bool timed = false;
+    if (g_time_gemm && gemm_mfma_uses_prefill_tile(M, N)) {
+      timed_lock.lock();
+      hipError_t ee = g_stats.gemm.begin(s, &timed);
       if (ee != hipSuccess) return ee;
     }
     // a shape the tensor-core kernels refuse comes back as hipErrorNotSupported (the caller's DSK_ESHAPE): a bf16
@@ -136,11 +165,7 @@ hipError_t gemm_any(int dtype, const void* A, int64_t lda, const void* W, int64_
     hipError_t e = launch_gemm_mfma_bf16(A, lda, W, ldw, C, ldc, R, ldr, M, N, K, epi, ws, ws_bytes, s);
     if (e == hipSuccess) {
       ++g_stats.gemm_mfma;
-      if (timed) {
-        e = hipEventRecord(g_stats.ev[2 * g_stats.n_timed + 1], s);
-        g_stats.timed_flops += 2.0 * M * N * K;
-        ++g_stats.n_timed;
-      }
+      if (timed) e = g_stats.gemm.end(s, 2.0 * M * N * K);
     }
     return e;
   }
@@ -155,8 +180,27 @@ hipError_t gemm(const dsk_model* m, const void* A, int64_t lda, const void* W, i
 
 hipError_t attention_any(int dtype, const AttnArgs& a, hipStream_t s) {
   if (dtype == DSK_BF16 && !g_force_generic && a.vt) {  // no transposed V: the caller chose the plain kernel
+    std::unique_lock<std::mutex> timed_lock(g_stats.timed_mu, std::defer_lock);
+    bool timed = false;
+    if (g_time_gemm && a.n_q >= 1024 && !a.p_cu) {  // the prefix pass: causal self-attention, no earlier rows
+      timed_lock.lock();
+      hipError_t ee = g_stats.attn.begin(s, &timed);
+      if (ee != hipSuccess) return ee;
+    }
     hipError_t e = launch_attn_mfma_bf16(a, s);
-    if (e == hipSuccess) ++g_stats.attn_mfma;
+    if (e == hipSuccess) {
+      ++g_stats.attn_mfma;
+      if (timed) {
+        // algorithmic flops: every query row against the keys it may see (causal), 4*Hq*dh per (query, key) pair
+        double pairs = 0.0;
+        for (int b = 0; b < a.n_seqs; ++b) {
+          const double len = a.q_cu_host[b + 1] - a.q_cu_host[b];
+          const double pre = a.p_cu_host ? a.p_cu_host[b + 1] - a.p_cu_host[b] : 0.0;
+          pairs += len * (len + 1.0) / 2.0 + len * pre;
+        }
+        e = g_stats.attn.end(s, 4.0 * a.Hq * a.dh * pairs);
+      }
+    }
     return e;
   }
   ++g_stats.attn_generic;
@@ -814,8 +858,8 @@ int dsk_set_option(const char* name, int value) {
   else if (!strcmp(name, "reset_stats")) {
     g_stats.gemm_mfma = 0; g_stats.gemm_generic = 0; g_stats.attn_mfma = 0; g_stats.attn_generic = 0; g_stats.e_chunks = 0;
     std::lock_guard<std::mutex> timed_lock(g_stats.timed_mu);
-    g_stats.n_timed = 0;
-    g_stats.timed_flops = 0.0;
+    g_stats.gemm.n = g_stats.attn.n = 0;
+    g_stats.gemm.flops = g_stats.attn.flops = 0.0;
     attn_mfma_counts(nullptr, nullptr, 1);
   } else return DSK_EINVAL;
   return DSK_OK;
@@ -833,18 +877,14 @@ int dsk_get_stat(const char* name, double* value) {
     attn_mfma_counts(&split, &packed, 0);
     *value = (double)(name[5] == 'k' ? split : packed);
   }
-  else if (!strcmp(name, "timed_gemm_launches")) *value = (double)g_stats.n_timed;
-  else if (!strcmp(name, "timed_gemm_flops")) *value = g_stats.timed_flops;
-  else if (!strcmp(name, "timed_gemm_ms")) {
+  else if (!strncmp(name, "timed_gemm_", 11) || !strncmp(name, "timed_attn_", 11)) {
     std::lock_guard<std::mutex> timed_lock(g_stats.timed_mu);
-    double total = 0.0;
-    for (int i = 0; i < g_stats.n_timed; ++i) {
-      HIP_TRY(hipEventSynchronize(g_stats.ev[2 * i + 1]));
-      float ms = 0.f;
-      HIP_TRY(hipEventElapsedTime(&ms, g_stats.ev[2 * i], g_stats.ev[2 * i + 1]));
-      total += ms;
-    }
-    *value = total;
+    TimedList& t = name[6] == 'g' ? g_stats.gemm : g_stats.attn;
+    const char* what = name + 11;
+    if (!strcmp(what, "launches")) *value = (double)t.n;
+    else if (!strcmp(what, "flops")) *value = t.flops;
+    else if (!strcmp(what, "ms")) return t.total_ms(value);
+    else return DSK_EINVAL;
   } else return DSK_EINVAL;
   return DSK_OK;
 }
