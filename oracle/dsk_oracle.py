@@ -17,7 +17,9 @@ The paper is silent on the layer itself ("same architecture"); the readings take
 pre-norm residual blocks, RMSNorm with eps inside the square root, half-split RoPE
 pairing (i, i+dh/2) with theta_i = base^(-2i/dh), K cached after RoPE and V as projected,
 contiguous GQA groups (kv head = q head // (Hq/Hkv)), softmax scale 1/sqrt(dh), SwiGLU
-MLP, no biases.
+MLP, no biases.  For the mixture-of-experts receiver of Sec. 5.4 (Mixtral) the MLP is a
+router over E expert SwiGLU MLPs: top-k experts by router logit, gate weights = softmax
+over the chosen logits, ties to the lower expert index; attention and KV are unchanged.
 
 Every function here is pinned by tests/test_oracle_*.py against something that is not
 this file: hand-worked values, closed forms, invariants, an explicit T x T brute-force
@@ -44,6 +46,8 @@ class Config:
     ffn: int
     rope_base: float
     rms_eps: float = 1e-5
+    n_experts: int = 0  # 0: dense SwiGLU MLP; > 0: that many expert MLPs behind a router
+    top_k: int = 0      # experts per token
 
 
 def rmsnorm(x, g, eps):
@@ -66,6 +70,43 @@ def rope(x, positions, base):
 
 def silu(z):
     return z / (1.0 + np.exp(-z))
+
+
+def swiglu_mlp(y, wg, wu, wd):
+    """(silu(y Wg^T) * (y Wu^T)) Wd^T for token rows y [n, d]."""
+    return (silu(y @ wg.T) * (y @ wu.T)) @ wd.T
+
+
+def moe_route(y, router, top_k):
+    """Expert choice of every token (Sec. 5.4, the mixture-of-experts receiver; routing as in Mixtral).
+
+    y [n, d] normalised hidden states, router [E, d].  Returns (logits [n, E], experts [n, top_k], gates
+    [n, top_k]): the top_k experts of a token by router logit, highest first, equal logits going to the lower
+    expert index, and the softmax of those top_k logits (the same numbers as a softmax over all E logits
+    renormalised over the chosen ones)."""
+    logits = y @ router.T
+    n, E = logits.shape
+    experts = np.empty((n, top_k), dtype=np.int64)
+    gates = np.empty((n, top_k), dtype=logits.dtype)
+    for i in range(n):
+        order = sorted(range(E), key=lambda e: (-logits[i, e], e))[:top_k]
+        chosen = logits[i, order]
+        p = np.exp(chosen - chosen.max())
+        experts[i] = order
+        gates[i] = p / p.sum()
+    return logits, experts, gates
+
+
+def moe_mlp(y, router, experts_w, top_k):
+    """Sparse mixture-of-experts MLP: every token goes through its top_k experts' SwiGLU MLPs and the results are
+    added with the gate weights.  experts_w[e] = dict(wg, wu, wd) of expert e.  Returns [n, d]."""
+    _, experts, gates = moe_route(y, router, top_k)
+    out = np.zeros((y.shape[0], experts_w[0]["wd"].shape[0]), dtype=y.dtype)
+    for i in range(y.shape[0]):
+        for j in range(top_k):
+            ew = experts_w[experts[i, j]]
+            out[i] += gates[i, j] * swiglu_mlp(y[i:i + 1], ew["wg"], ew["wu"], ew["wd"])[0]
+    return out
 
 
 def attend_row(q_t, K, V):
@@ -110,7 +151,9 @@ def layer_rows(cfg, w, h_rows, pos_rows, visible):
         attn[i] = attend_row(q[i], K_i, V_i).reshape(-1)
     h1 = h_rows + attn @ w["wo"].T
     y = rmsnorm(h1, w["g2"], cfg.rms_eps)
-    return h1 + (silu(y @ w["wg"].T) * (y @ w["wu"].T)) @ w["wd"].T
+    if "router" in w:
+        return h1 + moe_mlp(y, w["router"], w["experts"], cfg.top_k)
+    return h1 + swiglu_mlp(y, w["wg"], w["wu"], w["wd"])
 
 
 def _seq_of_rows(cu_seqlens, T):

@@ -42,7 +42,9 @@ LANE_SUM_STD = math.sqrt(8.0 * (2.0**32 - 1.0) / 12.0)
 
 # tensor kinds inside one decoder layer; weight stream id = layer*16 + kind
 G1, WQ, WK, WV, WO, G2, WG, WU, WD = range(9)
+WR = 9  # router of a mixture-of-experts layer
 TENSOR_NAMES = ("g1", "wq", "wk", "wv", "wo", "g2", "wg", "wu", "wd")
+EXPERT_STREAM0 = 1 << 20  # expert tensors: stream EXPERT_STREAM0 + (layer*64 + expert)*4 + {0: wg, 1: wu, 2: wd}
 
 # seed plan for the synthetic workloads
 SEED_RECEIVER = 0
@@ -154,13 +156,15 @@ class ModelShape:
     rope_base: float
     rms_eps: float = 1e-5
     dtype: str = "bf16"  # "f32" or "bf16"
+    n_experts: int = 0   # 0: dense MLP; E > 0: E expert MLPs of width F behind a router [E, d]
+    top_k: int = 0       # experts per token
 
     def tensor_shape(self, kind: int) -> tuple:
         d, hq, hkv, dh, f = self.hidden, self.n_q_heads, self.n_kv_heads, self.head_dim, self.ffn
         return {
             G1: (d,), G2: (d,),
             WQ: (hq * dh, d), WK: (hkv * dh, d), WV: (hkv * dh, d),
-            WO: (d, hq * dh), WG: (f, d), WU: (f, d), WD: (d, f),
+            WO: (d, hq * dh), WG: (f, d), WU: (f, d), WD: (d, f), WR: (self.n_experts, d),
         }[kind]
 
     @property
@@ -175,6 +179,8 @@ class ModelShape:
 TINY = ModelShape(4, 256, 4, 2, 64, 688, 10000.0, 1e-5, "f32")
 LLAMA_8B = ModelShape(32, 4096, 32, 8, 128, 14336, 500000.0, 1e-5, "bf16")
 LLAMA_70B = ModelShape(80, 8192, 64, 8, 128, 28672, 500000.0, 1e-5, "bf16")
+TINY_MOE = ModelShape(3, 256, 4, 2, 64, 320, 10000.0, 1e-5, "f32", 4, 2)
+MIXTRAL_8X7B = ModelShape(32, 4096, 32, 8, 128, 14336, 1000000.0, 1e-5, "bf16", 8, 2)
 
 WEIGHT_STD = 0.02
 
@@ -193,8 +199,25 @@ def layer_tensor(shape: ModelShape, seed: int, layer: int, kind: int) -> np.ndar
     return normal(n, seed, weight_stream(layer, kind), WEIGHT_STD, offset, shape.dtype).reshape(tshape)
 
 
+def expert_stream(layer: int, expert: int, kind: int) -> int:
+    return EXPERT_STREAM0 + (layer * 64 + expert) * 4 + {WG: 0, WU: 1, WD: 2}[kind]
+
+
+def expert_tensor(shape: ModelShape, seed: int, layer: int, expert: int, kind: int) -> np.ndarray:
+    """WG, WU or WD of one expert of a mixture-of-experts layer, [out, in] row-major, N(0, 0.02)."""
+    tshape = shape.tensor_shape(kind)
+    return normal(int(np.prod(tshape)), seed, expert_stream(layer, expert, kind), WEIGHT_STD, 0.0,
+                  shape.dtype).reshape(tshape)
+
+
 def layer_weights(shape: ModelShape, seed: int, layer: int) -> dict:
-    return {TENSOR_NAMES[k]: layer_tensor(shape, seed, layer, k) for k in range(9)}
+    if shape.n_experts == 0:
+        return {TENSOR_NAMES[k]: layer_tensor(shape, seed, layer, k) for k in range(9)}
+    w = {TENSOR_NAMES[k]: layer_tensor(shape, seed, layer, k) for k in (G1, WQ, WK, WV, WO, G2)}
+    w["router"] = layer_tensor(shape, seed, layer, WR)
+    w["experts"] = [{TENSOR_NAMES[k]: expert_tensor(shape, seed, layer, e, k) for k in (WG, WU, WD)}
+                    for e in range(shape.n_experts)]
+    return w
 
 
 def hidden_states(shape: ModelShape, n_tokens: int, seed: int = SEED_HIDDEN, stream: int = 0) -> np.ndarray:

@@ -9,7 +9,7 @@ from paper_2411_02820_amd import synth
 
 def oracle_config(shape: synth.ModelShape) -> O.Config:
     return O.Config(shape.n_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads,
-                    shape.head_dim, shape.ffn, shape.rope_base, shape.rms_eps)
+                    shape.head_dim, shape.ffn, shape.rope_base, shape.rms_eps, shape.n_experts, shape.top_k)
 
 
 def weights_fn(shape: synth.ModelShape, seed: int, dtype=np.float64, cache=None):
@@ -18,7 +18,10 @@ def weights_fn(shape: synth.ModelShape, seed: int, dtype=np.float64, cache=None)
 
     def get(l):
         if l not in cache:
-            cache[l] = {k: v.astype(dtype) for k, v in synth.layer_weights(shape, seed, l).items()}
+            w = synth.layer_weights(shape, seed, l)
+            cache[l] = {k: v.astype(dtype) for k, v in w.items() if k != "experts"}
+            if "experts" in w:
+                cache[l]["experts"] = [{k: v.astype(dtype) for k, v in e.items()} for e in w["experts"]]
         return cache[l]
     return get
 
