@@ -61,8 +61,14 @@ typedef enum { DSK_MEM_DEVICE = 0, DSK_MEM_HOST_PINNED = 1 } dsk_mem;
  * G1,G2 [d]; WQ [Hq*dh, d]; WK,WV [Hkv*dh, d]; WO [d, Hq*dh]; WG,WU [F, d]; WD [d, F]. */
 typedef enum {
   DSK_G1 = 0, DSK_WQ = 1, DSK_WK = 2, DSK_WV = 3, DSK_WO = 4,
-  DSK_G2 = 5, DSK_WG = 6, DSK_WU = 7, DSK_WD = 8
+  DSK_G2 = 5, DSK_WG = 6, DSK_WU = 7, DSK_WD = 8,
+  DSK_WR = 9 /* router [E, d] of a mixture-of-experts layer */
 } dsk_tensor;
+/* Mixture-of-experts models (n_experts > 0) have no layer-wide WG/WU/WD; expert e's are addressed as
+ * DSK_EXPERT(e, DSK_WG | DSK_WU | DSK_WD) wherever a tensor id is taken. */
+#define DSK_EXPERT(e, t) (16 + (e) * 16 + (t))
+#define DSK_MOE_MAX_EXPERTS 64
+#define DSK_MOE_MAX_TOP_K 8
 
 /* Llama-style decoder: pre-norm residual blocks, RMSNorm (eps inside the root), rotary
  * embedding on pairs (i, i+dh/2) with theta_i = rope_base^(-2i/dh), grouped-query causal
@@ -77,6 +83,12 @@ typedef struct {
   double rope_base;
   double rms_eps;
   int32_t dtype;      /* dsk_dtype */
+  /* Mixture-of-experts receiver (Sec. 5.4, Mixtral): the MLP of every layer is n_experts SwiGLU MLPs of width F
+   * behind a router; a token goes through its top_k experts by router logit (equal logits: lower index first) and
+   * their outputs are added with the softmax of those top_k logits.  Attention and the KV cache are as in the dense
+   * model, so everything the selective prefill does with caches is unchanged.  0 / 0: dense MLP. */
+  int32_t n_experts;  /* E <= DSK_MOE_MAX_EXPERTS */
+  int32_t top_k;      /* 1 <= top_k <= min(E, DSK_MOE_MAX_TOP_K) */
 } dsk_config_t;
 
 /* A per-layer KV cache (Sec. 4.4: the cache is split into layers).  Layer l's keys are
@@ -132,8 +144,9 @@ DSK_API int dsk_model_get_tensor(const dsk_model_t* model, int layer, int tensor
 
 /* Fills all weights on the device with the counter-based generator of dsk_fill_normal:
  * tensor `t` of layer `l` is stream l*16+t, element index = out*in_dim + in; projection
- * matrices N(0, std), norm gains 1 + N(0, std).  For synthetic workloads (the 70B shape
- * cannot be staged through host memory). */
+ * matrices N(0, std), norm gains 1 + N(0, std); WG, WU, WD of expert e are streams
+ * 2^20 + (l*64 + e)*4 + {0, 1, 2}.  For synthetic workloads (the 70B shape cannot be staged
+ * through host memory). */
 DSK_API int dsk_model_init_random(dsk_model_t* model, uint64_t seed, float std, void* stream);
 
 /* dst[i] = offset + std * z(seed, stream_id, idx0 + i), i < n, rounded to dtype; z is an
@@ -305,6 +318,13 @@ DSK_API int dsk_linear_static(int dtype, const void* x, const void* w, void* y, 
 DSK_API int dsk_attention(int dtype, const void* q, const void* k_rows, const void* v_rows, void* out,
                           const dsk_batch_t* queries, const dsk_batch_t* prefix, int64_t own_row0, int n_q_heads,
                           int n_kv_heads, int head_dim, void* scratch, int64_t scratch_bytes, void* stream);
+
+/* Router of a mixture-of-experts layer (Sec. 5.4; routing as in Mixtral) on its own: for token rows x [n, d] and
+ * router weights wr [E, d] (both `dtype`, device) writes the top_k experts of every token by fp32 router logit,
+ * highest first, equal logits to the lower index (experts_out int32 [n, top_k]) and the softmax of those logits
+ * (gates_out fp32 [n, top_k]).  d a multiple of 8; limits as in dsk_config_t, else DSK_ESHAPE. */
+DSK_API int dsk_moe_route(int dtype, const void* x, const void* wr, int n, int d, int n_experts, int top_k,
+                          int32_t* experts_out, float* gates_out, void* stream);
 
 /* ---- hooks for tests and benchmarks (process-wide, not thread-safe; no production caller needs them) ----
  * Unknown names and out-of-range values return DSK_EINVAL.

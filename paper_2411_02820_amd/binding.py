@@ -40,6 +40,7 @@ EXPORTS = (
     "dsk_strerror", "dsk_last_hip_error", "dsk_hash_context", "dsk_store_create", "dsk_store_destroy",
     "dsk_store_put_kv", "dsk_store_put_e", "dsk_store_fetch_kv_layer", "dsk_store_fetch_kv", "dsk_store_fetch_e",
     "dsk_store_erase", "dsk_store_usage", "dsk_estimate_prefill_ms", "dsk_select_recompute", "dsk_linear", "dsk_linear_static", "dsk_attention", "dsk_set_option", "dsk_get_stat",
+    "dsk_moe_route",
 )
 
 
@@ -60,7 +61,8 @@ class dsk_latency_model_t(C.Structure):
 class dsk_config_t(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("hidden", C.c_int32), ("n_q_heads", C.c_int32),
                 ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("ffn", C.c_int32),
-                ("rope_base", C.c_double), ("rms_eps", C.c_double), ("dtype", C.c_int32)]
+                ("rope_base", C.c_double), ("rms_eps", C.c_double), ("dtype", C.c_int32),
+                ("n_experts", C.c_int32), ("top_k", C.c_int32)]
 
 
 class dsk_kv_t(C.Structure):
@@ -91,6 +93,7 @@ lib.dsk_linear.argtypes = [C.c_int, _P, _P, _P, _P, C.c_int, C.c_int, C.c_int, _
 lib.dsk_linear_static.argtypes = [C.c_int, _P, _P, _P, _P, C.c_int, C.c_int, C.c_int, _P]
 lib.dsk_attention.argtypes = [C.c_int, _P, _P, _P, _P, C.POINTER(dsk_batch_t), C.POINTER(dsk_batch_t), C.c_int64,
                               C.c_int, C.c_int, C.c_int, _P, C.c_int64, _P]
+lib.dsk_moe_route.argtypes = [C.c_int, _P, _P, C.c_int, C.c_int, C.c_int, C.c_int, _P, _P, _P]
 lib.dsk_set_option.argtypes = [C.c_char_p, C.c_int]
 lib.dsk_get_stat.argtypes = [C.c_char_p, C.POINTER(C.c_double)]
 lib.dsk_join_loads.argtypes = [_P, _P]
@@ -236,6 +239,15 @@ def dsk_attention(dtype: int, q, k_rows, v_rows, out, queries: dsk_batch_t, pref
                              _ptr(scratch), nbytes, _stream(stream)), "dsk_attention")
 
 
+def dsk_moe_route(dtype: int, x, wr, n: int, d: int, n_experts: int, top_k: int, experts_out, gates_out, stream=None):
+    _check(lib.dsk_moe_route(dtype, _ptr(x), _ptr(wr), n, d, n_experts, top_k, _ptr(experts_out), _ptr(gates_out),
+                             _stream(stream)), "dsk_moe_route")
+
+
+def DSK_EXPERT(e: int, t: int) -> int:
+    return 16 + e * 16 + t
+
+
 def dsk_set_option(name: str, value: int):
     _check(lib.dsk_set_option(name.encode(), value), "dsk_set_option")
 
@@ -355,7 +367,8 @@ def dsk_model_workspace_bytes(model: int) -> int:
 def config_from_shape(shape) -> dsk_config_t:
     """shape: an object with n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, rope_base, rms_eps, dtype."""
     return dsk_config_t(shape.n_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.ffn,
-                        float(shape.rope_base), float(shape.rms_eps), DSK_F32 if shape.dtype == "f32" else DSK_BF16)
+                        float(shape.rope_base), float(shape.rms_eps), DSK_F32 if shape.dtype == "f32" else DSK_BF16,
+                        getattr(shape, "n_experts", 0), getattr(shape, "top_k", 0))
 
 
 def kv_desc(t) -> dsk_kv_t:

@@ -49,7 +49,7 @@ void free_model(dsk_model* m) {
     for (int l = 0; l < m->cfg.n_layers; ++l) {
       LayerWeights& w = m->layers[l];
       (void)hipFree(w.g1); (void)hipFree(w.wqkv); (void)hipFree(w.wo);
-      (void)hipFree(w.g2); (void)hipFree(w.wgu); (void)hipFree(w.wd);
+      (void)hipFree(w.g2); (void)hipFree(w.wgu); (void)hipFree(w.wd); (void)hipFree(w.wr);
     }
     free(m->layers);
   }
@@ -67,6 +67,8 @@ void free_model(dsk_model* m) {
   for (int i = 0; i < DSK_MAX_E_CHUNKS; ++i)
     if (m->ev_e_chunk[i]) (void)hipEventDestroy(m->ev_e_chunk[i]);
   (void)hipFree(m->chunk_cu);
+  (void)hipFree(m->moe_experts); (void)hipFree(m->moe_gates); (void)hipFree(m->moe_slot); (void)hipFree(m->moe_src);
+  (void)hipFree(m->moe_tab); (void)hipFree(m->moe_xg); (void)hipFree(m->moe_y);
   if (m->load_stream) (void)hipStreamDestroy(m->load_stream);
   free(m->pending);
   free(m);
@@ -209,6 +211,51 @@ hipError_t attention_any(int dtype, const AttnArgs& a, hipStream_t s) {
 
 hipError_t attention(const dsk_model* m, const AttnArgs& a, hipStream_t s) { return attention_any(m->cfg.dtype, a, s); }
 
+// The MLP of a mixture-of-experts layer (Sec. 5.4; routing as in Mixtral) over the n normalised rows in m->xn:
+// h_out = h_mid + sum over the token's top_k experts of gate * SwiGLU-MLP_e(xn).  On the tensor-core path with more
+// than 64 rows the (token, expert) pairs are grouped by expert and the two projections run once over all experts;
+// otherwise (few rows: every expert's weights are streamed anyway; fp32 models) every expert runs over all rows and
+// the sum picks the chosen ones.
+int run_moe_mlp(dsk_model* m, const LayerWeights& w, int n, const float* h_mid, void* h_out, int out_f32, hipStream_t s) {
+  const dsk_config_t& c = m->cfg;
+  const int d = c.hidden, F = c.ffn, E = c.n_experts, k = c.top_k;
+  const int64_t wgu_stride = 2 * (int64_t)F * d, wd_stride = (int64_t)d * F;  // elements per expert
+  HIP_TRY(launch_moe_route(c.dtype, m->xn, w.wr, m->moe_experts, m->moe_gates, n, d, E, k, s));
+  const bool tensor_cores = c.dtype == DSK_BF16 && !g_force_generic;
+  if (tensor_cores && n > 64) {
+    if (m->gu_block != 32) return DSK_ESHAPE;
+    int tile_rows = (int)(((int64_t)n * k + 255) / 256) + E;
+    if (tile_rows > m->moe_tile_rows) tile_rows = m->moe_tile_rows;
+    HIP_TRY(launch_moe_place(m->moe_experts, m->moe_slot, m->moe_src, m->moe_tab, n, k, E, 256, tile_rows, s));
+    HIP_TRY(launch_moe_gather(c.dtype, m->xn, m->moe_src, m->moe_xg, n * k, n, d, s));
+    HIP_TRY(launch_gemm_mfma_grouped(m->moe_xg, d, (int64_t)n * k, w.wgu, d, wgu_stride, m->act, F, 2 * F, d, EPI_SWIGLU,
+                                     m->moe_tab, tile_rows, s));
+    HIP_TRY(launch_gemm_mfma_grouped(m->act, F, (int64_t)n * k, w.wd, F, wd_stride, m->moe_y, d, d, F, EPI_C_F32,
+                                     m->moe_tab, tile_rows, s));
+    g_stats.gemm_mfma += 2;
+    HIP_TRY(launch_moe_combine(m->moe_y, h_mid, m->moe_gates, m->moe_experts, m->moe_slot, h_out, out_f32, n, d, k,
+                               (int64_t)n * k, s));
+    return DSK_OK;
+  }
+  if ((int64_t)E * n > m->moe_y_rows) return DSK_EINVAL;
+  const bool fused_swiglu = tensor_cores && m->gu_block == 32 &&
+                            gemm_mfma_swiglu_supported(n, 2 * F, d, m->gemm_ws ? m->gemm_ws_bytes : 0);
+  for (int e = 0; e < E; ++e) {
+    const char* wgu = (const char*)w.wgu + e * wgu_stride * m->elem;
+    const char* wd = (const char*)w.wd + e * wd_stride * m->elem;
+    if (fused_swiglu) {
+      HIP_TRY(gemm(m, m->xn, d, wgu, d, m->act, F, nullptr, 0, n, 2 * F, d, EPI_SWIGLU, s));
+    } else {
+      HIP_TRY(gemm(m, m->xn, d, wgu, d, m->gu, 2 * (int64_t)F, nullptr, 0, n, 2 * F, d, EPI_STORE, s));
+      HIP_TRY(launch_swiglu(c.dtype, m->gu, m->act, n, F, m->gu_block, s));
+    }
+    HIP_TRY(gemm(m, m->act, F, wd, F, m->moe_y + (int64_t)e * n * d, d, nullptr, 0, n, d, F, EPI_C_F32, s));
+  }
+  HIP_TRY(launch_moe_combine(m->moe_y, h_mid, m->moe_gates, m->moe_experts, nullptr, h_out, out_f32, n, d, k,
+                             (int64_t)E * n, s));
+  return DSK_OK;
+}
+
 // One decoder layer over n token rows.  h_in: residual stream entering the layer; h_out: where the
 // state leaving the layer is written (may equal h_in).  K/V of the tokens go to rows own_row0.. of the
 // cache layer (k_rows, v_rows); attention additionally sees the prefix rows delimited by p_cu.
@@ -261,6 +308,7 @@ int run_layer(dsk_model* m, int l, const void* h_in, int h_in_f32, void* h_out, 
                  EPI_RESIDUAL | EPI_C_F32 | ((h_in_f32 || all_f32) ? EPI_R_F32 : 0), s));
     HIP_TRY(launch_rmsnorm(c.dtype, h_mid, 1, w.g2, m->xn, n, d, (float)c.rms_eps, s));
   }
+  if (c.n_experts > 0) return run_moe_mlp(m, w, n, h_mid, h_out, h_out_f32 || all_f32, s);
   if (c.dtype == DSK_BF16 && !g_force_generic && m->gu_block == 32 && gemm_mfma_swiglu_supported(n, 2 * F, d, m->gemm_ws ? m->gemm_ws_bytes : 0)) {
     HIP_TRY(gemm(m, m->xn, d, w.wgu, d, m->act, F, nullptr, 0, n, 2 * F, d, EPI_SWIGLU, s));  // SwiGLU in the epilogue
   } else {
@@ -308,6 +356,25 @@ int place_tensor(const dsk_model* m, int layer, int tensor, TensorPlace* p) {
   const dsk_config_t& c = m->cfg;
   const LayerWeights& w = m->layers[layer];
   const int64_t d = c.hidden, nq = (int64_t)c.n_q_heads * c.head_dim, nkv = (int64_t)c.n_kv_heads * c.head_dim, F = c.ffn;
+  if (c.n_experts > 0) {
+    // a mixture-of-experts layer: router, and WG/WU/WD per expert under DSK_EXPERT(e, t)
+    if (tensor == DSK_WG || tensor == DSK_WU || tensor == DSK_WD) return DSK_EINVAL;
+    if (tensor == DSK_WR) { *p = {w.wr, c.n_experts, d, 0, 0}; return DSK_OK; }
+    if (tensor >= 16) {
+      const int e = (tensor - 16) / 16, t = (tensor - 16) % 16;
+      if (e >= c.n_experts) return DSK_EINVAL;
+      char* gu = (char*)w.wgu + (int64_t)e * 2 * F * d * m->elem;
+      char* dn = (char*)w.wd + (int64_t)e * d * F * m->elem;
+      switch (t) {
+        case DSK_WG: *p = {gu, F, d, 1, 0}; return DSK_OK;
+        case DSK_WU: *p = {gu, F, d, 2, 0}; return DSK_OK;
+        case DSK_WD: *p = {dn, d, F, 0, 0}; return DSK_OK;
+        default: return DSK_EINVAL;
+      }
+    }
+  } else if (tensor == DSK_WR || tensor >= 16) {
+    return DSK_EINVAL;
+  }
   switch (tensor) {
     case DSK_G1: *p = {w.g1, 1, d, 0, 0}; break;
     case DSK_G2: *p = {w.g2, 1, d, 0, 0}; break;
@@ -339,6 +406,11 @@ int dsk_model_create(const dsk_config_t* cfg, int64_t max_tokens, int64_t max_kv
   const int per16 = 16 / elem;
   if (cfg->hidden % per16 || cfg->ffn % per16 || cfg->head_dim % per16) return DSK_ESHAPE;
   if (!(cfg->rope_base > 0.0) || !(cfg->rms_eps >= 0.0)) return DSK_EINVAL;
+  if (cfg->n_experts < 0 || cfg->n_experts > DSK_MOE_MAX_EXPERTS) return DSK_ESHAPE;
+  if (cfg->n_experts == 0 ? cfg->top_k != 0
+                          : (cfg->top_k < 1 || cfg->top_k > cfg->n_experts || cfg->top_k > DSK_MOE_MAX_TOP_K || cfg->hidden % 8))
+    return DSK_ESHAPE;
+  const int E = cfg->n_experts, top_k = cfg->top_k;
   // A bf16 model runs on the tensor-core kernels or not at all (the plain-ALU kernels serve fp32 models and the
   // "force_generic" test hook): contraction lengths in whole 64-element k-tiles, head_dim 64 or 128, K/V rows in
   // whole 64-element blocks, and token rows addressable by the kernels' 32-bit byte offsets.
@@ -349,7 +421,7 @@ int dsk_model_create(const dsk_config_t* cfg, int64_t max_tokens, int64_t max_kv
     const int64_t d_ = cfg->hidden, f_ = cfg->ffn, lim = (int64_t)1 << 32;
     int64_t widest = d_ > f_ ? d_ : f_;  // longest activation row the projections read
     if (nq_ > widest) widest = nq_;
-    if (max_tokens * widest * 2 >= lim) return DSK_ESHAPE;
+    if (max_tokens * (E > 0 ? top_k : 1) * widest * 2 >= lim) return DSK_ESHAPE;  // expert rows: top_k per token
     if ((nq_ + 2 * kvw_) * d_ * 2 >= lim || d_ * nq_ * 2 >= lim || 2 * f_ * d_ * 2 >= lim) return DSK_ESHAPE;
   }
 
@@ -377,8 +449,10 @@ int dsk_model_create(const dsk_config_t* cfg, int64_t max_tokens, int64_t max_kv
     if ((rc = alloc_dev(&w.g2, d * elem, &m->weight_bytes))) break;
     if ((rc = alloc_dev(&w.wqkv, (int64_t)m->n_qkv * d * elem, &m->weight_bytes))) break;
     if ((rc = alloc_dev(&w.wo, d * nq * elem, &m->weight_bytes))) break;
-    if ((rc = alloc_dev(&w.wgu, 2 * F * d * elem, &m->weight_bytes))) break;
-    if ((rc = alloc_dev(&w.wd, d * F * elem, &m->weight_bytes))) break;
+    const int64_t n_mlp = E > 0 ? E : 1;
+    if ((rc = alloc_dev(&w.wgu, n_mlp * 2 * F * d * elem, &m->weight_bytes))) break;
+    if ((rc = alloc_dev(&w.wd, n_mlp * d * F * elem, &m->weight_bytes))) break;
+    if (E > 0 && (rc = alloc_dev(&w.wr, (int64_t)E * d * elem, &m->weight_bytes))) break;
   }
   const int64_t T = max_tokens;
   const int half = cfg->head_dim / 2;
@@ -386,7 +460,21 @@ int dsk_model_create(const dsk_config_t* cfg, int64_t max_tokens, int64_t max_kv
   if (rc == DSK_OK) rc = alloc_dev(&m->qkv, T * m->n_qkv * elem, &m->workspace_bytes);
   if (rc == DSK_OK) rc = alloc_dev(&m->attn, T * nq * elem, &m->workspace_bytes);
   if (rc == DSK_OK) rc = alloc_dev(&m->gu, T * 2 * F * elem, &m->workspace_bytes);
-  if (rc == DSK_OK) rc = alloc_dev(&m->act, T * F * elem, &m->workspace_bytes);
+  // with experts on the tensor-core path the MLP works on top_k rows per token, grouped by expert
+  const bool moe_grouped = E > 0 && cfg->dtype == DSK_BF16;
+  if (rc == DSK_OK) rc = alloc_dev(&m->act, T * (moe_grouped ? top_k : 1) * F * elem, &m->workspace_bytes);
+  if (rc == DSK_OK && E > 0) {
+    const int64_t dense_rows = (int64_t)E * (cfg->dtype == DSK_BF16 ? (T < 64 ? T : 64) : T);  // every expert over all rows
+    m->moe_y_rows = moe_grouped && T * top_k > dense_rows ? T * top_k : dense_rows;
+    m->moe_tile_rows = (int)((T * top_k + 255) / 256) + E;
+    rc = alloc_dev((void**)&m->moe_experts, T * top_k * 4, &m->workspace_bytes);
+    if (rc == DSK_OK) rc = alloc_dev((void**)&m->moe_gates, T * top_k * 4, &m->workspace_bytes);
+    if (rc == DSK_OK) rc = alloc_dev((void**)&m->moe_slot, T * top_k * 4, &m->workspace_bytes);
+    if (rc == DSK_OK) rc = alloc_dev((void**)&m->moe_src, T * top_k * 4, &m->workspace_bytes);
+    if (rc == DSK_OK) rc = alloc_dev(&m->moe_tab, (int64_t)m->moe_tile_rows * 16, &m->workspace_bytes);
+    if (rc == DSK_OK && moe_grouped) rc = alloc_dev(&m->moe_xg, T * top_k * d * elem, &m->workspace_bytes);
+    if (rc == DSK_OK) rc = alloc_dev((void**)&m->moe_y, m->moe_y_rows * d * 4, &m->workspace_bytes);
+  }
   if (rc == DSK_OK) rc = alloc_dev((void**)&m->h, T * d * 4, &m->workspace_bytes);
   if (rc == DSK_OK) rc = alloc_dev(&m->e_stage, T * d * elem, &m->workspace_bytes);
   if (rc == DSK_OK) rc = alloc_dev((void**)&m->pace_t0, 8, &m->workspace_bytes);
@@ -480,15 +568,28 @@ int dsk_model_get_tensor(const dsk_model_t* model, int layer, int tensor, void* 
 
 int dsk_model_init_random(dsk_model_t* model, uint64_t seed, float std, void* stream) {
   if (!model || !(std >= 0.f)) return DSK_EINVAL;
-  for (int l = 0; l < model->cfg.n_layers; ++l)
-    for (int t = DSK_G1; t <= DSK_WD; ++t) {
-      TensorPlace p;
-      int rc = place_tensor(model, l, t, &p);
+  const int E = model->cfg.n_experts;
+  auto fill = [&](int l, int tensor, uint64_t stream_id) -> int {
+    TensorPlace p;
+    int rc = place_tensor(model, l, tensor, &p);
+    if (rc) return rc;
+    const float offset = (tensor == DSK_G1 || tensor == DSK_G2) ? 1.0f : 0.0f;
+    HIP_TRY(launch_fill_weight(model->cfg.dtype, p.base, p.rows, p.cols, p.map, model->gu_block, p.row_off, seed, stream_id,
+                               std, offset, (hipStream_t)stream));
+    return (int)DSK_OK;
+  };
+  for (int l = 0; l < model->cfg.n_layers; ++l) {
+    for (int t = DSK_G1; t <= (E > 0 ? DSK_G2 : DSK_WD); ++t) {
+      int rc = fill(l, t, (uint64_t)l * 16 + (uint64_t)t);
       if (rc) return rc;
-      float offset = (t == DSK_G1 || t == DSK_G2) ? 1.0f : 0.0f;
-      HIP_TRY(launch_fill_weight(model->cfg.dtype, p.base, p.rows, p.cols, p.map, model->gu_block, p.row_off, seed,
-                                 (uint64_t)l * 16 + (uint64_t)t, std, offset, (hipStream_t)stream));
     }
+    if (E == 0) continue;
+    int rc = fill(l, DSK_WR, (uint64_t)l * 16 + DSK_WR);
+    if (rc) return rc;
+    for (int e = 0; e < E; ++e)
+      for (int j = 0; j < 3; ++j)
+        if ((rc = fill(l, DSK_EXPERT(e, DSK_WG + j), ((uint64_t)1 << 20) + ((uint64_t)l * 64 + e) * 4 + j))) return rc;
+  }
   return DSK_OK;
 }
 
@@ -842,6 +943,14 @@ int dsk_attention(int dtype, const void* q, const void* k_rows, const void* v_ro
     a.vt = scratch; a.ldvt = rows64;
   }
   HIP_TRY(attention_any(dtype, a, (hipStream_t)stream));
+  return DSK_OK;
+}
+
+int dsk_moe_route(int dtype, const void* x, const void* wr, int n, int d, int n_experts, int top_k, int32_t* experts_out,
+                  float* gates_out, void* stream) {
+  if (!x || !wr || !experts_out || !gates_out || n < 0 || d < 1) return DSK_EINVAL;
+  if (dtype != DSK_F32 && dtype != DSK_BF16) return DSK_EDTYPE;
+  HIP_TRY(launch_moe_route(dtype, x, wr, experts_out, gates_out, n, d, n_experts, top_k, (hipStream_t)stream));
   return DSK_OK;
 }
 

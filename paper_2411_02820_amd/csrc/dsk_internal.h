@@ -24,8 +24,9 @@ struct LayerWeights {
   void* wqkv;  // [(Hq+2Hkv)*dh, d]
   void* wo;    // [d, Hq*dh]
   void* g2;
-  void* wgu;   // [2F, d] interleaved
-  void* wd;    // [d, F]
+  void* wgu;   // [2F, d] interleaved; a mixture-of-experts layer: [E][2F, d]
+  void* wd;    // [d, F]; a mixture-of-experts layer: [E][d, F]
+  void* wr;    // router [E, d] of a mixture-of-experts layer
 };
 
 constexpr int DSK_MAX_E_CHUNKS = 16;
@@ -55,6 +56,16 @@ struct dsk_model {
   int64_t gemm_ws_bytes;
   void* attn_ws;    // fp32 partial outputs of the key-split attention
   int64_t attn_ws_bytes;
+  // mixture-of-experts layers (cfg.n_experts > 0)
+  int32_t* moe_experts;  // [maxT, top_k] chosen experts
+  float* moe_gates;      // [maxT, top_k] their gate weights
+  int32_t* moe_slot;     // [maxT, top_k] row of the entry once the rows are grouped by expert
+  int32_t* moe_src;      // [maxT*top_k]  token of every grouped row
+  void* moe_tab;         // int4 [moe_tile_rows] row tiles of the grouped projections
+  int moe_tile_rows;
+  void* moe_xg;          // [maxT*top_k, d] normalised activations, grouped by expert
+  float* moe_y;          // expert outputs, fp32: [maxT*top_k, d] grouped, or [E][n][d] when every expert runs over all rows
+  int64_t moe_y_rows;
   int64_t workspace_bytes;
   // load pipeline
   hipStream_t load_stream;
@@ -142,6 +153,20 @@ hipError_t launch_pack_rows(int dtype, void* packed, const void* logical, int64_
                             int gu_block, int64_t row_off, int to_packed, hipStream_t s);
 hipError_t launch_fill_weight(int dtype, void* packed, int64_t rows, int64_t cols, int map, int gu_block, int64_t row_off,
                               uint64_t seed, uint64_t stream_id, float std, float offset, hipStream_t s);
+
+// mixture-of-experts MLP: router, grouping by expert, grouped projections, gate-weighted sum (moe.hip, gemm_mfma.hip)
+hipError_t launch_moe_route(int dtype, const void* xn, const void* wr, int32_t* experts, float* gates, int n, int d, int E,
+                            int top_k, hipStream_t s);
+hipError_t launch_moe_place(const int32_t* experts, int32_t* slot_of, int32_t* src_token, void* tile_tab, int n, int top_k,
+                            int E, int tile_m, int tile_rows_max, hipStream_t s);
+hipError_t launch_moe_gather(int dtype, const void* xn, const int32_t* src_token, void* xg, int n_slots, int n_tokens, int d,
+                             hipStream_t s);
+hipError_t launch_moe_combine(const float* y, const float* h_mid, const float* gates, const int32_t* experts,
+                              const int32_t* slot_of, void* out, int out_f32, int n, int d, int top_k, int64_t y_rows,
+                              hipStream_t s);
+hipError_t launch_gemm_mfma_grouped(const void* A, int64_t lda, int64_t a_rows, const void* W, int64_t ldw,
+                                    int64_t w_group_stride, void* C, int64_t ldc, int N, int K, int epi,
+                                    const void* tile_tab, int tile_rows, hipStream_t s);
 
 // tuning knobs (dsk_set_option)
 void gemm_mfma_set_variant(int v);

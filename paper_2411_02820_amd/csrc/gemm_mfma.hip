@@ -437,11 +437,14 @@ __global__ void __launch_bounds__(WAVES_M* WAVES_N * 64)
 // Schedule per k-tile (two k-steps of 32 MFMAs): the fragments of k-step 1 are read during k-step 0; a barrier
 // between the k-steps frees the stage; the loads of tile t+2 go out one per four MFMAs of k-step 1; a barrier in
 // the middle of k-step 1 publishes tile t+1, whose first fragments are read during the rest of it.
-template <int BM, int BN, int WAVES_M, int WAVES_N>
+// GROUPED (the expert projections of a mixture-of-experts layer): the token rows are sorted by expert, and row tile
+// tm of the grid is described by tile_tab[tm] = {expert, first row, end of the expert's rows, -} (built on the
+// device; expert < 0: no such tile, the workgroup leaves); the expert's matrix is W + expert * w_group_stride.
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool GROUPED = false>
 __global__ void __launch_bounds__(WAVES_M* WAVES_N * 64)
-    gemm16_bf16_kernel(const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ W, int64_t ldw,
-                       void* __restrict__ C, int64_t ldc, const void* __restrict__ R, int64_t ldr, int M, int N, int K,
-                       int epi, int tiles_m, int tiles_n) {
+    gemm16_bf16_kernel(const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ W_all, int64_t ldw,
+                       void* __restrict__ C, int64_t ldc, const void* __restrict__ R, int64_t ldr, int M_all, int N, int K,
+                       int epi, int tiles_m, int tiles_n, const int4* __restrict__ tile_tab, int64_t w_group_stride) {
   constexpr int NW = WAVES_M * WAVES_N;
   constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
   constexpr int TM = WTM / 16, TN = WTN / 16;  // 16x16 MFMA tiles per wave
@@ -469,7 +472,16 @@ __global__ void __launch_bounds__(WAVES_M* WAVES_N * 64)
   const int first_m = group * GROUP_M;
   const int gsz = min(GROUP_M, tiles_m - first_m);
   const int in_group = pid - group * per_group;
-  const int m0 = (first_m + in_group % gsz) * BM, n0 = (in_group / gsz) * BN;
+  int m0 = (first_m + in_group % gsz) * BM, M = M_all;
+  const int n0 = (in_group / gsz) * BN;
+  const bf16_t* W = W_all;
+  if constexpr (GROUPED) {
+    const int4 te = tile_tab[first_m + in_group % gsz];
+    if (te.x < 0) return;  // uniform over the workgroup, before any barrier
+    m0 = te.y;
+    M = te.z;
+    W = W_all + (int64_t)te.x * w_group_stride;
+  }
 
   const int lr = lane / CH, lp = lane % CH;
   uint32_t a_off[A_INST], w_off[W_INST];
@@ -860,7 +872,25 @@ hipError_t launch16(const void* A, int64_t lda, const void* W, int64_t ldw, void
   }
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(WAVES_M * WAVES_N * 64), lds, s, (const bf16_t*)A, lda,
-                     (const bf16_t*)W, ldw, C, ldc, R, ldr, M, N, K, epi, tiles_m, tiles_n);
+                     (const bf16_t*)W, ldw, C, ldc, R, ldr, M, N, K, epi, tiles_m, tiles_n, (const int4*)nullptr, (int64_t)0);
+  return hipGetLastError();
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N>
+hipError_t launch16_grouped(const void* A, int64_t lda, const void* W, int64_t ldw, int64_t w_group_stride, void* C,
+                            int64_t ldc, int N, int K, int epi, const int4* tile_tab, int tile_rows, hipStream_t s) {
+  auto kern = gemm16_bf16_kernel<BM, BN, WAVES_M, WAVES_N, true>;
+  constexpr int lds = NSTAGE * (BM + BN) * BK * 2;
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  const int tiles_n = (N + BN - 1) / BN;
+  hipLaunchKernelGGL(kern, dim3(tile_rows * tiles_n), dim3(WAVES_M * WAVES_N * 64), lds, s, (const bf16_t*)A, lda,
+                     (const bf16_t*)W, ldw, C, ldc, (const void*)nullptr, (int64_t)0, 0, N, K, epi, tile_rows, tiles_n,
+                     tile_tab, w_group_stride);
   return hipGetLastError();
 }
 
@@ -978,6 +1008,19 @@ hipError_t launch_gemm_mfma_bf16(const void* A, int64_t lda, const void* W, int6
     case 2: return launch<128, 128, 2, 2, false, 1>(A, lda, W, ldw, C, ldc, R, ldr, nullptr, M, N, K, epi, 1, KT, s);
     default: return launch16<256, 256, 2, 4>(A, lda, W, ldw, C, ldc, R, ldr, M, N, K, epi, s);
   }
+}
+
+// Projections of a mixture-of-experts layer over token rows sorted by expert: one launch over all experts, on the
+// 256-row prefill tiling.  tile_tab[0..tile_rows) describes the row tiles (see the kernel); rows of A and C are the
+// sorted slots.  epi: EPI_SWIGLU (C bf16 [slots, N/2]) or EPI_C_F32 / EPI_STORE (C [slots, N]); no residual.
+hipError_t launch_gemm_mfma_grouped(const void* A, int64_t lda, int64_t a_rows, const void* W, int64_t ldw,
+                                    int64_t w_group_stride, void* C, int64_t ldc, int N, int K, int epi,
+                                    const void* tile_tab, int tile_rows, hipStream_t s) {
+  if (tile_rows <= 0) return hipSuccess;
+  if (K < BK || K % BK || N % 64 || (lda & 7) || (ldw & 7) || (ldc & 3) || (epi & EPI_RESIDUAL)) return hipErrorNotSupported;
+  if (a_rows * lda * 2 >= ((int64_t)1 << 32) || (int64_t)N * ldw * 2 >= ((int64_t)1 << 32)) return hipErrorNotSupported;
+  return launch16_grouped<256, 256, 2, 4>(A, lda, W, ldw, w_group_stride, C, ldc, N, K, epi, (const int4*)tile_tab,
+                                          tile_rows, s);
 }
 
 // ---- few token rows (M <= 64): projection + the step that follows it, in the split-K reduction ----

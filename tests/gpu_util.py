@@ -45,21 +45,28 @@ class GpuModel:
 
     def load_from_generator(self, seed, layers=None, scale=None):
         """Uploads host-generated tensors (the same arrays the oracle gets)."""
+        moe = self.shape.n_experts > 0
         for l in (range(self.shape.n_layers) if layers is None else layers):
-            for kind in range(9):
+            for kind in ((synth.G1, synth.WQ, synth.WK, synth.WV, synth.WO, synth.G2, synth.WR) if moe else range(9)):
                 w = synth.layer_tensor(self.shape, seed, l, kind)
                 if scale is not None and kind not in (synth.G1, synth.G2):
                     w = w * np.float32(scale)
                 B.dsk_model_set_tensor(self.handle, l, kind, to_dev(w, self.shape))
+            for e in range(self.shape.n_experts):
+                for kind in (synth.WG, synth.WU, synth.WD):
+                    w = synth.expert_tensor(self.shape, seed, l, e, kind)
+                    if scale is not None:
+                        w = w * np.float32(scale)
+                    B.dsk_model_set_tensor(self.handle, l, B.DSK_EXPERT(e, kind), to_dev(w, self.shape))
         torch.cuda.synchronize()
 
     def init_random(self, seed, std=synth.WEIGHT_STD):
         B.dsk_model_init_random(self.handle, seed, std)
         torch.cuda.synchronize()
 
-    def get_tensor(self, layer, kind):
+    def get_tensor(self, layer, kind, expert=None):
         out = torch.empty(self.shape.tensor_shape(kind), dtype=torch_dtype(self.shape), device="cuda")
-        B.dsk_model_get_tensor(self.handle, layer, kind, out)
+        B.dsk_model_get_tensor(self.handle, layer, kind if expert is None else B.DSK_EXPERT(expert, kind), out)
         torch.cuda.synchronize()
         return out
 

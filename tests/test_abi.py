@@ -43,3 +43,15 @@ def test_error_strings_without_gpu():
     # null arguments are rejected before any device call
     assert B.lib.dsk_model_create(None, 1, 1, None) == B.DSK_EINVAL
     assert B.lib.dsk_partial_prefill(None, None, 0, 0, 0, None, None, None, None, 0, None) == B.DSK_EINVAL
+
+
+def test_binding_declares_the_argument_types_of_every_export():
+    # without argtypes ctypes passes a Python int as a 32-bit C int: a device pointer would arrive truncated
+    from paper_2411_02820_amd import binding as B
+    text = open(os.path.join(ROOT, "include", "dsk.h")).read()
+    for name in B.EXPORTS:
+        fn = getattr(B.lib, name)
+        assert fn.argtypes is not None, name
+        decl = re.search(r"\b" + name + r"\s*\(([^;]*?)\)\s*;", text, re.S).group(1)
+        n_params = 0 if decl.strip() in ("", "void") else decl.count(",") + 1
+        assert len(fn.argtypes) == n_params, (name, len(fn.argtypes), n_params)
