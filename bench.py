@@ -6,7 +6,7 @@ from the sender's E cache while the other layers' KV is spliced in on the side s
 dsk_suffix_prefill (the new tokens through all layers against the mixed cache).  Inputs are
 synthetic and resident in HBM before the timed region.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 8b-8k|8b-4k|8b-ragged|8b-16k-hostkv|70b-8k|tiny]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 8b-8k|8b-4k|8b-ragged|8b-16k-hostkv|70b-8k|mixtral-8k|tiny]
 """
 import argparse
 import json
@@ -28,13 +28,15 @@ WORKLOADS = {
     "8b-16k-hostkv": ("LLAMA_8B", [16384], 4, 12, 64, True),  # workload 4: reused KV + E cache in pinned host memory
     "70b-8k": ("LLAMA_70B", [8192], 20, 36, 64, False),      # workload 5
     "tiny": ("TINY", [128], 1, 3, 16, False),                # workload 1
+    "mixtral-8k": ("MIXTRAL_8X7B", [8192], 8, 16, 64, False),  # the mixture-of-experts receiver of Sec. 5.4
 }
 
 
 def recompute_flops(shape, lens, n_layers):
     """Algorithmic flops of recomputing n_layers over the packed prefixes (MAC = 2, attention causal)."""
     d, hq, hkv, dh, f = shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.ffn
-    gemm = 2.0 * sum(lens) * (d * (hq + 2 * hkv) * dh + hq * dh * d + 3 * d * f)
+    mlps = shape.top_k if shape.n_experts else 1  # expert MLPs a token goes through (+ the router)
+    gemm = 2.0 * sum(lens) * (d * (hq + 2 * hkv) * dh + hq * dh * d + mlps * 3 * d * f + d * shape.n_experts)
     attn = sum(2.0 * hq * dh * t * (t + 1) for t in lens)
     return n_layers * (gemm + attn)
 
@@ -92,8 +94,10 @@ def cpu_baseline(shape, lens, lo, hi):
     n_rows = min(T, 768 if shape.hidden <= 4096 else 256)   # about 10-30 s of host work
     rows = sorted(set(int(r) for r in np.linspace(0, T - 1, n_rows).round()))
     cfg = O.Config(shape.n_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.ffn,
-                   shape.rope_base, shape.rms_eps)
-    w = {k: v.astype(np.float64) for k, v in synth.layer_weights(shape, synth.SEED_RECEIVER, lo).items()}
+                   shape.rope_base, shape.rms_eps, shape.n_experts, shape.top_k)
+    w = synth.layer_weights(shape, synth.SEED_RECEIVER, lo)
+    w = {k: ([{n: t.astype(np.float64) for n, t in e.items()} for e in v] if k == "experts" else v.astype(np.float64))
+         for k, v in w.items()}
     x = synth.hidden_states(shape, T).astype(np.float64)
     pos, cu = synth.packed_positions(lens), synth.cu_seqlens(lens)
     t0 = time.perf_counter()
@@ -371,7 +375,8 @@ def main():
         out["roofline"] = {"bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                            "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": measured_traffic(args.workload),
                            "traffic_unit": "bytes per launch (L2<->fabric reads + writes, rocprofv3 --pmc, see profiles/)",
-                           "kernel": "gemm16_bf16_kernel<256,256,2,4> (prefill GEMMs: QKV, O, gate/up, down)",
+                           "kernel": "gemm16_bf16_kernel<256,256,2,4> (prefill GEMMs: QKV, O, gate/up, down"
+                                     + ("; the expert projections are its grouped instantiation, one launch over all experts)" if shape.n_experts else ")"),
                            "launches": int(gemm_n), "avg_launch_ms": round(gemm_ms / gemm_n, 4),
                            "flops_per_launch": round(gemm_flops / gemm_n / 1e9, 1), "flops_unit": "GFLOP"}
     else:

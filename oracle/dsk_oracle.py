@@ -99,13 +99,14 @@ def moe_route(y, router, top_k):
 
 def moe_mlp(y, router, experts_w, top_k):
     """Sparse mixture-of-experts MLP: every token goes through its top_k experts' SwiGLU MLPs and the results are
-    added with the gate weights.  experts_w[e] = dict(wg, wu, wd) of expert e.  Returns [n, d]."""
+    added with the gate weights.  experts_w[e] = dict(wg, wu, wd) of expert e.  Returns [n, d].
+    Written expert by expert (the tokens that chose expert e go through its MLP together), which is the same sum."""
     _, experts, gates = moe_route(y, router, top_k)
     out = np.zeros((y.shape[0], experts_w[0]["wd"].shape[0]), dtype=y.dtype)
-    for i in range(y.shape[0]):
-        for j in range(top_k):
-            ew = experts_w[experts[i, j]]
-            out[i] += gates[i, j] * swiglu_mlp(y[i:i + 1], ew["wg"], ew["wu"], ew["wd"])[0]
+    for e, ew in enumerate(experts_w):
+        rows, place = np.nonzero(experts == e)  # a token lists an expert at most once: rows are distinct
+        if len(rows):
+            out[rows] += gates[rows, place][:, None] * swiglu_mlp(y[rows], ew["wg"], ew["wu"], ew["wd"])
     return out
 
 

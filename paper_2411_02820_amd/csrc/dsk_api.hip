@@ -228,11 +228,23 @@ int run_moe_mlp(dsk_model* m, const LayerWeights& w, int n, const float* h_mid, 
     if (tile_rows > m->moe_tile_rows) tile_rows = m->moe_tile_rows;
     HIP_TRY(launch_moe_place(m->moe_experts, m->moe_slot, m->moe_src, m->moe_tab, n, k, E, 256, tile_rows, s));
     HIP_TRY(launch_moe_gather(c.dtype, m->xn, m->moe_src, m->moe_xg, n * k, n, d, s));
-    HIP_TRY(launch_gemm_mfma_grouped(m->moe_xg, d, (int64_t)n * k, w.wgu, d, wgu_stride, m->act, F, 2 * F, d, EPI_SWIGLU,
-                                     m->moe_tab, tile_rows, s));
-    HIP_TRY(launch_gemm_mfma_grouped(m->act, F, (int64_t)n * k, w.wd, F, wd_stride, m->moe_y, d, d, F, EPI_C_F32,
-                                     m->moe_tab, tile_rows, s));
-    g_stats.gemm_mfma += 2;
+    // under "time_gemm" the two grouped launches are bracketed like the other prefill projections (n*k rows each)
+    auto grouped = [&](const void* A, int64_t lda, const void* W, int64_t ldw, int64_t w_stride, void* C, int64_t ldc, int N,
+                       int K, int epi) -> int {
+      std::unique_lock<std::mutex> timed_lock(g_stats.timed_mu, std::defer_lock);
+      bool timed = false;
+      if (g_time_gemm && gemm_mfma_uses_prefill_tile(n * k, N)) {
+        timed_lock.lock();
+        HIP_TRY(g_stats.gemm.begin(s, &timed));
+      }
+      HIP_TRY(launch_gemm_mfma_grouped(A, lda, (int64_t)n * k, W, ldw, w_stride, C, ldc, N, K, epi, m->moe_tab, tile_rows, s));
+      ++g_stats.gemm_mfma;
+      if (timed) HIP_TRY(g_stats.gemm.end(s, 2.0 * n * k * N * K));
+      return DSK_OK;
+    };
+    int rc = grouped(m->moe_xg, d, w.wgu, d, wgu_stride, m->act, F, 2 * F, d, EPI_SWIGLU);
+    if (rc == DSK_OK) rc = grouped(m->act, F, w.wd, F, wd_stride, m->moe_y, d, d, F, EPI_C_F32);
+    if (rc) return rc;
     HIP_TRY(launch_moe_combine(m->moe_y, h_mid, m->moe_gates, m->moe_experts, m->moe_slot, h_out, out_f32, n, d, k,
                                (int64_t)n * k, s));
     return DSK_OK;

@@ -252,3 +252,75 @@ def test_expert_with_no_tokens(G, monkeypatch):
         ok = ~rec.calls[0]
         assert ok.mean() > 0.75
         assert O.max_rel_err(G.to_np(h_out)[ok], h_ref[ok]) <= TOL["bf16"]
+
+
+# ---------------------------------------------------------------- at the width of Mixtral 8x7B
+def host_moe_layer(shape, seed, layer):
+    print(f"[host] generating layer {layer} of the {shape.hidden}-wide model with {shape.n_experts} experts", flush=True)
+    w = synth.layer_weights(shape, seed, layer)
+    return {k: ([{n: t.astype(np.float64) for n, t in e.items()} for e in v] if k == "experts" else v.astype(np.float64))
+            for k, v in w.items()}
+
+
+def test_mixtral_width_layer_over_4096_tokens_and_suffix_pass(G, monkeypatch):
+    # Two layers of the Mixtral 8x7B layer shape (d 4096, 32/8 heads, 8 experts of width 14336, top 2), weights from the
+    # device generator (bit-identical to the host's).  (a) Layer 0 over 4096 tokens: 8192 expert rows grouped on the
+    # device, about four 256-row tiles per expert, both expert projections in one grouped launch each: K/V of every
+    # row and the state leaving the layer at sampled rows against the oracle.  (b) The suffix pass of 64 tokens through
+    # both layers against seeded N(0,1) prefix rows: every expert streamed over the 64 rows on the few-row tiles.
+    from paper_2411_02820_amd import binding as B
+    from tests.test_gpu_fullsize import device_kv_cache, device_normal, host_kv_rows
+    base = synth.MIXTRAL_8X7B
+    shape = synth.ModelShape(2, base.hidden, base.n_q_heads, base.n_kv_heads, base.head_dim, base.ffn, base.rope_base,
+                             base.rms_eps, "bf16", base.n_experts, base.top_k)
+    cfg = oracle_config(shape)
+    T, S = 4096, 64
+    rows = sorted({0, 1, 63, 64, 255, 256, 1000, 2047, 2048, 3000, 4000, 4094, 4095})
+    hidden_host = synth.hidden_states(shape, T)
+    w0 = host_moe_layer(shape, synth.SEED_RECEIVER, 0)
+    rec = RouteRecorder(monkeypatch, shape.top_k, MARGIN["bf16"])
+    with G.GpuModel(shape, T, T + S) as m:
+        m.init_random(synth.SEED_RECEIVER)
+        B.dsk_set_option("reset_stats", 0)
+        hidden_dev = device_normal(B, (T, shape.hidden), synth.SEED_HIDDEN, 0)
+        assert np.array_equal(G.to_np(hidden_dev[:2]), hidden_host[:2])
+        kv_1, h_1 = m.partial(hidden_dev, 0, 1, device_kv_cache(B, shape, T, T), [T])
+        torch.cuda.synchronize()
+        assert B.dsk_get_stat("gemm_generic_launches") == 0 and B.dsk_get_stat("gemm_mfma_launches") == 4
+        h_ref, K, V = O.prefix_layer(cfg, w0, hidden_host.astype(np.float64), synth.packed_positions([T]),
+                                     synth.cu_seqlens([T]), rows=rows)
+        ok = ~rec.calls[0]
+        errs = {"K": O.max_rel_err(G.to_np(kv_1[0, 0, :T]), K), "V": O.max_rel_err(G.to_np(kv_1[0, 1, :T]), V),
+                "hidden_rows": O.max_rel_err(G.to_np(h_1)[rows][ok], h_ref[ok])}
+        print(f"layer 0 over {T} tokens: {ok.sum()} of {len(rows)} sampled rows decided; max-rel-err:",
+              {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
+        assert ok.sum() >= len(rows) - 4 and max(errs.values()) <= TOL["bf16"], errs
+
+        # (b) suffix pass
+        rec.calls.clear()
+        cu, cus = synth.cu_seqlens([T]), synth.cu_seqlens([S])
+        spos = synth.packed_positions([S], start=[T])
+        xs_host = synth.hidden_states(shape, S, seed=synth.SEED_SUFFIX)
+        kv = device_kv_cache(B, shape, T + S, T)
+        B.dsk_set_option("reset_stats", 0)
+        hs = m.suffix(G.to_dev(xs_host, shape), kv, [T], [S])
+        torch.cuda.synchronize()
+        assert B.dsk_get_stat("gemm_generic_launches") == 0 and B.dsk_get_stat("attn_generic_launches") == 0
+        weights = {0: w0}
+
+        def wfn(l):
+            if l not in weights:
+                weights.clear()
+                weights[l] = host_moe_layer(shape, synth.SEED_RECEIVER, l)
+            return weights[l]
+        del w0
+        kv_s, hs_ref = O.suffix_prefill(cfg, wfn, xs_host.astype(np.float64), [host_kv_rows(shape, l, T) for l in range(2)],
+                                        spos, cu, cus)
+        bad0, bad1 = rec.calls[0], rec.calls[0] | rec.calls[1]
+        errs = {"sK0": O.max_rel_err(G.to_np(kv[0, 0, T:]), kv_s[0][0]), "sV0": O.max_rel_err(G.to_np(kv[0, 1, T:]), kv_s[0][1]),
+                "sK1": O.max_rel_err(G.to_np(kv[1, 0, T:])[~bad0], kv_s[1][0][~bad0]),
+                "sV1": O.max_rel_err(G.to_np(kv[1, 1, T:])[~bad0], kv_s[1][1][~bad0]),
+                "suffix_hidden": O.max_rel_err(G.to_np(hs)[~bad1], hs_ref[~bad1])}
+        print(f"suffix pass: undecided routings {bad0.sum()} + {(bad1 & ~bad0).sum()} of {S}; max-rel-err:",
+              {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
+        assert bad1.mean() <= 0.35 and max(errs.values()) <= TOL["bf16"], errs
