@@ -224,7 +224,7 @@ int run_moe_mlp(dsk_model* m, const LayerWeights& w, int n, const float* h_mid, 
   const bool tensor_cores = c.dtype == DSK_BF16 && !g_force_generic;
   if (tensor_cores && n > 64) {
     if (m->gu_block != 32) return DSK_ESHAPE;
-    int tile_rows = (int)(((int64_t)n * k + 255) / 256) + E;
+    int tile_rows = moe_tile_table_rows((int64_t)n * k, E);
     if (tile_rows > m->moe_tile_rows) tile_rows = m->moe_tile_rows;
     HIP_TRY(launch_moe_place(m->moe_experts, m->moe_slot, m->moe_src, m->moe_tab, n, k, E, 256, tile_rows, s));
     HIP_TRY(launch_moe_gather(c.dtype, m->xn, m->moe_src, m->moe_xg, n * k, n, d, s));
@@ -478,12 +478,12 @@ int dsk_model_create(const dsk_config_t* cfg, int64_t max_tokens, int64_t max_kv
   if (rc == DSK_OK && E > 0) {
     const int64_t dense_rows = (int64_t)E * (cfg->dtype == DSK_BF16 ? (T < 64 ? T : 64) : T);  // every expert over all rows
     m->moe_y_rows = moe_grouped && T * top_k > dense_rows ? T * top_k : dense_rows;
-    m->moe_tile_rows = (int)((T * top_k + 255) / 256) + E;
+    m->moe_tile_rows = moe_tile_table_rows(T * top_k, E);
     rc = alloc_dev((void**)&m->moe_experts, T * top_k * 4, &m->workspace_bytes);
     if (rc == DSK_OK) rc = alloc_dev((void**)&m->moe_gates, T * top_k * 4, &m->workspace_bytes);
     if (rc == DSK_OK) rc = alloc_dev((void**)&m->moe_slot, T * top_k * 4, &m->workspace_bytes);
     if (rc == DSK_OK) rc = alloc_dev((void**)&m->moe_src, T * top_k * 4, &m->workspace_bytes);
-    if (rc == DSK_OK) rc = alloc_dev(&m->moe_tab, (int64_t)m->moe_tile_rows * 16, &m->workspace_bytes);
+    if (rc == DSK_OK) rc = alloc_dev(&m->moe_tab, ((int64_t)m->moe_tile_rows + 1) * 16, &m->workspace_bytes);
     if (rc == DSK_OK && moe_grouped) rc = alloc_dev(&m->moe_xg, T * top_k * d * elem, &m->workspace_bytes);
     if (rc == DSK_OK) rc = alloc_dev((void**)&m->moe_y, m->moe_y_rows * d * 4, &m->workspace_bytes);
   }

@@ -157,8 +157,11 @@ hipError_t launch_fill_weight(int dtype, void* packed, int64_t rows, int64_t col
 // mixture-of-experts MLP: router, grouping by expert, grouped projections, gate-weighted sum (moe.hip, gemm_mfma.hip)
 hipError_t launch_moe_route(int dtype, const void* xn, const void* wr, int32_t* experts, float* gates, int n, int d, int E,
                             int top_k, hipStream_t s);
+// tile_tab: int4 [tile_rows_max + 1] (the last entry receives the number of tiles)
 hipError_t launch_moe_place(const int32_t* experts, int32_t* slot_of, int32_t* src_token, void* tile_tab, int n, int top_k,
                             int E, int tile_m, int tile_rows_max, hipStream_t s);
+// rows of the grouped projections' tile table for n_rows rows over E experts (every expert may end in a partial tile)
+inline int moe_tile_table_rows(int64_t n_rows, int E) { return (int)((n_rows + 255) / 256) + E; }
 hipError_t launch_moe_gather(int dtype, const void* xn, const int32_t* src_token, void* xg, int n_slots, int n_tokens, int d,
                              hipStream_t s);
 hipError_t launch_moe_combine(const float* y, const float* h_mid, const float* gates, const int32_t* experts,

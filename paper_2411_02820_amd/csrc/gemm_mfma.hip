@@ -439,7 +439,8 @@ __global__ void __launch_bounds__(WAVES_M* WAVES_N * 64)
 // the middle of k-step 1 publishes tile t+1, whose first fragments are read during the rest of it.
 // GROUPED (the expert projections of a mixture-of-experts layer): the token rows are sorted by expert, and row tile
 // tm of the grid is described by tile_tab[tm] = {expert, first row, end of the expert's rows, -} (built on the
-// device; expert < 0: no such tile, the workgroup leaves); the expert's matrix is W + expert * w_group_stride.
+// device; tile_tab[tiles_m].x = number of tiles that exist; expert < 0: no such tile, the workgroup leaves); the
+// expert's matrix is W + expert * w_group_stride.
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool GROUPED = false>
 __global__ void __launch_bounds__(WAVES_M* WAVES_N * 64)
     gemm16_bf16_kernel(const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ W_all, int64_t ldw,
@@ -461,8 +462,15 @@ __global__ void __launch_bounds__(WAVES_M* WAVES_N * 64)
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave % WAVES_M, wn = wave / WAVES_M;
   int pid = blockIdx.x;
+  int nb = gridDim.x, n_tiles_m = tiles_m;
+  if constexpr (GROUPED) {
+    // the grid is sized for the worst case; the tiles that exist are the first tile_tab[tiles_m].x of the table, and
+    // only their workgroups are spread over the dies (the rest, the highest block ids, leave at once)
+    n_tiles_m = min(tile_tab[tiles_m].x, tiles_m);
+    nb = n_tiles_m * tiles_n;
+    if (pid >= nb) return;
+  }
   {
-    const int nb = gridDim.x;
     const int q = nb / N_XCD, rem = nb % N_XCD;
     const int xcd = pid % N_XCD, loc = pid / N_XCD;
     pid = (xcd < rem) ? xcd * (q + 1) + loc : rem * (q + 1) + (xcd - rem) * q + loc;
@@ -470,7 +478,7 @@ __global__ void __launch_bounds__(WAVES_M* WAVES_N * 64)
   const int per_group = GROUP_M * tiles_n;
   const int group = pid / per_group;
   const int first_m = group * GROUP_M;
-  const int gsz = min(GROUP_M, tiles_m - first_m);
+  const int gsz = min(GROUP_M, n_tiles_m - first_m);
   const int in_group = pid - group * per_group;
   int m0 = (first_m + in_group % gsz) * BM, M = M_all;
   const int n0 = (in_group / gsz) * BN;
@@ -1011,8 +1019,8 @@ hipError_t launch_gemm_mfma_bf16(const void* A, int64_t lda, const void* W, int6
 }
 
 // Projections of a mixture-of-experts layer over token rows sorted by expert: one launch over all experts, on the
-// 256-row prefill tiling.  tile_tab[0..tile_rows) describes the row tiles (see the kernel); rows of A and C are the
-// sorted slots.  epi: EPI_SWIGLU (C bf16 [slots, N/2]) or EPI_C_F32 / EPI_STORE (C [slots, N]); no residual.
+// 256-row prefill tiling.  tile_tab[0..tile_rows) describes the row tiles and tile_tab[tile_rows] holds their number
+// (see the kernel); rows of A and C are the sorted slots.  epi: EPI_SWIGLU (C bf16 [slots, N/2]) or EPI_C_F32 / EPI_STORE (C [slots, N]); no residual.
 hipError_t launch_gemm_mfma_grouped(const void* A, int64_t lda, int64_t a_rows, const void* W, int64_t ldw,
                                     int64_t w_group_stride, void* C, int64_t ldc, int N, int K, int epi,
                                     const void* tile_tab, int tile_rows, hipStream_t s) {

@@ -73,7 +73,9 @@ __global__ void __launch_bounds__(256) moe_route_kernel(const T* __restrict__ xn
 // depend on timing).  One workgroup per expert e: it counts the entries of every expert (LDS histogram), derives the
 // first slot of its own rows and the first row tile of its own tiles, then walks the entries in order and gives the
 // j-th entry of expert e the slot first + j.  slot_of[entry] = slot, src_token[slot] = token.  tile_tab[r], r <
-// tile_rows_max: {expert, first slot of the tile, end of the expert's slots, 0}, or expert -1 past the last tile.
+// tile_rows_max: {expert, first slot of the tile, end of the expert's slots, 0}, the tiles of all experts back to back,
+// expert -1 past the last tile; tile_tab[tile_rows_max].x = number of tiles (the GEMM spreads exactly those over the
+// chip: a grid sized for the worst case would leave the dies that get its empty end idle).
 __global__ void __launch_bounds__(256) moe_place_kernel(const int32_t* __restrict__ experts, int32_t* __restrict__ slot_of,
                                                         int32_t* __restrict__ src_token, int4* __restrict__ tile_tab,
                                                         int n_entries, int top_k, int E, int tile_m, int tile_rows_max) {
@@ -96,8 +98,10 @@ __global__ void __launch_bounds__(256) moe_place_kernel(const int32_t* __restric
   const int my_tiles = (mine + tile_m - 1) / tile_m;
   for (int r = tid; r < my_tiles; r += 256)
     if (first_tile + r < tile_rows_max) tile_tab[first_tile + r] = make_int4(e, first + r * tile_m, first + mine, 0);
-  if (e == E - 1)
+  if (e == E - 1) {
     for (int r = first_tile + my_tiles + tid; r < tile_rows_max; r += 256) tile_tab[r] = make_int4(-1, 0, 0, 0);
+    if (tid == 0) tile_tab[tile_rows_max] = make_int4(min(first_tile + my_tiles, tile_rows_max), 0, 0, 0);
+  }
   int running = 0;
   int buf = 0;
   for (int base = 0; base < n_entries; base += 256, buf ^= 1) {
