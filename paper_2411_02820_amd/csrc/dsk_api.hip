@@ -476,8 +476,7 @@ int dsk_model_create(const dsk_config_t* cfg, int64_t max_tokens, int64_t max_kv
   const bool moe_grouped = E > 0 && cfg->dtype == DSK_BF16;
   if (rc == DSK_OK) rc = alloc_dev(&m->act, T * (moe_grouped ? top_k : 1) * F * elem, &m->workspace_bytes);
   if (rc == DSK_OK && E > 0) {
-    const int64_t dense_rows = (int64_t)E * (cfg->dtype == DSK_BF16 ? (T < 64 ? T : 64) : T);  // every expert over all rows
-    m->moe_y_rows = moe_grouped && T * top_k > dense_rows ? T * top_k : dense_rows;
+    m->moe_y_rows = (int64_t)E * T;  // every expert over all rows (few rows, fp32, "force_generic"); grouped: T * top_k
     m->moe_tile_rows = moe_tile_table_rows(T * top_k, E);
     rc = alloc_dev((void**)&m->moe_experts, T * top_k * 4, &m->workspace_bytes);
     if (rc == DSK_OK) rc = alloc_dev((void**)&m->moe_gates, T * top_k * 4, &m->workspace_bytes);

@@ -324,3 +324,41 @@ def test_mixtral_width_layer_over_4096_tokens_and_suffix_pass(G, monkeypatch):
         print(f"suffix pass: undecided routings {bad0.sum()} + {(bad1 & ~bad0).sum()} of {S}; max-rel-err:",
               {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
         assert bad1.mean() <= 0.35 and max(errs.values()) <= TOL["bf16"], errs
+
+
+def test_bf16_experts_on_the_plain_kernels_agree_with_the_tensor_core_path(G, monkeypatch):
+    # the "force_generic" hook sends a bf16 model through the plain-ALU kernels, every expert over all rows, for any
+    # number of rows: the same oracle bar, and the same tokens decided
+    from paper_2411_02820_amd import binding as B
+    B.dsk_set_option("force_generic", 1)
+    try:
+        run_moe_case(G, monkeypatch, SMALL_MOE_BF16, [150], 0, 2, [5], 2.0)
+    finally:
+        B.dsk_set_option("force_generic", 0)
+
+
+def test_model_create_rejects_bad_expert_configurations(G):
+    from paper_2411_02820_amd import binding as B
+    import dataclasses
+    for E, k in ((4, 0), (4, 5), (65, 2), (0, 2), (16, 9)):
+        shape = dataclasses.replace(synth.TINY_MOE, n_experts=E, top_k=k)
+        with pytest.raises(B.DskError) as err:
+            B.dsk_model_create(B.config_from_shape(shape), 8, 8)
+        assert err.value.status == B.DSK_ESHAPE, (E, k)
+
+
+def test_two_recompute_groups_with_experts(G, monkeypatch):
+    # the several-groups call on an expert model: bit-identical to chained single-group calls (Sec. 4.1)
+    shape = SMALL_MOE_BF16
+    T = 200
+    hidden = synth.hidden_states(shape, T)
+    kv_r = synth.kv_cache(shape, T)
+    with G.GpuModel(shape, T) as m:
+        m.load_from_generator(synth.SEED_RECEIVER, scale=2.0)
+        h_dev, kv_dev = G.to_dev(hidden, shape), G.to_dev(kv_r, shape)
+        kv_g, outs = m.partial_groups([(0, 1, h_dev), (1, 2, h_dev)], kv_dev, [T])
+        kv_a, h_a = m.partial(h_dev, 0, 1, kv_dev, [T])
+        kv_b, h_b = m.partial(h_dev, 1, 2, kv_a, [T])
+        torch.cuda.synchronize()
+        assert torch.equal(kv_g[:, :, :T], kv_b[:, :, :T])
+        assert torch.equal(outs[0], h_a) and torch.equal(outs[1], h_b)
