@@ -6,7 +6,7 @@ from the sender's E cache while the other layers' KV is spliced in on the side s
 dsk_suffix_prefill (the new tokens through all layers against the mixed cache).  Inputs are
 synthetic and resident in HBM before the timed region.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 8b-8k|8b-4k|8b-ragged|8b-16k-hostkv|70b-8k|mixtral-8k|tiny]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 8b-8k|8b-4k|8b-ragged|8b-16k-hostkv|8b-32k|70b-8k|mixtral-8k|tiny]
 """
 import argparse
 import json
@@ -28,6 +28,7 @@ WORKLOADS = {
     "8b-16k-hostkv": ("LLAMA_8B", [16384], 4, 12, 64, True),  # workload 4: reused KV + E cache in pinned host memory
     "70b-8k": ("LLAMA_70B", [8192], 20, 36, 64, False),      # workload 5
     "tiny": ("TINY", [128], 1, 3, 16, False),                # workload 1
+    "8b-32k": ("LLAMA_8B", [32768], 8, 16, 64, False),       # the long end of the paper's contexts (App. A: P95 about 30k)
     "mixtral-8k": ("MIXTRAL_8X7B", [8192], 8, 16, 64, False),  # the mixture-of-experts receiver of Sec. 5.4
 }
 

@@ -240,6 +240,32 @@ def test_8b_one_layer_full_length_sampled_rows(G, B):
         assert max(errs.values()) <= TOL, errs
 
 
+def test_8b_one_layer_at_32768_tokens_sampled_rows(G, B):
+    # A context at the long end of the paper's workloads (App. A: P95 up to about 30k tokens), four times the headline
+    # length: a two-layer clone of the 8B shape, layer 1 recomputed over 32768 tokens; K, V of every row and the
+    # layer output at sampled rows (tile edges, middle, the last rows: attention over up to 32768 keys).
+    base = synth.LLAMA_8B
+    shape = synth.ModelShape(2, base.hidden, base.n_q_heads, base.n_kv_heads, base.head_dim, base.ffn, base.rope_base,
+                             base.rms_eps, "bf16")
+    cfg = oracle_config(shape)
+    T, l = 32768, 1
+    hidden_host = synth.hidden_states(shape, T)
+    with G.GpuModel(shape, T) as m:
+        m.init_random(synth.SEED_RECEIVER)
+        kv_r = device_kv_cache(B, shape, T, 0)
+        B.dsk_set_option("reset_stats", 0)
+        kv_out, h_out = m.partial(device_normal(B, (T, shape.hidden), synth.SEED_HIDDEN, 0), l, l + 1, kv_r, [T], kv_out=kv_r)
+        torch.cuda.synchronize()
+        assert B.dsk_get_stat("gemm_generic_launches") == 0 and B.dsk_get_stat("attn_generic_launches") == 0
+        w = host_weights(shape, synth.SEED_RECEIVER, [l])(l)
+        rows = [0, 127, 128, 8191, 8192, 16383, 20000, 32639, 32640, 32766, 32767]
+        h_ref, K, V = O.prefix_layer(cfg, w, hidden_host.astype(np.float64), np.arange(T), np.array([0, T]), rows=rows)
+        errs = {"K": O.max_rel_err(G.to_np(kv_out[l, 0]), K), "V": O.max_rel_err(G.to_np(kv_out[l, 1]), V),
+                "hidden_rows": O.max_rel_err(G.to_np(h_out)[rows], h_ref)}
+        print("32768 tokens: max-rel-err:", {k: f"{v:.2e}" for k, v in errs.items()})
+        assert max(errs.values()) <= TOL, errs
+
+
 def test_config3_8b_ragged_batch(G, B):
     # 8 prefixes with seeded lengths in [1024, 8192], 4 layers from a seeded start layer, packed
     shape = synth.LLAMA_8B
