@@ -362,3 +362,11 @@ def test_two_recompute_groups_with_experts(G, monkeypatch):
         torch.cuda.synchronize()
         assert torch.equal(kv_g[:, :, :T], kv_b[:, :, :T])
         assert torch.equal(outs[0], h_a) and torch.equal(outs[1], h_b)
+
+
+def test_other_expert_counts(G, monkeypatch):
+    # one expert per token of three (fp32), and four of sixteen on the grouped tensor-core path
+    run_moe_case(G, monkeypatch, synth.ModelShape(2, 256, 4, 2, 64, 192, 10000.0, 1e-5, "f32", 3, 1), [90, 41], 0, 2, [6, 2], 8.0,
+                 max_undecided=0.02)
+    run_moe_case(G, monkeypatch, synth.ModelShape(2, 512, 8, 2, 128, 128, 500000.0, 1e-5, "bf16", 16, 4), [200], 0, 2, [40], 2.0,
+                 max_undecided=0.5)
