@@ -1,5 +1,6 @@
-"""Builds libdsk.so (gfx950) from csrc/*.hip, and libdsk_diag.so (device measurements for benchmarks) from
-csrc/diag/*.hip, with hipcc, in-tree, next to this file."""
+"""Builds libdsk.so (gfx950) from csrc/*.hip, libdsk_diag.so (device measurements for benchmarks) from
+csrc/diag/*.hip, and dsk_c_demo (examples/c_abi_demo.c, plain C against the C ABI, compiled by gcc), in-tree, next to this
+file; the libraries are compiled by hipcc."""
 from __future__ import annotations
 
 import os
@@ -13,6 +14,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libdsk.so")
 DIAG_LIB = os.path.join(HERE, "libdsk_diag.so")
+C_DEMO = os.path.join(HERE, "dsk_c_demo")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -53,6 +55,18 @@ def _link(lib: str, objs) -> None:
         raise RuntimeError(f"link failed:\n{r.stdout}\n{r.stderr}")
 
 
+def _build_c_demo() -> None:
+    """examples/c_abi_demo.c: a plain C program against include/dsk.h, libdsk.so and the HIP runtime."""
+    src = os.path.join(HERE, "examples", "c_abi_demo.c")
+    rocm = os.path.dirname(os.path.dirname(os.path.realpath(HIPCC)))
+    cmd = ["gcc", "-std=c11", "-O2", "-Wall", "-D__HIP_PLATFORM_AMD__", "-I", os.path.join(rocm, "include"),
+           "-I", os.path.join(ROOT, "include"), src, "-L", HERE, "-ldsk", "-L", os.path.join(rocm, "lib"), "-lamdhip64", "-lm",
+           "-Wl,-rpath,$ORIGIN", "-Wl,-rpath," + os.path.join(rocm, "lib"), "-o", C_DEMO]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"building the C demo failed:\n{r.stdout}\n{r.stderr}")
+
+
 def build(force: bool = True, jobs: int = 8) -> str:
     os.makedirs(OBJ_DIR, exist_ok=True)
     main, diag = sources(), sources("diag")
@@ -60,6 +74,7 @@ def build(force: bool = True, jobs: int = 8) -> str:
         objs = list(ex.map(lambda s: _compile(s, force), main + diag))
     _link(LIB, objs[:len(main)])
     _link(DIAG_LIB, objs[len(main):])
+    _build_c_demo()
     return LIB
 
 

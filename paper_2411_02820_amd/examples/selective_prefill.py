@@ -58,8 +58,8 @@ def main():
             B.dsk_partial_prefill(sender, embeddings, 0, lo, B.kv_desc(kv_sender), B.kv_desc(kv_sender), prefix.desc, e_lo)
         else:
             e_lo.copy_(embeddings)
-        B.dsk_store_put_kv(store, context, SENDER, B.kv_desc(kv_sender), L, T, row_bytes, B.DSK_TIER_HOST)
-        B.dsk_store_put_e(store, context, SENDER, lo, e_lo, B.DSK_TIER_HOST)
+        B.dsk_store_put_kv(store, context, SENDER, B.kv_desc(kv_sender), L, T, row_bytes)   # GPU memory while it fits (Sec. 4.4)
+        B.dsk_store_put_e(store, context, SENDER, lo, e_lo)
         torch.cuda.synchronize()
 
         # ---- receiver: fetch, selective prefill (loads pipelined under the recompute), suffix ----
