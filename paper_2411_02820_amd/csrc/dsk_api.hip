@@ -54,7 +54,7 @@ void free_model(dsk_model* m) {
     free(m->layers);
   }
   (void)hipFree(m->xn); (void)hipFree(m->qkv); (void)hipFree(m->attn); (void)hipFree(m->gu);
-  (void)hipFree(m->act); (void)hipFree(m->h); (void)hipFree(m->e_stage); (void)hipFree(m->pace_t0); (void)hipFree(m->rope_cs); (void)hipFree(m->theta); (void)hipFree(m->vt); (void)hipFree(m->gemm_ws); (void)hipFree(m->attn_ws);
+  (void)hipFree(m->act); (void)hipFree(m->h); (void)hipFree(m->e_stage); (void)hipFree(m->pace_t0); (void)hipFree(m->rope_cs); (void)hipFree(m->theta); (void)hipFree(m->vt); (void)hipFree(m->gemm_ws); (void)hipFree(m->attn_ws); (void)hipFree(m->ssq);
   if (m->ev_kv) {
     for (int l = 0; l < m->cfg.n_layers; ++l)
       if (m->ev_kv[l]) (void)hipEventDestroy(m->ev_kv[l]);
@@ -278,9 +278,11 @@ int run_layer(dsk_model* m, int l, const void* h_in, int h_in_f32, void* h_out, 
               char* v_layer, int64_t own_row0,
               const int32_t* q_cu, const int32_t* q_cu_host, const int32_t* p_cu, const int32_t* p_cu_host,
               int64_t n_pre_rows, int n_seqs, int n, hipStream_t s, float* h_mid = nullptr, const float2* cs = nullptr,
-              int64_t vt_first_row = 0) {
+              int64_t vt_first_row = 0, bool xn_prescaled = false, const void* g_next = nullptr,
+              bool* next_prescaled = nullptr) {
   if (!h_mid) h_mid = m->h;
   if (!cs) cs = m->rope_cs;
+  if (next_prescaled) *next_prescaled = false;
   const dsk_config_t& c = m->cfg;
   const LayerWeights& w = m->layers[l];
   const int d = c.hidden, F = c.ffn, nq = c.n_q_heads * c.head_dim;
@@ -288,15 +290,26 @@ int run_layer(dsk_model* m, int l, const void* h_in, int h_in_f32, void* h_out, 
   char* k_own = k_layer + own_row0 * row_bytes;
   char* v_own = v_layer + own_row0 * row_bytes;
   const int all_f32 = c.dtype == DSK_F32;  // an fp32 model: every buffer is fp32 anyway
-  HIP_TRY(launch_rmsnorm(c.dtype, h_in, h_in_f32 || all_f32, w.g1, m->xn, n, d, (float)c.rms_eps, s));
   // few token rows (the suffix pass) on the tensor-core path: RoPE + KV write, and below the post-attention
   // RMSNorm, are done by the split-K reduction of the projection in front of them
   const bool few_rows = c.dtype == DSK_BF16 && !g_force_generic && n <= 64 && m->gemm_ws;
+  // ... and with a hidden width in whole 1024-column blocks each RMSNorm is split in two: the reduction in front of it
+  // leaves h * g and the row's sums of squares, the reduction behind the next projection applies the row factor
+  // (xn_prescaled: the layer before has done so for this layer's input norm).  Dense MLP only: the router of an
+  // expert layer reads the normalised rows themselves.
+  const bool split_norm = few_rows && c.n_experts == 0 && m->ssq && m->gu_block == 32 &&
+                          gemm_small_m_prescale_supported(n, d, nq, nq, nq, m->gemm_ws_bytes) &&
+                          gemm_small_m_prescale_supported(n, d, F, F, F, m->gemm_ws_bytes) &&
+                          gemm_small_m_fused_supported(n, 2 * F, d, d, d, m->gemm_ws_bytes);
+  if (xn_prescaled && !split_norm) return DSK_EINVAL;  // the caller decides both from the same conditions
+  if (!xn_prescaled) HIP_TRY(launch_rmsnorm(c.dtype, h_in, h_in_f32 || all_f32, w.g1, m->xn, n, d, (float)c.rms_eps, s));
   if (few_rows && gemm_small_m_rope_supported(n, d, c.n_q_heads, c.n_kv_heads, c.head_dim, d, d, m->n_qkv, m->gemm_ws_bytes)) {
     HIP_TRY(launch_gemm_small_m_rope(m->xn, d, w.wqkv, d, m->qkv, m->n_qkv, cs, k_own, v_own, n, d, c.n_q_heads,
-                                     c.n_kv_heads, c.head_dim, m->gemm_ws, m->gemm_ws_bytes, s));
+                                     c.n_kv_heads, c.head_dim, m->gemm_ws, m->gemm_ws_bytes,
+                                     xn_prescaled ? m->ssq : nullptr, (float)c.rms_eps, s));
     ++g_stats.gemm_mfma;
   } else {
+    if (xn_prescaled) return DSK_EINVAL;
     HIP_TRY(gemm(m, m->xn, d, w.wqkv, d, m->qkv, m->n_qkv, nullptr, 0, n, m->n_qkv, d, EPI_STORE, s));
     HIP_TRY(launch_rope_kv_write(c.dtype, m->qkv, cs, k_own, v_own, n, c.n_q_heads, c.n_kv_heads, c.head_dim, s));
   }
@@ -311,6 +324,23 @@ int run_layer(dsk_model* m, int l, const void* h_in, int h_in_f32, void* h_out, 
     a.vt = m->vt; a.ldvt = m->ldvt;
   }
   HIP_TRY(attention(m, a, s));
+  if (split_norm) {
+    HIP_TRY(launch_gemm_small_m_prescale(m->attn, nq, w.wo, nq, h_mid, h_in, h_in_f32 ? 1 : 0, w.g2, m->xn, m->ssq, n, d, nq,
+                                         m->gemm_ws, m->gemm_ws_bytes, s));
+    HIP_TRY(launch_gemm_small_m_swiglu_scaled(m->xn, d, w.wgu, d, m->act, F, n, 2 * F, d, m->gemm_ws, m->gemm_ws_bytes, m->ssq,
+                                              (float)c.rms_eps, s));
+    g_stats.gemm_mfma += 2;
+    if (g_next && h_out_f32) {
+      // the down projection prepares the next layer's input norm the same way
+      HIP_TRY(launch_gemm_small_m_prescale(m->act, F, w.wd, F, (float*)h_out, h_mid, 1, g_next, m->xn, m->ssq, n, d, F,
+                                           m->gemm_ws, m->gemm_ws_bytes, s));
+      ++g_stats.gemm_mfma;
+      if (next_prescaled) *next_prescaled = true;
+      return DSK_OK;
+    }
+    HIP_TRY(gemm(m, m->act, F, w.wd, F, h_out, d, h_mid, d, n, d, F, EPI_RESIDUAL | EPI_R_F32 | (h_out_f32 ? EPI_C_F32 : 0), s));
+    return DSK_OK;
+  }
   if (few_rows && gemm_small_m_rmsnorm_supported(n, d, nq, nq, nq, m->gemm_ws_bytes)) {
     HIP_TRY(launch_gemm_small_m_rmsnorm(m->attn, nq, w.wo, nq, h_mid, h_in, h_in_f32 ? 1 : 0, w.g2, m->xn, (float)c.rms_eps, n,
                                         d, nq, m->gemm_ws, m->gemm_ws_bytes, s));
@@ -504,6 +534,7 @@ int dsk_model_create(const dsk_config_t* cfg, int64_t max_tokens, int64_t max_kv
     if (cfg->hidden > max_n) max_n = cfg->hidden;
     m->gemm_ws_bytes = gemm_mfma_workspace_bytes(max_n);
     rc = alloc_dev(&m->gemm_ws, m->gemm_ws_bytes, &m->workspace_bytes);
+    if (rc == DSK_OK) rc = alloc_dev((void**)&m->ssq, 64 * DSK_MAX_SSQ_PARTS * (int64_t)sizeof(float), &m->workspace_bytes);
   }
   if (rc == DSK_OK) {
     double* th = (double*)malloc(half * sizeof(double));
@@ -827,6 +858,7 @@ int dsk_suffix_prefill(dsk_model_t* model, const void* suffix_hidden_in, const d
   hipStream_t s = (hipStream_t)stream;
   HIP_TRY(launch_rope_table(suffix->positions_dev, m->theta, m->rope_cs, S, c.head_dim / 2, s));
   const void* h_cur = suffix_hidden_in;
+  bool prescaled = false;  // whether the layer before has prepared this layer's input norm (few rows, see run_layer)
   for (int l = 0; l < c.n_layers; ++l) {
     if (m->pending[l]) {
       HIP_TRY(hipStreamWaitEvent(s, m->ev_kv[l], 0));
@@ -834,10 +866,12 @@ int dsk_suffix_prefill(dsk_model_t* model, const void* suffix_hidden_in, const d
     }
     const bool last = l == c.n_layers - 1;
     void* h_next = last ? hidden_out : (void*)m->h;
+    bool next_prescaled = false;
     rc = run_layer(m, l, h_cur, l > 0, h_next, !last, kv_k(kv, l), kv_v(kv, l), suffix_row0, suffix->cu_seqlens_dev,
                    suffix->cu_seqlens_host, prefix->cu_seqlens_dev, prefix->cu_seqlens_host, prefix->n_tokens,
-                   suffix->n_seqs, S, s);
+                   suffix->n_seqs, S, s, nullptr, nullptr, 0, prescaled, last ? nullptr : m->layers[l + 1].g1, &next_prescaled);
     if (rc) return rc;
+    prescaled = next_prescaled;
     h_cur = h_next;
   }
   m->any_pending = 0;

@@ -52,6 +52,7 @@ struct dsk_model {
   double* theta;    // [dh/2]         rope_base^(-2i/dh)
   void* vt;         // [Hkv*dh, ldvt] transposed V of the layer in flight (bf16 MFMA attention)
   int64_t ldvt;     // max_kv_rows rounded up to 64
+  float* ssq;       // [64, DSK_MAX_SSQ_PARTS] partial sums of squares of the few-row pass (RMSNorm split in two)
   void* gemm_ws;    // fp32 partial tiles of the K-split small-M GEMM
   int64_t gemm_ws_bytes;
   void* attn_ws;    // fp32 partial outputs of the key-split attention
@@ -102,9 +103,21 @@ bool gemm_small_m_fused_supported(int M, int N, int K, int64_t lda, int64_t ldw,
 bool gemm_small_m_rope_supported(int M, int K, int Hq, int Hkv, int dh, int64_t lda, int64_t ldw, int64_t ldq,
                                  int64_t ws_bytes);
 bool gemm_small_m_rmsnorm_supported(int M, int d, int K, int64_t lda, int64_t ldw, int64_t ws_bytes);
+// ssq (optional, with eps): the input rows lack the RMSNorm row factor, which is applied to the sums (see prescale)
 hipError_t launch_gemm_small_m_rope(const void* A, int64_t lda, const void* W, int64_t ldw, void* qkv, int64_t ldq,
                                     const float2* cs, void* k_rows, void* v_rows, int M, int K, int Hq, int Hkv, int dh,
-                                    void* ws, int64_t ws_bytes, hipStream_t s);
+                                    void* ws, int64_t ws_bytes, const float* ssq, float eps, hipStream_t s);
+// Few rows, RMSNorm split in two: a projection with residual writes h, a = bf16(h * g) and per-row partial sums of
+// h^2 (ssq [M, d/1024]); the projection that reads a multiplies its sums by rsqrt(mean(h^2) + eps).  One launch less
+// per norm than normalising in between, and the reduction stays spread over all compute units.
+constexpr int DSK_MAX_SSQ_PARTS = 16;
+bool gemm_small_m_prescale_supported(int M, int d, int K, int64_t lda, int64_t ldw, int64_t ws_bytes);
+hipError_t launch_gemm_small_m_prescale(const void* A, int64_t lda, const void* W, int64_t ldw, float* h, const void* R,
+                                        int r_f32, const void* g, void* a, float* ssq, int M, int d, int K, void* ws,
+                                        int64_t ws_bytes, hipStream_t s);
+hipError_t launch_gemm_small_m_swiglu_scaled(const void* A, int64_t lda, const void* W, int64_t ldw, void* act, int64_t ldc,
+                                             int M, int N, int K, void* ws, int64_t ws_bytes, const float* ssq, float eps,
+                                             hipStream_t s);
 hipError_t launch_gemm_small_m_rmsnorm(const void* A, int64_t lda, const void* W, int64_t ldw, float* h, const void* R,
                                        int r_f32, const void* g, void* xn, float eps, int M, int d, int K, void* ws,
                                        int64_t ws_bytes, hipStream_t s);

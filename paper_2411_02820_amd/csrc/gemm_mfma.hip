@@ -702,8 +702,18 @@ __global__ void __launch_bounds__(256) splitk_reduce_kernel(const float* __restr
 // The same for the gate/up projection, with SwiGLU applied to the sums: act[m][f] = silu(gate) * up, where gate
 // column f sits at packed column (f/32)*64 + f%32 of P and its up column 32 further (rows of W interleaved in
 // blocks of 32).  N = 2F columns in P, F columns in act.
+// ssq != nullptr: the projection's input rows were x*g without the RMSNorm factor; the sums of row m are multiplied
+// by rsqrt(mean(x^2) + eps) here, from the row's n_parts partial sums of squares (row_scale below).
+__device__ __forceinline__ float row_scale(const float* __restrict__ ssq, int m, int n_parts, float inv_d, float eps) {
+  float ss = 0.f;
+  for (int c = 0; c < n_parts; ++c) ss += ssq[m * n_parts + c];
+  return rsqrtf(ss * inv_d + eps);
+}
+
 __global__ void __launch_bounds__(256) splitk_reduce_swiglu_kernel(const float* __restrict__ P, bf16_t* __restrict__ act,
-                                                                   int64_t ldc, int M, int N, int splits) {
+                                                                   int64_t ldc, int M, int N, int splits,
+                                                                   const float* __restrict__ ssq, int n_parts, float inv_d,
+                                                                   float eps) {
   const int F = N / 2;
   const int64_t quads = (int64_t)M * (F / 4);
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -717,6 +727,11 @@ __global__ void __launch_bounds__(256) splitk_reduce_swiglu_kernel(const float* 
     const f32x4 g2 = *(const f32x4*)row, u2 = *(const f32x4*)(row + 32);
     g[0] += g2[0]; g[1] += g2[1]; g[2] += g2[2]; g[3] += g2[3];
     u[0] += u2[0]; u[1] += u2[1]; u[2] += u2[2]; u[3] += u2[3];
+  }
+  if (ssq) {
+    const float rs = row_scale(ssq, m, n_parts, inv_d, eps);
+    g *= rs;
+    u *= rs;
   }
   bf16x4 o;
 #pragma unroll
@@ -733,19 +748,23 @@ __global__ void __launch_bounds__(256) splitk_reduce_swiglu_kernel(const float* 
 __global__ void __launch_bounds__(256) splitk_reduce_rope_kernel(const float* __restrict__ P, bf16_t* __restrict__ qkv,
                                                                  int64_t ldq, const float2* __restrict__ cs,
                                                                  bf16_t* __restrict__ k_rows, bf16_t* __restrict__ v_rows,
-                                                                 int M, int N, int splits, int Hq, int Hkv, int dh) {
+                                                                 int M, int N, int splits, int Hq, int Hkv, int dh,
+                                                                 const float* __restrict__ ssq, int n_parts, float inv_d,
+                                                                 float eps) {
   const int half = dh / 2;
   const int rot_units = (Hq + Hkv) * (half / 4), v_units = Hkv * dh / 4;
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= (int64_t)M * (rot_units + v_units)) return;
   const int m = (int)(i / (rot_units + v_units)), u = (int)(i - (int64_t)m * (rot_units + v_units));
   const int kvw = Hkv * dh;
+  const float rs = ssq ? row_scale(ssq, m, n_parts, inv_d, eps) : 1.0f;
   auto sum4 = [&](int col) {
     f32x4 a = *(const f32x4*)(P + (int64_t)m * N + col);
     for (int k = 1; k < splits; ++k) {
       const f32x4 b = *(const f32x4*)(P + ((int64_t)k * M + m) * N + col);
       a[0] += b[0]; a[1] += b[1]; a[2] += b[2]; a[3] += b[3];
     }
+    if (ssq) a *= rs;
     return a;
   };
   auto to_bf16 = [](f32x4 v) {
@@ -848,6 +867,43 @@ __global__ void __launch_bounds__(256) splitk_reduce_rmsnorm_kernel(const float*
       *(bf16x4*)(xn + (int64_t)m * d + n) = o;
     }
   }
+}
+
+// A projection with residual whose result feeds an RMSNorm, with the norm's row factor left to the next projection's
+// reduction: h = sum of the partials + R (fp32 residual stream), a = bf16(h * g) (what that projection reads), and
+// ssq[m][c] = sum of h^2 over columns 1024c .. 1024c+1023 (one workgroup per row and 1024 columns; the partial sums
+// of a row are added in index order by row_scale).  N a multiple of 1024.
+__global__ void __launch_bounds__(256) splitk_reduce_prescale_kernel(const float* __restrict__ P, float* __restrict__ h,
+                                                                     const void* __restrict__ R, int r_f32,
+                                                                     const bf16_t* __restrict__ g, bf16_t* __restrict__ a,
+                                                                     float* __restrict__ ssq, int M, int N, int splits) {
+  __shared__ float part[4];
+  const int n_parts = N / 1024;
+  const int m = blockIdx.x / n_parts, c = blockIdx.x % n_parts;
+  const int n = c * 1024 + threadIdx.x * 4;
+  f32x4 v = *(const f32x4*)(P + (int64_t)m * N + n);
+  for (int k = 1; k < splits; ++k) {
+    const f32x4 b = *(const f32x4*)(P + ((int64_t)k * M + m) * N + n);
+    v[0] += b[0]; v[1] += b[1]; v[2] += b[2]; v[3] += b[3];
+  }
+  if (r_f32) {
+    v += *(const f32x4*)((const float*)R + (int64_t)m * N + n);
+  } else {
+    const bf16x4 rb = *(const bf16x4*)((const bf16_t*)R + (int64_t)m * N + n);
+    v[0] += (float)rb[0]; v[1] += (float)rb[1]; v[2] += (float)rb[2]; v[3] += (float)rb[3];
+  }
+  *(f32x4*)(h + (int64_t)m * N + n) = v;
+  const bf16x4 gg = *(const bf16x4*)(g + n);
+  bf16x4 o;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) o[e] = (bf16_t)(v[e] * (float)gg[e]);
+  *(bf16x4*)(a + (int64_t)m * N + n) = o;
+  float ss = v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) ss += __shfl_xor(ss, off, 64);
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  if (threadIdx.x == 0) ssq[m * n_parts + c] = (part[0] + part[1]) + (part[2] + part[3]);
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool PARTIAL, int SCHED = 0>
@@ -963,7 +1019,7 @@ hipError_t launch_gemm_mfma_bf16(const void* A, int64_t lda, const void* W, int6
       if (e != hipSuccess) return e;
       const int64_t quads = (int64_t)M * (N / 8);
       hipLaunchKernelGGL(splitk_reduce_swiglu_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s,
-                         (const float*)ws, (bf16_t*)C, ldc, M, N, splits);
+                         (const float*)ws, (bf16_t*)C, ldc, M, N, splits, (const float*)nullptr, 0, 0.f, 0.f);
       return hipGetLastError();
     }
     if ((int64_t)((M + 255) / 256) * ((N + 255) / 256) >= 192 || variant == 1)
@@ -1063,17 +1119,53 @@ bool gemm_small_m_rmsnorm_supported(int M, int d, int K, int64_t lda, int64_t ld
 }
 
 // qkv projection + RoPE + KV-cache write: N = (Hq + 2 Hkv) dh
+// ssq (optional): the rows of A are x*g of an RMSNorm over K columns without its row factor, ssq [M, K/1024] holds
+// the partial sums of x^2 (splitk_reduce_prescale_kernel), and the factor is applied to the sums here
 hipError_t launch_gemm_small_m_rope(const void* A, int64_t lda, const void* W, int64_t ldw, void* qkv, int64_t ldq,
                                     const float2* cs, void* k_rows, void* v_rows, int M, int K, int Hq, int Hkv, int dh,
-                                    void* ws, int64_t ws_bytes, hipStream_t s) {
+                                    void* ws, int64_t ws_bytes, const float* ssq, float eps, hipStream_t s) {
   const int N = (Hq + 2 * Hkv) * dh;
   if (!ws || !gemm_small_m_rope_supported(M, K, Hq, Hkv, dh, lda, ldw, ldq, ws_bytes)) return hipErrorNotSupported;
+  if (ssq && K % 1024) return hipErrorNotSupported;
   int splits = 0;
   hipError_t e = small_m_partials(A, lda, W, ldw, M, N, K, ws, ws_bytes, &splits, s);
   if (e != hipSuccess) return e;
   const int64_t units = (int64_t)M * ((Hq + Hkv) * (dh / 8) + Hkv * dh / 4);
   hipLaunchKernelGGL(splitk_reduce_rope_kernel, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, s, (const float*)ws,
-                     (bf16_t*)qkv, ldq, cs, (bf16_t*)k_rows, (bf16_t*)v_rows, M, N, splits, Hq, Hkv, dh);
+                     (bf16_t*)qkv, ldq, cs, (bf16_t*)k_rows, (bf16_t*)v_rows, M, N, splits, Hq, Hkv, dh, ssq, K / 1024,
+                     1.0f / (float)K, eps);
+  return hipGetLastError();
+}
+
+// gate/up projection + SwiGLU over few rows whose input lacks the RMSNorm row factor (see above): act [M, N/2]
+hipError_t launch_gemm_small_m_swiglu_scaled(const void* A, int64_t lda, const void* W, int64_t ldw, void* act, int64_t ldc,
+                                             int M, int N, int K, void* ws, int64_t ws_bytes, const float* ssq, float eps,
+                                             hipStream_t s) {
+  if (!ws || !ssq || K % 1024 || N % 64 || !gemm_small_m_fused_supported(M, N, K, lda, ldw, ws_bytes)) return hipErrorNotSupported;
+  int splits = 0;
+  hipError_t e = small_m_partials(A, lda, W, ldw, M, N, K, ws, ws_bytes, &splits, s);
+  if (e != hipSuccess) return e;
+  const int64_t quads = (int64_t)M * (N / 8);
+  hipLaunchKernelGGL(splitk_reduce_swiglu_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s, (const float*)ws,
+                     (bf16_t*)act, ldc, M, N, splits, ssq, K / 1024, 1.0f / (float)K, eps);
+  return hipGetLastError();
+}
+
+// projection + residual, result prepared for an RMSNorm whose row factor the next projection applies:
+// h [M, d] fp32 = x W^T + R, a [M, d] bf16 = h * g, ssq [M, d/1024] partial sums of h^2; d a multiple of 1024
+bool gemm_small_m_prescale_supported(int M, int d, int K, int64_t lda, int64_t ldw, int64_t ws_bytes) {
+  return d % 1024 == 0 && d / 1024 <= DSK_MAX_SSQ_PARTS && gemm_small_m_fused_supported(M, d, K, lda, ldw, ws_bytes);
+}
+
+hipError_t launch_gemm_small_m_prescale(const void* A, int64_t lda, const void* W, int64_t ldw, float* h, const void* R,
+                                        int r_f32, const void* g, void* a, float* ssq, int M, int d, int K, void* ws,
+                                        int64_t ws_bytes, hipStream_t s) {
+  if (!ws || !gemm_small_m_prescale_supported(M, d, K, lda, ldw, ws_bytes)) return hipErrorNotSupported;
+  int splits = 0;
+  hipError_t e = small_m_partials(A, lda, W, ldw, M, d, K, ws, ws_bytes, &splits, s);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(splitk_reduce_prescale_kernel, dim3((unsigned)(M * (d / 1024))), dim3(256), 0, s, (const float*)ws, h, R,
+                     r_f32, (const bf16_t*)g, (bf16_t*)a, ssq, M, d, splits);
   return hipGetLastError();
 }
 
