@@ -461,6 +461,41 @@ __global__ void __launch_bounds__(64) attn_combine_kernel(const float* __restric
   for (int a = 0; a < DH / 64; ++a) out[qh * DH + threadIdx.x + 64 * a] = (bf16_t)(acc[a] * inv);
 }
 
+// The same for at most MAXS splits, with every partial result requested before the first is used: the merge is a
+// chain of small dependent steps, and what it takes is the round trips to memory, not the arithmetic.  Same sums in
+// the same order as above.
+template <int DH, int MAXS>
+__global__ void __launch_bounds__(64) attn_combine_batched_kernel(const float* __restrict__ part_o,
+                                                                  const float* __restrict__ part_ml, bf16_t* __restrict__ out,
+                                                                  int Hq, int splits, float c) {
+  const int64_t qh = (int64_t)blockIdx.x * Hq + blockIdx.y;
+  const float* ml = part_ml + qh * splits * 2;
+  float ms[MAXS], ls[MAXS], po[MAXS][DH / 64];
+#pragma unroll
+  for (int s = 0; s < MAXS; ++s) {
+    const bool on = s < splits;
+    ms[s] = on ? ml[2 * s] : -INFINITY;
+    ls[s] = on ? ml[2 * s + 1] : 0.f;
+#pragma unroll
+    for (int a = 0; a < DH / 64; ++a) po[s][a] = on ? part_o[(qh * splits + s) * DH + threadIdx.x + 64 * a] : 0.f;
+  }
+  float M = -INFINITY;
+#pragma unroll
+  for (int s = 0; s < MAXS; ++s) M = fmaxf(M, ms[s]);
+  float den = 0.f, acc[DH / 64] = {};
+#pragma unroll
+  for (int s = 0; s < MAXS; ++s) {
+    if (ms[s] == -INFINITY) continue;  // not a split, or one that saw no visible key
+    const float w = __builtin_amdgcn_exp2f((ms[s] - M) * c);
+    den += ls[s] * w;
+#pragma unroll
+    for (int a = 0; a < DH / 64; ++a) acc[a] += po[s][a] * w;
+  }
+  const float inv = 1.0f / den;
+#pragma unroll
+  for (int a = 0; a < DH / 64; ++a) out[qh * DH + threadIdx.x + 64 * a] = (bf16_t)(acc[a] * inv);
+}
+
 // Vt[(kvh*dh + d)*ldvt + row] = V[row][kvh*dh + d] for the valid rows, 0 for the others, over whole
 // 64-row tiles.  valid(row) = row < n_pre || own_row0 <= row < own_row0 + n_own.
 __global__ void __launch_bounds__(256) transpose_v_kernel(const bf16_t* __restrict__ v_rows, bf16_t* __restrict__ vt,
@@ -604,8 +639,14 @@ hipError_t launch_attn_mfma_bf16(const AttnArgs& a, hipStream_t s) {
                         : a.dh == 128 ? launch_attn<128, true, 4>(p, grid, s) : launch_attn<64, true, 4>(p, grid, s);
     if (e != hipSuccess) return e;
     dim3 cgrid(a.n_q, a.Hq);
-    if (a.dh == 128)
+    if (a.dh == 128 && splits <= 16)
+      hipLaunchKernelGGL((attn_combine_batched_kernel<128, 16>), cgrid, dim3(64), 0, s, p.part_o, p.part_ml, p.out, a.Hq, splits, p.c);
+    else if (a.dh == 128 && splits <= 32)
+      hipLaunchKernelGGL((attn_combine_batched_kernel<128, 32>), cgrid, dim3(64), 0, s, p.part_o, p.part_ml, p.out, a.Hq, splits, p.c);
+    else if (a.dh == 128)
       hipLaunchKernelGGL(attn_combine_kernel<128>, cgrid, dim3(64), 0, s, p.part_o, p.part_ml, p.out, a.Hq, splits, p.c);
+    else if (splits <= 32)
+      hipLaunchKernelGGL((attn_combine_batched_kernel<64, 32>), cgrid, dim3(64), 0, s, p.part_o, p.part_ml, p.out, a.Hq, splits, p.c);
     else
       hipLaunchKernelGGL(attn_combine_kernel<64>, cgrid, dim3(64), 0, s, p.part_o, p.part_ml, p.out, a.Hq, splits, p.c);
     return hipGetLastError();
