@@ -683,6 +683,66 @@ __global__ void __launch_bounds__(WAVES_M* WAVES_N * 64)
   }
 }
 
+// Sum over the K splits of the quads at P + k * stride, k = 0 .. splits-1, added in split order.  The reductions are
+// short chains of dependent steps on little data: what they take is round trips to memory, so the loads of four
+// splits (of two columns at once in the second form) are requested together.
+__device__ __forceinline__ f32x4 sum_splits(const float* __restrict__ p, int64_t stride, int splits) {
+  f32x4 a = *(const f32x4*)p;
+  int k = 1;
+  for (; k + 3 < splits; k += 4) {
+    f32x4 b[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) b[u] = *(const f32x4*)(p + (k + u) * stride);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) a += b[u];
+  }
+  {  // the last one to three splits, requested together as well
+    f32x4 b[3];
+#pragma unroll
+    for (int u = 0; u < 3; ++u)
+      if (k + u < splits) b[u] = *(const f32x4*)(p + (k + u) * stride);
+#pragma unroll
+    for (int u = 0; u < 3; ++u)
+      if (k + u < splits) a += b[u];
+  }
+  return a;
+}
+__device__ __forceinline__ void sum_splits2(const float* __restrict__ p, const float* __restrict__ q, int64_t stride,
+                                            int splits, f32x4* a_out, f32x4* c_out) {
+  f32x4 a = *(const f32x4*)p, c = *(const f32x4*)q;
+  int k = 1;
+  for (; k + 3 < splits; k += 4) {
+    f32x4 b[4], d[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      b[u] = *(const f32x4*)(p + (k + u) * stride);
+      d[u] = *(const f32x4*)(q + (k + u) * stride);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      a += b[u];
+      c += d[u];
+    }
+  }
+  {
+    f32x4 b[3], d[3];
+#pragma unroll
+    for (int u = 0; u < 3; ++u)
+      if (k + u < splits) {
+        b[u] = *(const f32x4*)(p + (k + u) * stride);
+        d[u] = *(const f32x4*)(q + (k + u) * stride);
+      }
+#pragma unroll
+    for (int u = 0; u < 3; ++u)
+      if (k + u < splits) {
+        a += b[u];
+        c += d[u];
+      }
+  }
+  *a_out = a;
+  *c_out = c;
+}
+
 // C[m][n] = bf16( sum_s P[s][m][n] (+ R[m][n]) ), the partials added in split order.
 __global__ void __launch_bounds__(256) splitk_reduce_kernel(const float* __restrict__ P, void* __restrict__ C, int64_t ldc,
                                                             const void* __restrict__ R, int64_t ldr, int M, int N,
@@ -691,11 +751,7 @@ __global__ void __launch_bounds__(256) splitk_reduce_kernel(const float* __restr
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= quads) return;
   const int m = (int)(i / (N / 4)), n = (int)(i - (int64_t)m * (N / 4)) * 4;
-  f32x4 s = *(const f32x4*)(P + (int64_t)m * N + n);
-  for (int k = 1; k < splits; ++k) {
-    f32x4 v = *(const f32x4*)(P + ((int64_t)k * M + m) * N + n);
-    s[0] += v[0]; s[1] += v[1]; s[2] += v[2]; s[3] += v[3];
-  }
+  const f32x4 s = sum_splits(P + (int64_t)m * N + n, (int64_t)M * N, splits);
   store_quad(C, ldc, R, ldr, m, n, s, epi);
 }
 
@@ -720,14 +776,8 @@ __global__ void __launch_bounds__(256) splitk_reduce_swiglu_kernel(const float* 
   if (i >= quads) return;
   const int m = (int)(i / (F / 4)), f = (int)(i - (int64_t)m * (F / 4)) * 4;
   const int pg = (f / 32) * 64 + f % 32;
-  f32x4 g = *(const f32x4*)(P + (int64_t)m * N + pg);
-  f32x4 u = *(const f32x4*)(P + (int64_t)m * N + pg + 32);
-  for (int k = 1; k < splits; ++k) {
-    const float* row = P + ((int64_t)k * M + m) * N + pg;
-    const f32x4 g2 = *(const f32x4*)row, u2 = *(const f32x4*)(row + 32);
-    g[0] += g2[0]; g[1] += g2[1]; g[2] += g2[2]; g[3] += g2[3];
-    u[0] += u2[0]; u[1] += u2[1]; u[2] += u2[2]; u[3] += u2[3];
-  }
+  f32x4 g, u;
+  sum_splits2(P + (int64_t)m * N + pg, P + (int64_t)m * N + pg + 32, (int64_t)M * N, splits, &g, &u);
   if (ssq) {
     const float rs = row_scale(ssq, m, n_parts, inv_d, eps);
     g *= rs;
@@ -758,15 +808,8 @@ __global__ void __launch_bounds__(256) splitk_reduce_rope_kernel(const float* __
   const int m = (int)(i / (rot_units + v_units)), u = (int)(i - (int64_t)m * (rot_units + v_units));
   const int kvw = Hkv * dh;
   const float rs = ssq ? row_scale(ssq, m, n_parts, inv_d, eps) : 1.0f;
-  auto sum4 = [&](int col) {
-    f32x4 a = *(const f32x4*)(P + (int64_t)m * N + col);
-    for (int k = 1; k < splits; ++k) {
-      const f32x4 b = *(const f32x4*)(P + ((int64_t)k * M + m) * N + col);
-      a[0] += b[0]; a[1] += b[1]; a[2] += b[2]; a[3] += b[3];
-    }
-    if (ssq) a *= rs;
-    return a;
-  };
+  const float* row = P + (int64_t)m * N;
+  const int64_t stride = (int64_t)M * N;
   auto to_bf16 = [](f32x4 v) {
     bf16x4 o;
     o[0] = (bf16_t)v[0]; o[1] = (bf16_t)v[1]; o[2] = (bf16_t)v[2]; o[3] = (bf16_t)v[3];
@@ -774,7 +817,10 @@ __global__ void __launch_bounds__(256) splitk_reduce_rope_kernel(const float* __
   };
   if (u < rot_units) {
     const int head = u / (half / 4), i0 = (u % (half / 4)) * 4;
-    const f32x4 x1 = sum4(head * dh + i0), x2 = sum4(head * dh + i0 + half);
+    f32x4 x1, x2;
+    sum_splits2(row + head * dh + i0, row + head * dh + i0 + half, stride, splits, &x1, &x2);
+    x1 *= rs;  // 1 when the input rows carried their RMSNorm factor already
+    x2 *= rs;
     f32x4 y1, y2;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
@@ -787,7 +833,7 @@ __global__ void __launch_bounds__(256) splitk_reduce_rope_kernel(const float* __
     *(bf16x4*)(dst + half) = to_bf16(y2);
   } else {
     const int j = (u - rot_units) * 4;
-    *(bf16x4*)(v_rows + (int64_t)m * kvw + j) = to_bf16(sum4((Hq + Hkv) * dh + j));
+    *(bf16x4*)(v_rows + (int64_t)m * kvw + j) = to_bf16(sum_splits(row + (Hq + Hkv) * dh + j, stride, splits) * rs);
   }
 }
 
@@ -881,11 +927,7 @@ __global__ void __launch_bounds__(256) splitk_reduce_prescale_kernel(const float
   const int n_parts = N / 1024;
   const int m = blockIdx.x / n_parts, c = blockIdx.x % n_parts;
   const int n = c * 1024 + threadIdx.x * 4;
-  f32x4 v = *(const f32x4*)(P + (int64_t)m * N + n);
-  for (int k = 1; k < splits; ++k) {
-    const f32x4 b = *(const f32x4*)(P + ((int64_t)k * M + m) * N + n);
-    v[0] += b[0]; v[1] += b[1]; v[2] += b[2]; v[3] += b[3];
-  }
+  f32x4 v = sum_splits(P + (int64_t)m * N + n, (int64_t)M * N, splits);
   if (r_f32) {
     v += *(const f32x4*)((const float*)R + (int64_t)m * N + n);
   } else {
