@@ -338,8 +338,9 @@ DSK_API int dsk_moe_route(int dtype, const void* x, const void* wr, int n, int d
  *                unchunked run (one sequence, bf16, chunks that still fill the chip), -1 = never, n > 0 (a multiple
  *                of 256) = n-row chunks on any single-sequence bf16 call (results then agree within tolerance only)
  *   "time_gemm": 1 = bracket every tensor-core GEMM launch that runs on the 256 x 256 prefill tiling (at least
- *                192 such tiles), and every tensor-core attention launch of the prefix pass (at least 1024 query rows, no earlier rows), by a pair
- *                of HIP events on its stream (read back through dsk_get_stat)
+ *                192 such tiles), and every tensor-core attention launch of the prefix pass (at least 1024 query rows, no
+ *                earlier rows), by a pair of HIP events attached to the kernel's own dispatch (they receive its start and
+ *                stop times, nothing else is put into the stream; read back through dsk_get_stat)
  *   "reset_stats": any value; clears all counters and recorded timings */
 DSK_API int dsk_set_option(const char* name, int value);
 

@@ -568,7 +568,7 @@ hipError_t launch_attn(const AttnParams& p, dim3 grid, hipStream_t s) {
     if (e != hipSuccess) return e;
     configured = true;
   }
-  hipLaunchKernelGGL(kern, grid, dim3(64 * NW), lds, s, p);
+  DSK_LAUNCH_TIMED(kern, grid, dim3(64 * NW), lds, s, p);
   return hipGetLastError();
 }
 

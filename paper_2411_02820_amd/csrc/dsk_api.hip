@@ -14,6 +14,7 @@
 // hipGetSymbolAddress; kernels and copies get the per-device address that call returns.
 static __device__ __align__(256) unsigned char scratch[DSK_STATIC_SCRATCH_BYTES];
 
+thread_local hipEvent_t g_launch_ev_start = nullptr, g_launch_ev_stop = nullptr;
 thread_local int g_last_hip_error = 0;  // shared with the cache store
 
 namespace {
@@ -111,26 +112,47 @@ struct TimedList {
   hipEvent_t* ev = nullptr;  // 2*kMax events, created on first use
   int n = 0;
   double flops = 0.0;
-  // records the start event of the next launch; false when the list is full
-  hipError_t begin(hipStream_t s, bool* on) {
+  // hands the event pair of the next launch to the launcher (which attaches them to the kernel's dispatch); false
+  // when the list is full
+  // creates the events (when the hook is switched on: creating thousands of events takes milliseconds, which must not
+  // fall into a timed region)
+  hipError_t prepare() {
+    if (ev) return hipSuccess;
+    hipEvent_t* fresh = (hipEvent_t*)calloc(2 * kMax, sizeof(hipEvent_t));
+    if (!fresh) return hipErrorOutOfMemory;
+    for (int i = 0; i < 2 * kMax; ++i) {
+      hipError_t e = hipEventCreate(&fresh[i]);
+      if (e != hipSuccess) {
+        for (int j = 0; j < i; ++j) (void)hipEventDestroy(fresh[j]);
+        free(fresh);
+        return e;
+      }
+    }
+    ev = fresh;
+    return hipSuccess;
+  }
+  hipError_t begin(hipStream_t, bool* on) {
     *on = false;
     if (n >= kMax) return hipSuccess;
     if (!ev) {
-      ev = (hipEvent_t*)calloc(2 * kMax, sizeof(hipEvent_t));
-      if (!ev) return hipErrorOutOfMemory;
-      for (int i = 0; i < 2 * kMax; ++i) {
-        hipError_t e = hipEventCreate(&ev[i]);
-        if (e != hipSuccess) return e;
-      }
+      hipError_t e = prepare();
+      if (e != hipSuccess) return e;
     }
     *on = true;
-    return hipEventRecord(ev[2 * n], s);
+    g_launch_ev_start = ev[2 * n];
+    g_launch_ev_stop = ev[2 * n + 1];
+    return hipSuccess;
   }
-  hipError_t end(hipStream_t s, double launch_flops) {
-    hipError_t e = hipEventRecord(ev[2 * n + 1], s);
+  // the launch failed before any kernel was enqueued: the pair goes back
+  void abandon() { g_launch_ev_start = g_launch_ev_stop = nullptr; }
+  hipError_t end(hipStream_t, double launch_flops) {
+    if (g_launch_ev_start) {  // no launcher took the pair (a kernel other than the timed ones ran): not counted
+      g_launch_ev_start = g_launch_ev_stop = nullptr;
+      return hipSuccess;
+    }
     flops += launch_flops;
     ++n;
-    return e;
+    return hipSuccess;
   }
   int total_ms(double* ms_out) {
     double total = 0.0;
@@ -168,6 +190,8 @@ hipError_t gemm_any(int dtype, const void* A, int64_t lda, const void* W, int64_
     if (e == hipSuccess) {
       ++g_stats.gemm_mfma;
       if (timed) e = g_stats.gemm.end(s, 2.0 * M * N * K);
+    } else if (timed) {
+      g_stats.gemm.abandon();
     }
     return e;
   }
@@ -202,6 +226,8 @@ hipError_t attention_any(int dtype, const AttnArgs& a, hipStream_t s) {
         }
         e = g_stats.attn.end(s, 4.0 * a.Hq * a.dh * pairs);
       }
+    } else if (timed) {
+      g_stats.attn.abandon();
     }
     return e;
   }
@@ -237,7 +263,10 @@ int run_moe_mlp(dsk_model* m, const LayerWeights& w, int n, const float* h_mid, 
         timed_lock.lock();
         HIP_TRY(g_stats.gemm.begin(s, &timed));
       }
-      HIP_TRY(launch_gemm_mfma_grouped(A, lda, (int64_t)n * k, W, ldw, w_stride, C, ldc, N, K, epi, m->moe_tab, tile_rows, s));
+      const hipError_t e = launch_gemm_mfma_grouped(A, lda, (int64_t)n * k, W, ldw, w_stride, C, ldc, N, K, epi, m->moe_tab,
+                                                    tile_rows, s);
+      if (e != hipSuccess && timed) g_stats.gemm.abandon();
+      HIP_TRY(e);
       ++g_stats.gemm_mfma;
       if (timed) HIP_TRY(g_stats.gemm.end(s, 2.0 * n * k * N * K));
       return DSK_OK;
@@ -1008,7 +1037,14 @@ int dsk_set_option(const char* name, int value) {
     if (value < -1 || (value > 0 && value % 256)) return DSK_EINVAL;
     g_e_chunk_rows = value;
   } else if (!strcmp(name, "force_generic")) g_force_generic = value;
-  else if (!strcmp(name, "time_gemm")) g_time_gemm = value;
+  else if (!strcmp(name, "time_gemm")) {
+    if (value) {
+      std::lock_guard<std::mutex> lock(g_stats.timed_mu);
+      HIP_TRY(g_stats.gemm.prepare());
+      HIP_TRY(g_stats.attn.prepare());
+    }
+    g_time_gemm = value;
+  }
   else if (!strcmp(name, "reset_stats")) {
     g_stats.gemm_mfma = 0; g_stats.gemm_generic = 0; g_stats.attn_mfma = 0; g_stats.attn_generic = 0; g_stats.e_chunks = 0;
     std::lock_guard<std::mutex> timed_lock(g_stats.timed_mu);

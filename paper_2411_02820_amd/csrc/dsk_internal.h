@@ -1,6 +1,7 @@
 // Internal declarations shared by the HIP sources of libdsk (gfx950 only).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "dsk.h"
@@ -125,6 +126,19 @@ hipError_t launch_gemm_small_m_rmsnorm(const void* A, int64_t lda, const void* W
 // x is fp32 when x_f32 is set, else the model dtype; g and y are the model dtype
 hipError_t launch_rmsnorm(int dtype, const void* x, int x_f32, const void* g, void* y, int T, int d, float eps, hipStream_t s);
 extern thread_local int g_last_hip_error;  // hipError_t of the last failed HIP call on this thread
+// Timing of single launches (the "time_gemm" hook): when set, the next tensor-core GEMM or attention launch on this
+// thread attaches the two events to its own dispatch (they receive the kernel's start and stop times; no extra
+// packets go into the stream) and clears the pair.
+extern thread_local hipEvent_t g_launch_ev_start, g_launch_ev_stop;
+#define DSK_LAUNCH_TIMED(kern, grid, block, lds, stream, ...)                                                        \
+  do {                                                                                                               \
+    if (g_launch_ev_start) {                                                                                         \
+      hipExtLaunchKernelGGL(kern, grid, block, lds, stream, g_launch_ev_start, g_launch_ev_stop, 0, __VA_ARGS__);    \
+      g_launch_ev_start = g_launch_ev_stop = nullptr;                                                                \
+    } else {                                                                                                         \
+      hipLaunchKernelGGL(kern, grid, block, lds, stream, __VA_ARGS__);                                               \
+    }                                                                                                                \
+  } while (0)
 
 // pacing of the load stream against the 100 MHz constant-rate clock
 hipError_t launch_pace_start(unsigned long long* t0, hipStream_t s);

@@ -960,8 +960,8 @@ hipError_t launch(const void* A, int64_t lda, const void* W, int64_t ldw, void* 
     configured = true;
   }
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n, splits), dim3(WAVES_M * WAVES_N * 64), lds, s, (const bf16_t*)A, lda,
-                     (const bf16_t*)W, ldw, C, ldc, R, ldr, P, M, N, K, epi, tiles_m, tiles_n, kt_per_split);
+  DSK_LAUNCH_TIMED(kern, dim3(tiles_m * tiles_n, splits), dim3(WAVES_M * WAVES_N * 64), lds, s, (const bf16_t*)A, lda,
+                   (const bf16_t*)W, ldw, C, ldc, R, ldr, P, M, N, K, epi, tiles_m, tiles_n, kt_per_split);
   return hipGetLastError();
 }
 
@@ -977,8 +977,8 @@ hipError_t launch16(const void* A, int64_t lda, const void* W, int64_t ldw, void
     configured = true;
   }
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(WAVES_M * WAVES_N * 64), lds, s, (const bf16_t*)A, lda,
-                     (const bf16_t*)W, ldw, C, ldc, R, ldr, M, N, K, epi, tiles_m, tiles_n, (const int4*)nullptr, (int64_t)0);
+  DSK_LAUNCH_TIMED(kern, dim3(tiles_m * tiles_n), dim3(WAVES_M * WAVES_N * 64), lds, s, (const bf16_t*)A, lda,
+                   (const bf16_t*)W, ldw, C, ldc, R, ldr, M, N, K, epi, tiles_m, tiles_n, (const int4*)nullptr, (int64_t)0);
   return hipGetLastError();
 }
 
@@ -994,9 +994,9 @@ hipError_t launch16_grouped(const void* A, int64_t lda, const void* W, int64_t l
     configured = true;
   }
   const int tiles_n = (N + BN - 1) / BN;
-  hipLaunchKernelGGL(kern, dim3(tile_rows * tiles_n), dim3(WAVES_M * WAVES_N * 64), lds, s, (const bf16_t*)A, lda,
-                     (const bf16_t*)W, ldw, C, ldc, (const void*)nullptr, (int64_t)0, 0, N, K, epi, tile_rows, tiles_n,
-                     tile_tab, w_group_stride);
+  DSK_LAUNCH_TIMED(kern, dim3(tile_rows * tiles_n), dim3(WAVES_M * WAVES_N * 64), lds, s, (const bf16_t*)A, lda,
+                   (const bf16_t*)W, ldw, C, ldc, (const void*)nullptr, (int64_t)0, 0, N, K, epi, tile_rows, tiles_n,
+                   tile_tab, w_group_stride);
   return hipGetLastError();
 }
 
