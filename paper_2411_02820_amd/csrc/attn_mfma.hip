@@ -360,11 +360,15 @@ __global__ void __launch_bounds__(64 * NW, 8 / NW) attn_bf16_kernel(AttnParams p
 #pragma unroll
     for (int r = 0; r < 16; ++r) s_a[kt][r] = s_b[kt][r] = 0.f;
   if (it_begin < it_end) {
+    // the first two K tiles and the first Vt tile are requested together, behind the Q fragments, and waited for
+    // once: one round trip to memory at the start of a workgroup instead of two (the wait is for everything: the
+    // compiler's own count for the Q fragments cannot see the direct-to-LDS loads, so a partial wait would be turned
+    // into a full one in front of the first use of Q anyway)
     issue_k(it_begin);
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): as a builtin the compiler accounts for it
-    __syncthreads();
     if (it_begin + 1 < it_end) issue_k(it_begin + 1);
     issue_v(it_begin);
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): as a builtin the compiler accounts for it
+    __syncthreads();
     if (it_begin < act_end) {
 #pragma unroll
       for (int kt = 0; kt < 2; ++kt)
