@@ -360,6 +360,8 @@ __global__ void __launch_bounds__(64 * NW, 8 / NW) attn_bf16_kernel(AttnParams p
 #pragma unroll
     for (int r = 0; r < 16; ++r) s_a[kt][r] = s_b[kt][r] = 0.f;
   if (it_begin < it_end) {
+    // (A four-stage ring for the packed few-query launch, where a workgroup has a compute unit to itself and next to
+    // no arithmetic per tile, was measured: 23.8 us per launch against 21.2 us with two stages; not kept.)
     // the first two K tiles and the first Vt tile are requested together, behind the Q fragments, and waited for
     // once: one round trip to memory at the start of a workgroup instead of two (the wait is for everything: the
     // compiler's own count for the Q fragments cannot see the direct-to-LDS loads, so a partial wait would be turned
