@@ -403,6 +403,33 @@ def test_suffix_pass_at_model_width_against_oracle(G, B, name, width, S):
         assert max(errs.values()) <= TOL, errs
 
 
+def test_8b_width_prefix_of_few_tokens(G, B):
+    # A prefix of at most 64 tokens at the 8B layer width takes the few-row projections inside the selective prefill as
+    # well (K-split tiles, RoPE / SwiGLU in the reductions, the post-attention RMSNorm split around the gate/up
+    # projection): two layers over 48 tokens of two sequences against the oracle.
+    base = synth.LLAMA_8B
+    shape = synth.ModelShape(2, base.hidden, base.n_q_heads, base.n_kv_heads, base.head_dim, base.ffn, base.rope_base,
+                             base.rms_eps, "bf16")
+    cfg = oracle_config(shape)
+    lens = [31, 17]
+    T = sum(lens)
+    hidden_host = synth.hidden_states(shape, T)
+    with G.GpuModel(shape, T) as m:
+        m.init_random(synth.SEED_RECEIVER)
+        B.dsk_set_option("reset_stats", 0)
+        kv_out, h_out = m.partial(G.to_dev(hidden_host, shape), 0, 2, None, lens)
+        torch.cuda.synchronize()
+        assert B.dsk_get_stat("gemm_generic_launches") == 0 and B.dsk_get_stat("gemm_mfma_launches") == 8
+        kv_ref, h_ref = O.partial_prefill(cfg, lambda l: host_layer(shape, synth.SEED_RECEIVER, l), hidden_host.astype(np.float64),
+                                          0, 2, [(None, None)] * 2, synth.packed_positions(lens), synth.cu_seqlens(lens))
+        errs = {"hidden": O.max_rel_err(G.to_np(h_out), h_ref)}
+        for l in range(2):
+            errs[f"K{l}"] = O.max_rel_err(G.to_np(kv_out[l, 0, :T]), kv_ref[l][0])
+            errs[f"V{l}"] = O.max_rel_err(G.to_np(kv_out[l, 1, :T]), kv_ref[l][1])
+        print("48 tokens at 8B width: max-rel-err:", {k: f"{v:.2e}" for k, v in errs.items()})
+        assert max(errs.values()) <= TOL, errs
+
+
 def test_config4_8b_prefix16384_kv_in_pinned_host_memory(G, B):
     # reused KV (2 GiB, bf16) and the E cache live in pinned host memory; loads are pipelined under layers [4,12)
     shape, T, lo, hi, S = synth.LLAMA_8B, 16384, 4, 12, 64
