@@ -28,13 +28,42 @@ __global__ void __launch_bounds__(256) moe_route_kernel(const T* __restrict__ xn
 #pragma unroll
   for (int j = 0; j < MAX_K; ++j) { best_v[j] = -INFINITY; best_e[j] = -1; }
   const T* x = xn + (int64_t)t * d;
+  // the token's row is read once and kept in registers (widths up to 512 * XCH; wider rows are re-read per expert)
+  constexpr int XCH = 8;
+  const bool in_regs = d <= 512 * XCH;
+  vec8 xr[XCH];
+  if (in_regs) {
+#pragma unroll
+    for (int i = 0; i < XCH; ++i) {
+      const int c = lane * 8 + 512 * i;
+      if (c < d) xr[i] = *(const vec8*)(x + c);
+    }
+  }
   for (int e = 0; e < E; ++e) {
     const T* w = wr + (int64_t)e * d;
     float acc = 0.f;
-    for (int c = lane * 8; c < d; c += 512) {
-      const vec8 a = *(const vec8*)(x + c), b = *(const vec8*)(w + c);
+    if (in_regs) {
+      // same products in the same order as the loop below
+      vec8 wv[XCH];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) acc = fmaf(to_f32(a[u]), to_f32(b[u]), acc);
+      for (int i = 0; i < XCH; ++i) {
+        const int c = lane * 8 + 512 * i;
+        if (c < d) wv[i] = *(const vec8*)(w + c);
+      }
+#pragma unroll
+      for (int i = 0; i < XCH; ++i) {
+        const int c = lane * 8 + 512 * i;
+        if (c < d) {
+#pragma unroll
+          for (int u = 0; u < 8; ++u) acc = fmaf(to_f32(xr[i][u]), to_f32(wv[i][u]), acc);
+        }
+      }
+    } else {
+      for (int c = lane * 8; c < d; c += 512) {
+        const vec8 a = *(const vec8*)(x + c), b = *(const vec8*)(w + c);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc = fmaf(to_f32(a[u]), to_f32(b[u]), acc);
+      }
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
@@ -80,13 +109,17 @@ __global__ void __launch_bounds__(256) moe_place_kernel(const int32_t* __restric
                                                         int32_t* __restrict__ src_token, int4* __restrict__ tile_tab,
                                                         int n_entries, int top_k, int E, int tile_m, int tile_rows_max) {
   __shared__ int hist[DSK_MOE_MAX_EXPERTS];
-  __shared__ int wave_cnt[2][4];
+  __shared__ int wave_cnt[2][4][4];
   const int e = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   if (tid < DSK_MOE_MAX_EXPERTS) hist[tid] = 0;
   __syncthreads();
-  for (int i = tid; i < n_entries; i += 256) {
-    const int x = experts[i];
-    if ((unsigned)x < (unsigned)E) atomicAdd(&hist[x], 1);  // the router only writes experts below E
+  for (int base = tid; base < n_entries; base += 1024) {
+    int x[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) x[q] = base + 256 * q < n_entries ? experts[base + 256 * q] : -1;
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      if ((unsigned)x[q] < (unsigned)E) atomicAdd(&hist[x[q]], 1);  // the router only writes experts below E
   }
   __syncthreads();
   int first = 0, first_tile = 0;
@@ -102,28 +135,42 @@ __global__ void __launch_bounds__(256) moe_place_kernel(const int32_t* __restric
     for (int r = first_tile + my_tiles + tid; r < tile_rows_max; r += 256) tile_tab[r] = make_int4(-1, 0, 0, 0);
     if (tid == 0) tile_tab[tile_rows_max] = make_int4(min(first_tile + my_tiles, tile_rows_max), 0, 0, 0);
   }
+  // rounds of 1024 entries, four groups of 256 in entry order; a thread's four entries are requested together (the
+  // walk is a chain of short rounds: what it takes is the round trips to memory)
   int running = 0;
   int buf = 0;
-  for (int base = 0; base < n_entries; base += 256, buf ^= 1) {
-    const int i = base + tid;
-    const bool match = i < n_entries && experts[i] == e;
-    const unsigned long long mask = __ballot(match);
-    if (lane == 0) wave_cnt[buf][wave] = __popcll(mask);
-    __syncthreads();  // the other buffer is written in the next round, after every wave has passed this barrier
-    int before = __popcll(mask & ((1ull << lane) - 1ull));
-    int total = 0;
+  for (int base = 0; base < n_entries; base += 1024, buf ^= 1) {
+    int ex[4];
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      const int c = wave_cnt[buf][w];
-      if (w < wave) before += c;
-      total += c;
+    for (int q = 0; q < 4; ++q) {
+      const int i = base + 256 * q + tid;
+      ex[q] = i < n_entries ? experts[i] : -1;
     }
-    if (match) {
-      const int slot = first + running + before;
-      slot_of[i] = slot;
-      src_token[slot] = i / top_k;
+    unsigned long long mask[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      mask[q] = __ballot(ex[q] == e);
+      if (lane == 0) wave_cnt[buf][q][wave] = __popcll(mask[q]);
     }
-    running += total;
+    __syncthreads();  // the other buffer is written in the next round, after every wave has passed this barrier
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      int before = __popcll(mask[q] & ((1ull << lane) - 1ull));
+      int total = 0;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const int c = wave_cnt[buf][q][w];
+        if (w < wave) before += c;
+        total += c;
+      }
+      if (ex[q] == e) {
+        const int i = base + 256 * q + tid;
+        const int slot = first + running + before;
+        slot_of[i] = slot;
+        src_token[slot] = i / top_k;
+      }
+      running += total;
+    }
   }
 }
 
