@@ -469,3 +469,37 @@ def test_argument_errors(G):
     with pytest.raises(B.DskError) as e:
         B.dsk_model_create(B.config_from_shape(bad), 8, 8)
     assert e.value.status == B.DSK_ESHAPE
+
+
+@pytest.mark.parametrize("shape,scale", [(synth.TINY, 8.0), (SMALL_BF16, None)])
+def test_tokens_one_at_a_time_equal_the_same_tokens_at_once(G, shape, scale):
+    # Generation after the prefill, for one sequence: each new token is a suffix pass of one row against everything
+    # cached so far (the rows stay contiguous: prefix = the first T + t rows).  Fed with given embeddings, five such
+    # steps must leave the K/V rows and produce the states that one suffix pass over the five tokens gives, and both
+    # must agree with the oracle.
+    tol = TOL[shape.dtype]
+    cfg = oracle_config(shape)
+    T, S = 150, 5
+    w = scaled_weights(shape, synth.SEED_RECEIVER, scale)
+    kv_r = synth.kv_cache(shape, T)
+    xs = synth.hidden_states(shape, S, seed=synth.SEED_SUFFIX)
+    with G.GpuModel(shape, T, T + S) as m:
+        m.load_from_generator(synth.SEED_RECEIVER, scale=scale)
+        kv_once = m.new_cache(T + S, fill=float("nan"))
+        kv_once[:, :, :T] = G.to_dev(kv_r, shape)
+        kv_steps = kv_once.clone()
+        hs_once = m.suffix(G.to_dev(xs, shape), kv_once, [T], [S])
+        hs_steps = []
+        for t in range(S):
+            hs_steps.append(m.suffix(G.to_dev(xs[t:t + 1], shape), kv_steps, [T + t], [1]))
+        torch.cuda.synchronize()
+        hs_steps = torch.cat(hs_steps)
+        kv_s, hs_ref = O.suffix_prefill(cfg, w, xs.astype(np.float64), kv_list(kv_r), synth.packed_positions([S], start=[T]),
+                                        synth.cu_seqlens([T]), synth.cu_seqlens([S]))
+        for name, kv, hs in (("at once", kv_once, hs_once), ("one at a time", kv_steps, hs_steps)):
+            assert O.max_rel_err(G.to_np(hs), hs_ref) <= tol, name
+            for l in range(shape.n_layers):
+                assert O.max_rel_err(G.to_np(kv[l, 0, T:]), kv_s[l][0]) <= tol, (name, l)
+                assert O.max_rel_err(G.to_np(kv[l, 1, T:]), kv_s[l][1]) <= tol, (name, l)
+        # the two ways differ only by rounding (different kernels' tilings see the same numbers)
+        assert O.max_rel_err(G.to_np(hs_steps), G.to_np(hs_once)) <= tol
