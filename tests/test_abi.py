@@ -55,3 +55,22 @@ def test_binding_declares_the_argument_types_of_every_export():
         decl = re.search(r"\b" + name + r"\s*\(([^;]*?)\)\s*;", text, re.S).group(1)
         n_params = 0 if decl.strip() in ("", "void") else decl.count(",") + 1
         assert len(fn.argtypes) == n_params, (name, len(fn.argtypes), n_params)
+
+
+def test_header_is_valid_c_and_the_c_demo_compiles():
+    # the boundary is a C ABI: the header must compile as plain C (not only as C++), and so must the demo that uses it
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    assert gcc, "gcc is part of the toolchain this build expects"
+    inc = os.path.join(ROOT, "include")
+    for hdr in ("dsk.h", "dsk_diag.h"):
+        r = subprocess.run([gcc, "-std=c99", "-pedantic", "-Wall", "-Werror", "-fsyntax-only", "-x", "c", "-I", inc, "-"],
+                           input=f'#include "{hdr}"\nint main(void) {{ return 0; }}\n', capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
+    rocm_inc = "/opt/rocm/include"
+    if os.path.isdir(rocm_inc):
+        demo = os.path.join(ROOT, "paper_2411_02820_amd", "examples", "c_abi_demo.c")
+        r = subprocess.run([gcc, "-std=c11", "-Wall", "-fsyntax-only", "-D__HIP_PLATFORM_AMD__", "-I", rocm_inc, "-I", inc, demo],
+                           capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
