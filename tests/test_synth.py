@@ -53,3 +53,28 @@ def test_shapes_and_ratios():
     assert cu[-1] == lens.sum()
     pos = synth.packed_positions(lens)
     assert pos[cu[1]] == 0 and pos[cu[1] - 1] == lens[0] - 1
+
+
+def test_expert_tensor_streams_do_not_collide_with_layer_streams():
+    # every tensor of a model is its own generator stream: layer tensors below 2^20, expert tensors from 2^20 on
+    streams = set()
+    for layer in range(80):
+        for kind in range(10):
+            streams.add(synth.weight_stream(layer, kind))
+        for e in range(64):
+            for kind in (synth.WG, synth.WU, synth.WD):
+                streams.add(synth.expert_stream(layer, e, kind))
+    assert len(streams) == 80 * 10 + 80 * 64 * 3
+    assert max(synth.weight_stream(l, k) for l in range(80) for k in range(10)) < synth.EXPERT_STREAM0
+
+
+def test_expert_layer_weights_have_the_declared_shapes():
+    shape = synth.TINY_MOE
+    w = synth.layer_weights(shape, synth.SEED_RECEIVER, 1)
+    assert w["router"].shape == (shape.n_experts, shape.hidden) and len(w["experts"]) == shape.n_experts
+    assert "wg" not in w
+    for e in w["experts"]:
+        assert e["wg"].shape == (shape.ffn, shape.hidden) and e["wu"].shape == (shape.ffn, shape.hidden)
+        assert e["wd"].shape == (shape.hidden, shape.ffn)
+    # different experts draw different numbers
+    assert not (w["experts"][0]["wg"] == w["experts"][1]["wg"]).all()
